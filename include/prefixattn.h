@@ -1,0 +1,160 @@
+/*
+ * libprefixattn: prefix-cached "extend" prefill on one MI355X (gfx950).
+ *
+ * The paper (Preble, arXiv 2407.00023) schedules requests so that the KV of shared
+ * prompt prefixes is computed once and reused; a request then costs only the prefill
+ * of its missed tokens (Sec. 3.2, cost P of Algorithm 2).  This library is that
+ * per-GPU computation: match each prompt against the radix tree of cached sequences,
+ * run attention of the new tokens over the cached prefix KV plus themselves, and put
+ * the new KV into the cache.
+ *
+ * Conventions
+ *  - Every function returns PA_OK (0) or a negative error code and never throws or
+ *    aborts; pa_last_error() returns a description of the most recent failure on the
+ *    calling thread.
+ *  - "host" / "device" says where a pointer must live.  Device buffers are owned by
+ *    the caller (allocate them however you like, e.g. with PyTorch); the library owns
+ *    only pa_tree objects (host structure and its device mirror).
+ *  - Hot-path calls only enqueue work on `stream` (a hipStream_t passed as void*, NULL
+ *    = the default stream); they do not synchronise and do not allocate.
+ *  - All index arrays are int32.  Packed per-request arrays use an offsets array of
+ *    B + 1 entries (offsets[0] = 0).
+ *  - dtype: PA_F32 computes in fp32 throughout; PA_BF16 takes bf16 inputs, multiplies
+ *    on the bf16 matrix cores with fp32 accumulation, keeps softmax in fp32, and
+ *    writes bf16.
+ *  - Supported shapes: D in {64, 128}; Hq a multiple of Hkv; page_size >= 1 dividing
+ *    num_slots.  Tensor base pointers must be 16-byte aligned.
+ */
+#ifndef PREFIXATTN_H
+#define PREFIXATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PA_OK 0
+#define PA_EINVAL (-1) /* bad argument, shape or alignment */
+#define PA_ENOMEM (-2) /* host or device allocation failed, or workspace too small */
+#define PA_ESTATE (-3) /* tree not uploaded, or changed since the last upload */
+#define PA_EHIP (-4)   /* HIP runtime error */
+
+#define PA_F32 0
+#define PA_BF16 1
+
+typedef struct pa_tree pa_tree;
+
+/* Text of the last error raised on this thread ("" if none).  Host. */
+const char* pa_last_error(void);
+
+/* ---------------------------------------------------------------------------------
+ * Radix tree of cached token sequences (host side; not on the timed path).
+ *
+ * Sec. 3.2, "global scheduler data structures", and Sec. 3.3 (the per-GPU copy): a
+ * radix tree over token ids.  Inserting a sequence matches it from the beginning until
+ * no match exists and adds the rest as a new leaf; a node that matches only partly is
+ * split into the matched part and the remainder; a sequence matching nothing starts a
+ * new tree (here: a new child of one empty virtual root).
+ * --------------------------------------------------------------------------------- */
+
+/* Create an empty tree.  *out receives a handle owned by the library. */
+int pa_tree_create(pa_tree** out);
+
+/* Insert tokens[0..n) with the KV slot of each token (host pointers, copied).  A token
+ * position already in the tree keeps the slot of its first insertion; slots passed for
+ * such positions are ignored.  *n_already_cached (may be NULL) receives how many leading
+ * tokens were present before the call.  Marks the device mirror stale. */
+int pa_tree_insert(pa_tree* tree, const int32_t* tokens, const int32_t* slots, int32_t n,
+                   int32_t* n_already_cached);
+
+/* Flatten the tree and copy it to the current device (allocates device memory owned by
+ * the tree, frees the previous mirror).  Synchronises `stream` before returning. */
+int pa_tree_upload(pa_tree* tree, void* stream);
+
+/* Number of nodes (including the virtual root) and of stored tokens.  Either pointer may be NULL. */
+int pa_tree_stats(const pa_tree* tree, int64_t* n_nodes, int64_t* n_tokens);
+
+/* Free the tree and its device mirror.  NULL is allowed. */
+int pa_tree_destroy(pa_tree* tree);
+
+/* ---------------------------------------------------------------------------------
+ * KV pool.  num_slots rows, each holding K and V of one token for all Hkv heads.  The
+ * byte layout is private to the library: only pa_append_kv writes it and only
+ * pa_extend_attention / pa_gather_kv read it.  The caller allocates
+ * pa_kv_pool_bytes(...) bytes of device memory (16-byte aligned); contents of slots
+ * never appended are never read for a request whose slot_idx does not name them.
+ * --------------------------------------------------------------------------------- */
+size_t pa_kv_pool_bytes(int64_t num_slots, int Hkv, int D, int dtype, int page_size);
+
+/* Bytes of device workspace pa_extend_attention needs for any batch with at most B
+ * requests, T extend tokens in total and prefix_len[r] + ext_len[r] <= max_kv_len.
+ * Returns 0 for invalid arguments. */
+size_t pa_extend_workspace_bytes(int B, int64_t T, int64_t max_kv_len, int Hq, int Hkv, int D, int dtype);
+
+/* ---------------------------------------------------------------------------------
+ * The hot path.  All pointers below are DEVICE pointers unless marked otherwise.
+ * --------------------------------------------------------------------------------- */
+
+/* Longest-prefix match (Algorithm 1: "match R_k to the radix tree; cached_len = sum of
+ * matched length"; Sec. 3.3: the local scheduler matches each new request to its tree).
+ *
+ * tokens     int32 [offsets[B]]  prompts of the B requests, packed
+ * offsets    int32 [B + 1]
+ * prefix_len int32 [B]           out: number of leading prompt tokens found in the tree.
+ *                                The match is token-granular: it may end inside a tree
+ *                                node (nothing is split) and may equal the prompt length.
+ * slot_idx   int32 [offsets[B]]  out: slot_idx[offsets[r] + j] = KV slot of prompt token
+ *                                j for j < prefix_len[r]; entries past that are
+ *                                unspecified (never read by pa_extend_attention).
+ * The tree must have been uploaded after its last insert (else PA_ESTATE).  B = 0 is a
+ * no-op.  Read-only on the tree: concurrent matches on different streams are safe. */
+int pa_match_prefixes(const pa_tree* tree, const int32_t* tokens, const int32_t* offsets, int B,
+                      int32_t* prefix_len, int32_t* slot_idx, void* stream);
+
+/* Extend attention: the prefill of the missed tokens with the cached prefix reused
+ * (Sec. 2.1 and Sec. 3.2: only non-cached tokens are computed; Sec. 5: prefix reuse is
+ * lossless, so the result equals causal attention over the whole prompt).
+ *
+ * For request r with P = prefix_len[r], E = ext_len[r], extend row i < E and query head h
+ * (KV head g = h / (Hq / Hkv)), the visible keys are the P prefix tokens, read from the
+ * pool at slot_idx[slot_offsets[r] + j], j < P, followed by extend tokens 0..i:
+ *     out[e0 + i, h, :] = sum_j softmax_j(scale * <q_ext[e0 + i, h, :], K_j[g, :]>) V_j[g, :]
+ * with e0 = ext_offsets[r].
+ *
+ * q_ext        [T, Hq, D]   k_ext, v_ext  [T, Hkv, D]   out [T, Hq, D]   (dtype elements)
+ * kv_pool      pool written by pa_append_kv with the same Hkv, D, dtype, page_size, num_slots
+ * slot_idx, slot_offsets   as produced by pa_match_prefixes (slot_offsets = its offsets)
+ * prefix_len, ext_len      int32 [B];  ext_offsets int32 [B + 1], ext_offsets[B] = T
+ * T, max_kv_len  HOST values: total extend tokens, and an upper bound on
+ *                prefix_len[r] + ext_len[r] (used to size the launch; a request exceeding
+ *                it is still computed correctly, only less efficiently)
+ * workspace    at least pa_extend_workspace_bytes(B, T, max_kv_len, ...) bytes, 256-byte aligned
+ * Requests with ext_len[r] = 0 produce no output rows.  Prefix slots must lie in
+ * [0, num_slots); a slot outside is clamped into the pool (no fault, result for that
+ * request unspecified).  out must not alias the inputs. */
+int pa_extend_attention(const void* q_ext, const void* k_ext, const void* v_ext, const void* kv_pool,
+                        const int32_t* slot_idx, const int32_t* slot_offsets, const int32_t* prefix_len,
+                        const int32_t* ext_len, const int32_t* ext_offsets, int B, int64_t T,
+                        int64_t max_kv_len, int Hq, int Hkv, int D, int page_size, int64_t num_slots,
+                        int dtype, float scale, void* out, void* workspace, size_t workspace_bytes,
+                        void* stream);
+
+/* Cache the KV of newly computed tokens (Sec. 3.2: a prefix stays cached on its GPU from
+ * its first assignment until eviction): pool[new_slots[t]] = (k_ext[t], v_ext[t]).
+ * new_slots int32 [T], pairwise distinct and in [0, num_slots).  Distinctness is the
+ * caller's responsibility (duplicate slots leave one of the rows, unspecified which); a
+ * slot outside the pool is skipped. */
+int pa_append_kv(void* kv_pool, const int32_t* new_slots, const void* k_ext, const void* v_ext, int64_t T,
+                 int Hkv, int D, int page_size, int64_t num_slots, int dtype, void* stream);
+
+/* Inverse of pa_append_kv, for tests and debugging (not on the timed path): copies the
+ * pool rows of slots[0..n) into dense k_out, v_out [n, Hkv, D]. */
+int pa_gather_kv(const void* kv_pool, const int32_t* slots, int64_t n, int Hkv, int D, int page_size,
+                 int64_t num_slots, int dtype, void* k_out, void* v_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PREFIXATTN_H */

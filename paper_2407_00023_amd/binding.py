@@ -1,0 +1,203 @@
+"""Thin ctypes binding of libprefixattn (argument marshalling only).
+
+Every function below forwards to the C entry point of the same name (``pa_`` prefix
+dropped); all computation happens in the HIP kernels of the library.  PyTorch supplies
+device memory and the stream, nothing else.  There is no fallback: if the shared library
+has not been built the import fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libprefixattn.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it first (python -m paper_2407_00023_amd.build, or __graft_entry__.build()). "
+        "There is no CPU fallback.")
+
+_lib = C.CDLL(LIB_PATH)
+
+F32, BF16 = 0, 1
+_DTYPES = {torch.float32: F32, torch.bfloat16: BF16}
+
+_vp, _i, _i64, _sz, _f = C.c_void_p, C.c_int, C.c_int64, C.c_size_t, C.c_float
+_SIGS = {
+    "pa_last_error": (C.c_char_p, []),
+    "pa_tree_create": (_i, [C.POINTER(_vp)]),
+    "pa_tree_insert": (_i, [_vp, _vp, _vp, C.c_int32, C.POINTER(C.c_int32)]),
+    "pa_tree_upload": (_i, [_vp, _vp]),
+    "pa_tree_stats": (_i, [_vp, C.POINTER(_i64), C.POINTER(_i64)]),
+    "pa_tree_destroy": (_i, [_vp]),
+    "pa_kv_pool_bytes": (_sz, [_i64, _i, _i, _i, _i]),
+    "pa_extend_workspace_bytes": (_sz, [_i, _i64, _i64, _i, _i, _i, _i]),
+    "pa_match_prefixes": (_i, [_vp, _vp, _vp, _i, _vp, _vp, _vp]),
+    "pa_extend_attention": (_i, [_vp] * 9 + [_i, _i64, _i64, _i, _i, _i, _i, _i64, _i, _f, _vp, _vp, _sz, _vp]),
+    "pa_append_kv": (_i, [_vp, _vp, _vp, _vp, _i64, _i, _i, _i, _i64, _i, _vp]),
+    "pa_gather_kv": (_i, [_vp, _vp, _i64, _i, _i, _i, _i64, _i, _vp, _vp, _vp]),
+}
+for _name, (_res, _args) in _SIGS.items():
+    _fn = getattr(_lib, _name)
+    _fn.restype, _fn.argtypes = _res, _args
+
+EXPORTED = tuple(_SIGS)
+
+
+class PrefixAttnError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where} failed with code {code}: {_lib.pa_last_error().decode()}")
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise PrefixAttnError(rc, where)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _dev_i32(t: torch.Tensor, name: str) -> torch.Tensor:
+    if t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous int32 CUDA tensor")
+    return t
+
+
+class Tree:
+    """Radix tree of cached sequences (pa_tree_*): host inserts, then upload() before matching."""
+
+    def __init__(self):
+        h = _vp()
+        _check(_lib.pa_tree_create(C.byref(h)), "pa_tree_create")
+        self._h = h
+
+    def insert(self, tokens, slots) -> int:
+        """tokens, slots: host int32 arrays (numpy or CPU tensors).  Returns how many leading tokens were cached."""
+        t = torch.as_tensor(tokens, dtype=torch.int32).contiguous()
+        s = torch.as_tensor(slots, dtype=torch.int32).contiguous()
+        if t.is_cuda or s.is_cuda or t.shape != s.shape or t.dim() != 1:
+            raise TypeError("tokens and slots must be host int32 vectors of equal length")
+        already = C.c_int32(0)
+        _check(_lib.pa_tree_insert(self._h, _ptr(t), _ptr(s), t.numel(), C.byref(already)), "pa_tree_insert")
+        return int(already.value)
+
+    def upload(self, stream=None):
+        _check(_lib.pa_tree_upload(self._h, _stream(stream)), "pa_tree_upload")
+
+    def stats(self) -> Tuple[int, int]:
+        a, b = _i64(0), _i64(0)
+        _check(_lib.pa_tree_stats(self._h, C.byref(a), C.byref(b)), "pa_tree_stats")
+        return int(a.value), int(b.value)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib.pa_tree_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+
+def kv_pool_bytes(num_slots: int, Hkv: int, D: int, dtype: torch.dtype, page_size: int) -> int:
+    n = int(_lib.pa_kv_pool_bytes(num_slots, Hkv, D, _DTYPES[dtype], page_size))
+    if n == 0:
+        raise ValueError("pa_kv_pool_bytes: invalid arguments")
+    return n
+
+
+def extend_workspace_bytes(B: int, T: int, max_kv_len: int, Hq: int, Hkv: int, D: int, dtype: torch.dtype) -> int:
+    n = int(_lib.pa_extend_workspace_bytes(B, T, max_kv_len, Hq, Hkv, D, _DTYPES[dtype]))
+    if n == 0:
+        raise ValueError("pa_extend_workspace_bytes: invalid arguments")
+    return n
+
+
+def match_prefixes(tree: Tree, tokens: torch.Tensor, offsets: torch.Tensor, prefix_len: Optional[torch.Tensor] = None,
+                   slot_idx: Optional[torch.Tensor] = None, stream=None):
+    """-> (prefix_len int32 [B], slot_idx int32 like tokens).  Asynchronous on the stream."""
+    _dev_i32(tokens, "tokens"), _dev_i32(offsets, "offsets")
+    B = offsets.numel() - 1
+    if prefix_len is None:
+        prefix_len = torch.empty(B, dtype=torch.int32, device=tokens.device)
+    if slot_idx is None:
+        slot_idx = torch.empty_like(tokens)
+    _dev_i32(prefix_len, "prefix_len"), _dev_i32(slot_idx, "slot_idx")
+    if prefix_len.numel() < B or slot_idx.numel() < tokens.numel():
+        raise ValueError("output tensors too small")
+    _check(_lib.pa_match_prefixes(tree._h, _ptr(tokens), _ptr(offsets), B, _ptr(prefix_len), _ptr(slot_idx),
+                                  _stream(stream)), "pa_match_prefixes")
+    return prefix_len, slot_idx
+
+
+def extend_attention(q_ext: torch.Tensor, k_ext: torch.Tensor, v_ext: torch.Tensor, kv_pool: torch.Tensor,
+                     slot_idx: torch.Tensor, slot_offsets: torch.Tensor, prefix_len: torch.Tensor,
+                     ext_len: torch.Tensor, ext_offsets: torch.Tensor, scale: float, *, page_size: int,
+                     num_slots: int, max_kv_len: int, out: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """q_ext [T,Hq,D], k_ext/v_ext [T,Hkv,D] -> out [T,Hq,D].  Asynchronous on the stream."""
+    T, Hq, D = q_ext.shape
+    Hkv = k_ext.shape[1]
+    dt = _DTYPES[q_ext.dtype]
+    for name, t in (("q_ext", q_ext), ("k_ext", k_ext), ("v_ext", v_ext)):
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == q_ext.dtype):
+            raise TypeError(f"{name} must be a contiguous CUDA tensor of dtype {q_ext.dtype}")
+    if k_ext.shape != (T, Hkv, D) or v_ext.shape != k_ext.shape:
+        raise ValueError("k_ext / v_ext shape mismatch")
+    for name, t in (("slot_idx", slot_idx), ("slot_offsets", slot_offsets), ("prefix_len", prefix_len),
+                    ("ext_len", ext_len), ("ext_offsets", ext_offsets)):
+        _dev_i32(t, name)
+    B = prefix_len.numel()
+    if slot_offsets.numel() != B + 1 or ext_offsets.numel() != B + 1 or ext_len.numel() != B:
+        raise ValueError("per-request arrays disagree on B")
+    if kv_pool.numel() * kv_pool.element_size() < kv_pool_bytes(num_slots, Hkv, D, q_ext.dtype, page_size):
+        raise ValueError("kv_pool smaller than pa_kv_pool_bytes")
+    if out is None:
+        out = torch.empty_like(q_ext)
+    elif out.shape != q_ext.shape or out.dtype != q_ext.dtype or not out.is_contiguous() or not out.is_cuda:
+        raise ValueError("bad out tensor")
+    need = extend_workspace_bytes(B, T, max_kv_len, Hq, Hkv, D, q_ext.dtype)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q_ext.device)
+    wbytes = workspace.numel() * workspace.element_size()
+    _check(_lib.pa_extend_attention(_ptr(q_ext), _ptr(k_ext), _ptr(v_ext), _ptr(kv_pool), _ptr(slot_idx),
+                                    _ptr(slot_offsets), _ptr(prefix_len), _ptr(ext_len), _ptr(ext_offsets), B, T,
+                                    max_kv_len, Hq, Hkv, D, page_size, num_slots, dt, float(scale), _ptr(out),
+                                    _ptr(workspace), wbytes, _stream(stream)), "pa_extend_attention")
+    return out
+
+
+def append_kv(kv_pool: torch.Tensor, new_slots: torch.Tensor, k_ext: torch.Tensor, v_ext: torch.Tensor, *,
+              page_size: int, num_slots: int, stream=None) -> None:
+    T, Hkv, D = k_ext.shape
+    _dev_i32(new_slots, "new_slots")
+    if new_slots.numel() != T or v_ext.shape != k_ext.shape or v_ext.dtype != k_ext.dtype:
+        raise ValueError("append_kv: shape mismatch")
+    if not (k_ext.is_cuda and v_ext.is_cuda and k_ext.is_contiguous() and v_ext.is_contiguous()):
+        raise TypeError("k_ext / v_ext must be contiguous CUDA tensors")
+    if kv_pool.numel() * kv_pool.element_size() < kv_pool_bytes(num_slots, Hkv, D, k_ext.dtype, page_size):
+        raise ValueError("kv_pool smaller than pa_kv_pool_bytes")
+    _check(_lib.pa_append_kv(_ptr(kv_pool), _ptr(new_slots), _ptr(k_ext), _ptr(v_ext), T, Hkv, D, page_size,
+                             num_slots, _DTYPES[k_ext.dtype], _stream(stream)), "pa_append_kv")
+
+
+def gather_kv(kv_pool: torch.Tensor, slots: torch.Tensor, *, Hkv: int, D: int, dtype: torch.dtype, page_size: int,
+              num_slots: int, stream=None):
+    """Test/debug helper: dense (k, v) [n, Hkv, D] of the given slots."""
+    _dev_i32(slots, "slots")
+    n = slots.numel()
+    k = torch.empty((n, Hkv, D), dtype=dtype, device=slots.device)
+    v = torch.empty_like(k)
+    _check(_lib.pa_gather_kv(_ptr(kv_pool), _ptr(slots), n, Hkv, D, page_size, num_slots, _DTYPES[dtype], _ptr(k),
+                             _ptr(v), _stream(stream)), "pa_gather_kv")
+    return k, v

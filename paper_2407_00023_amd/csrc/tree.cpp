@@ -1,0 +1,226 @@
+// Host-side radix tree of cached token sequences, its flattening, and the upload of the
+// flat form to device memory.
+//
+// Sec. 3.2 ("global scheduler data structures") and Sec. 3.3 of the paper: insertion
+// matches a sequence from the beginning until no match exists and adds the remainder as
+// a new leaf; a node that matches only partly is split into matched part + remainder; a
+// sequence that matches nothing becomes a new tree (here a child of an empty root).
+#include <algorithm>
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "common.h"
+
+namespace pa {
+
+static thread_local std::string g_last_error;
+
+int fail(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return code;
+}
+
+struct Node {
+    std::vector<int32_t> tok;   // edge tokens leading into this node
+    std::vector<int32_t> slot;  // KV slot of each edge token
+    std::unordered_map<int32_t, int32_t> child;  // first token of child's edge -> node id
+};
+
+}  // namespace pa
+
+struct pa_tree {
+    std::vector<pa::Node> nodes;
+    int64_t n_tokens = 0;
+    // device mirror
+    bool uploaded = false;
+    int device = -1;
+    void* d_blob = nullptr;
+    pa::DeviceTree view{};
+    std::mutex mu;
+};
+
+extern "C" const char* pa_last_error(void) { return pa::g_last_error.c_str(); }
+
+extern "C" int pa_tree_create(pa_tree** out) {
+    PA_REQUIRE(out != nullptr, "pa_tree_create: out is NULL");
+    pa_tree* t = new (std::nothrow) pa_tree();
+    if (!t) return pa::fail(PA_ENOMEM, "pa_tree_create: out of host memory");
+    t->nodes.emplace_back();  // node 0: empty virtual root
+    *out = t;
+    return PA_OK;
+}
+
+extern "C" int pa_tree_insert(pa_tree* tree, const int32_t* tokens, const int32_t* slots, int32_t n,
+                              int32_t* n_already_cached) {
+    PA_REQUIRE(tree != nullptr, "pa_tree_insert: tree is NULL");
+    PA_REQUIRE(n >= 0 && (n == 0 || (tokens && slots)), "pa_tree_insert: bad sequence (n=%d)", n);
+    std::lock_guard<std::mutex> lk(tree->mu);
+    auto& nodes = tree->nodes;
+    int32_t cur = 0, pos = 0;
+    try {
+        while (pos < n) {
+            auto it = nodes[cur].child.find(tokens[pos]);
+            if (it == nodes[cur].child.end()) break;
+            int32_t c = it->second;
+            const int32_t elen = static_cast<int32_t>(nodes[c].tok.size());
+            const int32_t lim = std::min(elen, n - pos);
+            int32_t k = 1;  // first token equal by construction of the child map
+            while (k < lim && nodes[c].tok[k] == tokens[pos + k]) ++k;
+            if (k < elen) {
+                if (pos + k == n) { pos = n; break; }  // the sequence ends inside this edge: nothing new to store
+                // split c at k: c keeps [0,k), a new node takes [k,elen) together with c's children
+                pa::Node rest;
+                rest.tok.assign(nodes[c].tok.begin() + k, nodes[c].tok.end());
+                rest.slot.assign(nodes[c].slot.begin() + k, nodes[c].slot.end());
+                rest.child.swap(nodes[c].child);
+                const int32_t rid = static_cast<int32_t>(nodes.size());
+                const int32_t first = rest.tok[0];
+                nodes.push_back(std::move(rest));
+                nodes[c].tok.resize(k);
+                nodes[c].slot.resize(k);
+                nodes[c].child.clear();
+                nodes[c].child.emplace(first, rid);
+                pos += k;
+                cur = c;
+                break;  // tokens[pos] differs from `first`, so the walk ends here
+            }
+            pos += elen;
+            cur = c;
+        }
+        if (n_already_cached) *n_already_cached = pos;
+        if (pos < n) {
+            pa::Node leaf;
+            leaf.tok.assign(tokens + pos, tokens + n);
+            leaf.slot.assign(slots + pos, slots + n);
+            const int32_t lid = static_cast<int32_t>(nodes.size());
+            nodes.push_back(std::move(leaf));
+            nodes[cur].child.emplace(tokens[pos], lid);
+            tree->n_tokens += n - pos;
+            tree->uploaded = false;
+        }
+    } catch (const std::bad_alloc&) {
+        return pa::fail(PA_ENOMEM, "pa_tree_insert: out of host memory");
+    }
+    return PA_OK;
+}
+
+extern "C" int pa_tree_stats(const pa_tree* tree, int64_t* n_nodes, int64_t* n_tokens) {
+    PA_REQUIRE(tree != nullptr, "pa_tree_stats: tree is NULL");
+    if (n_nodes) *n_nodes = static_cast<int64_t>(tree->nodes.size());
+    if (n_tokens) *n_tokens = tree->n_tokens;
+    return PA_OK;
+}
+
+static void release_device(pa_tree* t) {
+    if (t->d_blob) {
+        int prev = -1;
+        if (hipGetDevice(&prev) == hipSuccess && prev != t->device && t->device >= 0) (void)hipSetDevice(t->device);
+        (void)hipFree(t->d_blob);
+        if (prev >= 0 && prev != t->device) (void)hipSetDevice(prev);
+        t->d_blob = nullptr;
+    }
+    t->uploaded = false;
+}
+
+extern "C" int pa_tree_upload(pa_tree* tree, void* stream_) {
+    PA_REQUIRE(tree != nullptr, "pa_tree_upload: tree is NULL");
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    std::lock_guard<std::mutex> lk(tree->mu);
+    const auto& nodes = tree->nodes;
+    const int64_t nn = static_cast<int64_t>(nodes.size());
+    if (tree->n_tokens > INT32_MAX - 64 || nn > INT32_MAX / 4)
+        return pa::fail(PA_EINVAL, "pa_tree_upload: tree too large for 32-bit indices");
+
+    // hash capacity: power of two >= 2 * (#edges), at least 64 so a 64-lane probe window never wraps onto itself
+    uint64_t cap = 64;
+    while (cap < 2ull * static_cast<uint64_t>(nn)) cap <<= 1;
+
+    auto up = [](size_t x) { return (x + 255) & ~size_t(255); };
+    const size_t ntok = static_cast<size_t>(tree->n_tokens);
+    const size_t o_tok = 0;
+    const size_t o_slot = o_tok + up((ntok + 64) * 4);
+    const size_t o_start = o_slot + up((ntok + 64) * 4);
+    const size_t o_len = o_start + up(nn * 4);
+    const size_t o_key = o_len + up(nn * 4);
+    const size_t o_val = o_key + up(cap * 8);
+    const size_t total = o_val + up(cap * 4);
+
+    std::vector<unsigned char> blob;
+    try {
+        blob.assign(total, 0);
+    } catch (const std::bad_alloc&) {
+        return pa::fail(PA_ENOMEM, "pa_tree_upload: out of host memory");
+    }
+    int32_t* h_tok = reinterpret_cast<int32_t*>(blob.data() + o_tok);
+    int32_t* h_slot = reinterpret_cast<int32_t*>(blob.data() + o_slot);
+    int32_t* h_start = reinterpret_cast<int32_t*>(blob.data() + o_start);
+    int32_t* h_len = reinterpret_cast<int32_t*>(blob.data() + o_len);
+    unsigned long long* h_key = reinterpret_cast<unsigned long long*>(blob.data() + o_key);
+    int32_t* h_val = reinterpret_cast<int32_t*>(blob.data() + o_val);
+    for (uint64_t i = 0; i < cap; ++i) { h_key[i] = pa::kEmptyKey; h_val[i] = -1; }
+
+    int64_t cursor = 0;
+    for (int64_t i = 0; i < nn; ++i) {
+        const auto& nd = nodes[i];
+        h_start[i] = static_cast<int32_t>(cursor);
+        h_len[i] = static_cast<int32_t>(nd.tok.size());
+        if (!nd.tok.empty()) {
+            std::memcpy(h_tok + cursor, nd.tok.data(), nd.tok.size() * 4);
+            std::memcpy(h_slot + cursor, nd.slot.data(), nd.slot.size() * 4);
+        }
+        cursor += static_cast<int64_t>(nd.tok.size());
+        for (const auto& kv : nd.child) {
+            const unsigned long long key =
+                (static_cast<unsigned long long>(static_cast<uint32_t>(i)) << 32) | static_cast<uint32_t>(kv.first);
+            uint64_t h = pa::hash_key(key) & (cap - 1);
+            while (h_key[h] != pa::kEmptyKey) h = (h + 1) & (cap - 1);
+            h_key[h] = key;
+            h_val[h] = kv.second;
+        }
+    }
+
+    release_device(tree);
+    PA_HIP(hipGetDevice(&tree->device));
+    void* d = nullptr;
+    if (hipMalloc(&d, total) != hipSuccess) {
+        (void)hipGetLastError();
+        return pa::fail(PA_ENOMEM, "pa_tree_upload: hipMalloc of %zu bytes failed", total);
+    }
+    tree->d_blob = d;
+    PA_HIP(hipMemcpyAsync(d, blob.data(), total, hipMemcpyHostToDevice, stream));
+    PA_HIP(hipStreamSynchronize(stream));
+    unsigned char* b = static_cast<unsigned char*>(d);
+    tree->view.edge_tok = reinterpret_cast<const int32_t*>(b + o_tok);
+    tree->view.edge_slot = reinterpret_cast<const int32_t*>(b + o_slot);
+    tree->view.node_start = reinterpret_cast<const int32_t*>(b + o_start);
+    tree->view.node_len = reinterpret_cast<const int32_t*>(b + o_len);
+    tree->view.ht_key = reinterpret_cast<const unsigned long long*>(b + o_key);
+    tree->view.ht_val = reinterpret_cast<const int32_t*>(b + o_val);
+    tree->view.ht_mask = static_cast<uint32_t>(cap - 1);
+    tree->view.n_nodes = static_cast<int32_t>(nn);
+    tree->uploaded = true;
+    return PA_OK;
+}
+
+extern "C" int pa_tree_destroy(pa_tree* tree) {
+    if (!tree) return PA_OK;
+    release_device(tree);
+    delete tree;
+    return PA_OK;
+}
+
+int pa_tree_device(const pa_tree* tree, const pa::DeviceTree** out) {
+    if (!tree) return pa::fail(PA_EINVAL, "tree is NULL");
+    if (!tree->uploaded)
+        return pa::fail(PA_ESTATE, "tree not uploaded since its last insert (call pa_tree_upload)");
+    *out = &tree->view;
+    return PA_OK;
+}
