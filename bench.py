@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the prefix-cached extend-prefill hot path on one MI355X.
+
+One step = one pass of the whole path over one synthetic batch already resident in HBM:
+match_prefixes -> extend_attention -> append_kv.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload tool_use]
+
+value      extend (newly prefilled) tokens per second over the whole step
+roofline   the extend-attention kernel against the roof that binds it for this workload:
+           algorithmic bytes or flops per launch / average kernel time from HIP events
+cpu_baseline  the CPU oracle, as it stands, on a bounded sample of the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+
+# HBM bytes per launch of the extend-attention kernel, measured with rocprofv3 --pmc (FETCH_SIZE and
+# WRITE_SIZE, scaled by a copy kernel of known size); see profiles/.  None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_work(wl, prefix_len):
+    """Algorithmic bytes and flops of one extend-attention launch.
+
+    bytes: each request reads its own prefix K and V rows once per KV head (no credit for sharing
+    between requests), its slot ids, and q/k_ext/v_ext once; out is written once.
+    flops: QK^T and PV on visible (query, key) pairs only.
+    """
+    import numpy as np
+    el = 4 if wl.dtype == "f32" else 2
+    P = prefix_len.astype(np.int64)
+    E = wl.ext_len.astype(np.int64)
+    T = int(E.sum())
+    kv_bytes = int(P.sum()) * wl.Hkv * wl.D * el * 2
+    slot_bytes = 4 * int(P.sum())
+    io_bytes = T * (2 * wl.Hq * wl.D * el + 2 * wl.Hkv * wl.D * el)
+    flops = 4 * wl.D * wl.Hq * int((E * P + E * (E + 1) // 2).sum())
+    return kv_bytes + slot_bytes + io_bytes, flops
+
+
+def cpu_baseline(wl, budget_s=15.0):
+    """The oracle on the first n requests of the workload (all of their rows), n chosen so that the
+    attention part takes about budget_s."""
+    import numpy as np
+
+    import oracle
+    from harness import OracleSide
+    o = OracleSide(wl)
+    cores = int(os.environ.get("OMP_NUM_THREADS", 0)) or (os.cpu_count() or 1)
+    t0 = time.perf_counter()
+    pl, si = o.match()
+    t_match = time.perf_counter() - t0
+
+    def run(n):
+        eo = wl.ext_offsets[:n + 1]
+        T = int(eo[-1])
+        t = time.perf_counter()
+        oracle.extend_attention(wl.q_ext[:T], wl.k_ext[:T], wl.v_ext[:T], o.pool_k, o.pool_v, si, wl.offsets[:n + 1],
+                                pl[:n], wl.ext_len[:n], eo, wl.scale, wl.dtype)
+        return time.perf_counter() - t, T
+
+    t1, T1 = run(1)
+    n = int(max(1, min(wl.B, budget_s / max(t1, 1e-6))))
+    if n > 1:
+        t_att, Tn = run(n)
+    else:
+        t_att, Tn = t1, T1
+    t = time.perf_counter()
+    oracle.append_kv(o.pool_k, o.pool_v, wl.new_slots[:Tn], wl.k_ext[:Tn], wl.v_ext[:Tn], wl.dtype)
+    t_app = time.perf_counter() - t
+    total = t_match * n / wl.B + t_att + t_app
+    return {"value": Tn / total, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {n} of {wl.B} requests ({Tn} extend tokens, all heads): trie match {t_match * n / wl.B:.3f}s "
+                      f"(whole batch {t_match:.3f}s, {wl.B / t_match:.0f} req/s), fp64 attention {t_att:.2f}s, append {t_app:.4f}s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="tool_use", choices=["tiny_fp32", "tool_use", "long_doc_qa", "agent_tree", "video_qa"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", default="", help="time only one call of the path: match | extend | append (for profiling)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the path has no cross-GPU step); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from harness import GpuSide
+    from paper_2407_00023_amd import binding as pa
+    from paper_2407_00023_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU; there is no CPU fallback"
+    dev = torch.device("cuda:0")
+    wl = W.CONFIGS[args.workload]()
+    g = GpuSide(wl, dev)
+    tdt = g.tdtype
+    # every buffer of the step is allocated once, outside the timed region
+    prefix_len = torch.empty(wl.B, dtype=torch.int32, device=dev)
+    slot_idx = torch.empty_like(g.tokens)
+    out = torch.empty_like(g.q)
+    ws = torch.empty(pa.extend_workspace_bytes(wl.B, wl.T, g.max_kv_len, wl.Hq, wl.Hkv, wl.D, tdt), dtype=torch.uint8, device=dev)
+
+    def step():
+        if args.only in ("", "match"):
+            pa.match_prefixes(g.tree, g.tokens, g.offsets, prefix_len, slot_idx)
+        if args.only in ("", "extend"):
+            pa.extend_attention(g.q, g.k, g.v, g.pool, slot_idx, g.offsets, prefix_len, g.ext_len, g.ext_offsets, wl.scale,
+                                max_kv_len=g.max_kv_len, out=out, workspace=ws, **g.kw)
+        if args.only in ("", "append"):
+            pa.append_kv(g.pool, g.new_slots, g.k, g.v, **g.kw)
+
+    pa.match_prefixes(g.tree, g.tokens, g.offsets, prefix_len, slot_idx)  # outputs valid whatever --only says
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # same steps again with the library's per-kernel event timing switched on
+    pa.profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    pa.profile_enable(False)
+    kern = {}
+    for name in ("match_prefixes", "extend_tiles", "extend_attention", "extend_merge", "extend_attention_f32", "append_kv"):
+        ms, n = pa.profile_read(name)
+        if n:
+            kern[name] = {"avg_us": ms / n * 1e3, "launches_per_step": n / args.steps}
+
+    pl = prefix_len.cpu().numpy()
+    assert (pl == wl.designed_prefix_len).all(), "matcher disagrees with the designed prefix lengths"
+    nbytes, flops = algorithmic_work(wl, pl)
+    main_k = "extend_attention_f32" if wl.dtype == "f32" else "extend_attention"
+    roofline = None
+    if main_k in kern:
+        t_k = kern[main_k]["avg_us"] * 1e-6
+        gbs, tfs = nbytes / t_k / 1e9, flops / t_k / 1e12
+        peak_f = FP32_VECTOR_PEAK_TFLOPS if wl.dtype == "f32" else MFMA_BF16_PEAK_TFLOPS
+        t_mem, t_cmp = nbytes / (HBM_PEAK_GBS * 1e9), flops / (peak_f * 1e12)
+        if t_mem >= t_cmp:
+            roofline = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
+        else:
+            roofline = {"bound": "alu" if wl.dtype == "f32" else "mfma", "achieved": tfs, "peak": peak_f, "unit": "TFLOP/s",
+                        "frac": tfs / peak_f}
+        roofline.update({"traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "kernel": main_k,
+                         "avg_kernel_us": kern[main_k]["avg_us"], "algorithmic_bytes": nbytes, "algorithmic_flops": flops,
+                         "hbm_frac": gbs / HBM_PEAK_GBS, "compute_frac": tfs / peak_f})
+
+    res = {
+        "metric": "extend_prefill_tokens_per_s", "value": wl.T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": args.workload, "requests": wl.B, "extend_tokens": wl.T, "prompt_tokens": int(wl.offsets[-1]),
+                   "Hq": wl.Hq, "Hkv": wl.Hkv, "D": wl.D, "page_size": wl.page_size, "num_slots": wl.num_slots,
+                   "cached_sequences": wl.n_cached, "only": args.only or "whole path"},
+        "prompt_tokens_per_s": int(wl.offsets[-1]) / (ms_per_step * 1e-3),
+        "kernels": kern,
+        "roofline": roofline,
+    }
+    if "match_prefixes" in kern:
+        res["match_reqs_per_s"] = wl.B / (kern["match_prefixes"]["avg_us"] * 1e-6)
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -154,6 +154,18 @@ int pa_append_kv(void* kv_pool, const int32_t* new_slots, const void* k_ext, con
 int pa_gather_kv(const void* kv_pool, const int32_t* slots, int64_t n, int Hkv, int D, int page_size,
                  int64_t num_slots, int dtype, void* k_out, void* v_out, void* stream);
 
+/* ---------------------------------------------------------------------------------
+ * Per-kernel timing for benchmarks (not part of the method).  While enabled, every kernel
+ * the library launches is bracketed by two HIP events on its stream (this creates events on
+ * first use, so do not enable it under stream capture).  pa_profile_enable(1) clears the
+ * records and starts recording, pa_profile_enable(0) stops.  pa_profile_read waits for the
+ * recorded events and returns the summed device time (ms) and the number of launches of one
+ * kernel, named "match_prefixes", "extend_tiles", "extend_attention", "extend_merge",
+ * "extend_attention_f32", "append_kv" or "gather_kv".  At most 65536 launches are recorded.
+ * --------------------------------------------------------------------------------- */
+int pa_profile_enable(int on);
+int pa_profile_read(const char* kernel, double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

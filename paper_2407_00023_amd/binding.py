@@ -40,6 +40,8 @@ _SIGS = {
     "pa_extend_attention": (_i, [_vp] * 9 + [_i, _i64, _i64, _i, _i, _i, _i, _i64, _i, _f, _vp, _vp, _sz, _vp]),
     "pa_append_kv": (_i, [_vp, _vp, _vp, _vp, _i64, _i, _i, _i, _i64, _i, _vp]),
     "pa_gather_kv": (_i, [_vp, _vp, _i64, _i, _i, _i, _i64, _i, _vp, _vp, _vp]),
+    "pa_profile_enable": (_i, [_i]),
+    "pa_profile_read": (_i, [C.c_char_p, C.POINTER(C.c_double), C.POINTER(_i64)]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _fn = getattr(_lib, _name)
@@ -201,3 +203,14 @@ def gather_kv(kv_pool: torch.Tensor, slots: torch.Tensor, *, Hkv: int, D: int, d
     _check(_lib.pa_gather_kv(_ptr(kv_pool), _ptr(slots), n, Hkv, D, page_size, num_slots, _DTYPES[dtype], _ptr(k),
                              _ptr(v), _stream(stream)), "pa_gather_kv")
     return k, v
+
+
+def profile_enable(on: bool) -> None:
+    _check(_lib.pa_profile_enable(1 if on else 0), "pa_profile_enable")
+
+
+def profile_read(kernel: str) -> Tuple[float, int]:
+    """-> (summed device time in ms, launches) of one library kernel since profile_enable(True)."""
+    ms, n = C.c_double(0.0), _i64(0)
+    _check(_lib.pa_profile_read(kernel.encode(), C.byref(ms), C.byref(n)), "pa_profile_read")
+    return float(ms.value), int(n.value)

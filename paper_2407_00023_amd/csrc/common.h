@@ -67,6 +67,21 @@ __host__ __device__ inline int64_t pool_row(int64_t slot, int which, int g, int 
     return (((page * 2 + which) * Hkv + g) * page_size + o) * D;
 }
 
+// Per-kernel event timing (profile.cpp).  A ProfScope around a launch records a start/stop event
+// pair on the stream while profiling is switched on, and does nothing otherwise.
+enum ProfKernel { kProfMatch = 0, kProfTiles, kProfExtend, kProfMerge, kProfExtendF32, kProfAppend, kProfGather, kProfKernels };
+bool prof_begin(int kernel, hipStream_t stream, size_t* slot);
+void prof_end(size_t slot, hipStream_t stream);
+struct ProfScope {
+    hipStream_t stream;
+    size_t slot = 0;
+    bool on;
+    ProfScope(int kernel, hipStream_t s) : stream(s), on(prof_begin(kernel, s, &slot)) {}
+    ~ProfScope() { if (on) prof_end(slot, stream); }
+    ProfScope(const ProfScope&) = delete;
+    ProfScope& operator=(const ProfScope&) = delete;
+};
+
 }  // namespace pa
 
 // Internal: device view of an uploaded tree (PA_ESTATE if it is stale or was never uploaded).

@@ -421,22 +421,30 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
     const int G = Hq / Hkv;
     const float scale_log2e = scale * 1.4426950408889634f;
 
-    hipLaunchKernelGGL(extend_tiles_kernel, dim3(1), dim3(256), 0, stream, ext_len, B, G, p.tiles_cap, n_tiles, tile_req,
-                       tile_row0);
+    {
+        ProfScope prof(kProfTiles, stream);
+        hipLaunchKernelGGL(extend_tiles_kernel, dim3(1), dim3(256), 0, stream, ext_len, B, G, p.tiles_cap, n_tiles,
+                           tile_req, tile_row0);
+    }
     const dim3 grid(static_cast<unsigned>(p.tiles_cap) * p.nsplit, Hkv);
     const dim3 mgrid(p.tiles_cap, Hkv);
 #define PA_LAUNCH_BF16(DD)                                                                                           \
     do {                                                                                                             \
+        {                                                                                                            \
+        ProfScope prof(kProfExtend, stream);                                                                         \
         hipLaunchKernelGGL(extend_bf16_kernel<DD>, grid, dim3(kThreads), 0, stream,                                  \
                            static_cast<const __hip_bfloat16*>(q_ext), static_cast<const __hip_bfloat16*>(k_ext),     \
                            static_cast<const __hip_bfloat16*>(v_ext), static_cast<const __hip_bfloat16*>(kv_pool),   \
                            slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots,  \
                            scale_log2e, static_cast<__hip_bfloat16*>(out), n_tiles, tile_req, tile_row0, p.nsplit,   \
                            p.chunk, part_o, part_ml);                                                                \
-        if (p.nsplit > 1)                                                                                            \
+        }                                                                                                            \
+        if (p.nsplit > 1) {                                                                                          \
+            ProfScope prof(kProfMerge, stream);                                                                      \
             hipLaunchKernelGGL(extend_merge_kernel<DD>, mgrid, dim3(256), 0, stream, prefix_len, ext_len,            \
                                ext_offsets, Hq, Hkv, static_cast<__hip_bfloat16*>(out), n_tiles, tile_req,           \
                                tile_row0, p.nsplit, p.chunk, part_o, part_ml);                                       \
+        }                                                                                                            \
     } while (0)
     if (D == 64) PA_LAUNCH_BF16(64);
     else PA_LAUNCH_BF16(128);

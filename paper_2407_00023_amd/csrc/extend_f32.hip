@@ -123,8 +123,11 @@ int pa_extend_attention_f32(const void* q_ext, const void* k_ext, const void* v_
                        static_cast<const float*>(k_ext), static_cast<const float*>(v_ext),                       \
                        static_cast<const float*>(kv_pool), slot_idx, slot_offsets, prefix_len, ext_len,          \
                        ext_offsets, B, T, Hq, Hkv, page_size, num_slots, scale, static_cast<float*>(out))
-    if (D == 64) PA_LAUNCH_F32(64);
-    else PA_LAUNCH_F32(128);
+    {
+        pa::ProfScope prof(pa::kProfExtendF32, stream);
+        if (D == 64) PA_LAUNCH_F32(64);
+        else PA_LAUNCH_F32(128);
+    }
 #undef PA_LAUNCH_F32
     PA_HIP(hipGetLastError());
     return PA_OK;

@@ -66,6 +66,7 @@ extern "C" int pa_append_kv(void* kv_pool, const int32_t* new_slots, const void*
     int rc = pa::check_pool_args("pa_append_kv", kv_pool, new_slots, k_ext, v_ext, T, Hkv, D, page_size, num_slots, dtype);
     if (rc != PA_OK || T == 0) return rc;
     const int vpr = static_cast<int>(D * pa::elt_size(dtype) / 16);
+    pa::ProfScope prof(pa::kProfAppend, static_cast<hipStream_t>(stream));
     hipLaunchKernelGGL(pa::kv_rows_kernel<true>, dim3(pa::grid_for(T * 2 * Hkv * vpr)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), static_cast<uint4*>(kv_pool), new_slots,
                        static_cast<uint4*>(const_cast<void*>(k_ext)), static_cast<uint4*>(const_cast<void*>(v_ext)), T,
@@ -79,6 +80,7 @@ extern "C" int pa_gather_kv(const void* kv_pool, const int32_t* slots, int64_t n
     int rc = pa::check_pool_args("pa_gather_kv", kv_pool, slots, k_out, v_out, n, Hkv, D, page_size, num_slots, dtype);
     if (rc != PA_OK || n == 0) return rc;
     const int vpr = static_cast<int>(D * pa::elt_size(dtype) / 16);
+    pa::ProfScope prof(pa::kProfGather, static_cast<hipStream_t>(stream));
     hipLaunchKernelGGL(pa::kv_rows_kernel<false>, dim3(pa::grid_for(n * 2 * Hkv * vpr)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), static_cast<uint4*>(const_cast<void*>(kv_pool)), slots,
                        static_cast<uint4*>(k_out), static_cast<uint4*>(v_out), n, Hkv, vpr, page_size, num_slots);

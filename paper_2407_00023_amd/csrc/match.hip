@@ -108,8 +108,11 @@ extern "C" int pa_match_prefixes(const pa_tree* tree, const int32_t* tokens, con
     if (B == 0) return PA_OK;
     PA_REQUIRE(offsets && prefix_len, "pa_match_prefixes: offsets or prefix_len is NULL");
     // tokens / slot_idx may be NULL only if every prompt is empty (offsets[B] == 0), which the host cannot see
-    hipLaunchKernelGGL(pa::match_prefixes_kernel, dim3(B), dim3(pa::kMatchThreads), 0,
-                       static_cast<hipStream_t>(stream), *view, tokens, offsets, prefix_len, slot_idx);
+    {
+        pa::ProfScope prof(pa::kProfMatch, static_cast<hipStream_t>(stream));
+        hipLaunchKernelGGL(pa::match_prefixes_kernel, dim3(B), dim3(pa::kMatchThreads), 0,
+                           static_cast<hipStream_t>(stream), *view, tokens, offsets, prefix_len, slot_idx);
+    }
     PA_HIP(hipGetLastError());
     return PA_OK;
 }

@@ -1,0 +1,330 @@
+"""GPU parity: the HIP path, called through the C-ABI binding, against the CPU oracle on the
+same seeded inputs.
+
+Bars (written out in each test): prefix lengths and slot indices bit-exact; KV round trips
+bit-exact; extend attention within max-abs 1e-4 (fp32) and 2e-2 (bf16 in/out) of the fp64
+oracle, whose output is not rounded.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from harness import GpuSide, OracleSide, assert_match_equal, out_to_f64, sample_rows, to_torch
+from paper_2407_00023_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "radix_hand_example.txt")
+SMALL = ["tiny_fp32", "tool_use", "long_doc_qa", "agent_tree", "video_qa"]
+FULL = ["tool_use", "long_doc_qa", "agent_tree", "video_qa"]
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+@pytest.fixture(scope="module")
+def pa(gpu_device):
+    from paper_2407_00023_amd import binding
+    return binding
+
+
+# ------------------------------------------------------------------------------------ matcher
+
+def test_match_hand_worked_example(pa, gpu_device):
+    """The hand-derived radix example of tests/golden (Sec. 3.2 insert/split rules, Algorithm 1 cached_len)."""
+    tree, queries = pa.Tree(), []
+    for line in open(GOLDEN):
+        line = line.strip()
+        if line.startswith("insert"):
+            pairs = [x.split(":") for x in line.split()[1:]]
+            tree.insert(np.array([int(a) for a, _ in pairs], np.int32), np.array([int(b) for _, b in pairs], np.int32))
+        elif line.startswith("query"):
+            a, b, c = line[len("query"):].split("|")
+            queries.append(([int(x) for x in a.split()], int(b), [int(x) for x in c.split()]))
+    tree.upload()
+    toks = np.concatenate([np.asarray(q[0], np.int32) for q in queries])
+    off = np.zeros(len(queries) + 1, np.int32)
+    off[1:] = np.cumsum([len(q[0]) for q in queries])
+    pl, si = pa.match_prefixes(tree, torch.from_numpy(toks).to(gpu_device), torch.from_numpy(off).to(gpu_device))
+    pl, si = pl.cpu().numpy(), si.cpu().numpy()
+    for r, (_, want_len, want_slots) in enumerate(queries):
+        assert pl[r] == want_len, r
+        assert list(si[off[r]:off[r] + want_len]) == want_slots, r
+
+
+@pytest.mark.parametrize("vocab,seed", [(2, 0), (3, 1), (4, 2), (1000, 3)])
+def test_match_random_small_vocab(pa, gpu_device, vocab, seed):
+    """Tiny vocabularies force many splits, mid-edge stops and full matches; bit-exact vs the oracle trie."""
+    import oracle
+    rng = np.random.default_rng(seed)
+    cached, nslot = [], 0
+    for _ in range(150):
+        n = int(rng.integers(0, 40 if vocab < 10 else 3000))
+        cached.append((rng.integers(0, vocab, n).astype(np.int32), np.arange(nslot, nslot + n, dtype=np.int32)))
+        nslot += n
+    prompts = []
+    for _ in range(97):
+        if rng.random() < 0.5 and cached:
+            base = cached[int(rng.integers(0, len(cached)))][0]
+            cut = int(rng.integers(0, len(base) + 1))
+            tail = rng.integers(0, vocab, int(rng.integers(0, 20))).astype(np.int32)
+            prompts.append(np.concatenate([base[:cut], tail]))
+        else:
+            prompts.append(rng.integers(0, vocab, int(rng.integers(0, 30))).astype(np.int32))
+    toks = np.concatenate(prompts).astype(np.int32)
+    off = np.zeros(len(prompts) + 1, np.int32)
+    off[1:] = np.cumsum([len(p) for p in prompts])
+    pl_ref, si_ref = oracle.match_prefixes(cached, toks, off)
+    tree = pa.Tree()
+    for c in cached:
+        tree.insert(*c)
+    tree.upload()
+    pl, si = pa.match_prefixes(tree, torch.from_numpy(toks).to(gpu_device), torch.from_numpy(off).to(gpu_device))
+    pl, si = pl.cpu().numpy(), si.cpu().numpy()
+    np.testing.assert_array_equal(pl, pl_ref)
+    for r in range(len(prompts)):
+        np.testing.assert_array_equal(si[off[r]:off[r] + pl_ref[r]], si_ref[off[r]:off[r] + pl_ref[r]])
+
+
+def test_match_empty_tree_and_empty_batch(pa, gpu_device):
+    tree = pa.Tree()
+    tree.upload()
+    toks = torch.arange(10, dtype=torch.int32, device=gpu_device)
+    off = torch.tensor([0, 4, 4, 10], dtype=torch.int32, device=gpu_device)
+    pl, _ = pa.match_prefixes(tree, toks, off)
+    assert pl.cpu().tolist() == [0, 0, 0]
+    pl, si = pa.match_prefixes(tree, toks[:0], torch.zeros(1, dtype=torch.int32, device=gpu_device))
+    assert pl.numel() == 0 and si.numel() == 0
+
+
+# ------------------------------------------------------------------------------------ append / gather
+
+@pytest.mark.parametrize("dtype,Hkv,D,page,nslots", [("f32", 2, 64, 1, 512), ("bf16", 8, 128, 16, 4096),
+                                                     ("bf16", 2, 64, 16, 1024), ("f32", 1, 128, 4, 64)])
+def test_append_gather_round_trip_bit_exact(pa, gpu_device, dtype, Hkv, D, page, nslots):
+    """append_kv then gather_kv returns the rows bit for bit, untouched slots keep their previous content
+    (Sec. 3.2: computed KV stays cached), and an out-of-pool slot is skipped."""
+    rng = np.random.default_rng(5)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    pool = torch.zeros(pa.kv_pool_bytes(nslots, Hkv, D, tdt, page), dtype=torch.uint8, device=gpu_device)
+    kw = dict(page_size=page, num_slots=nslots)
+    perm = rng.permutation(nslots).astype(np.int32)
+    n1, n2 = nslots // 3, nslots // 4
+    s1, s2 = perm[:n1], perm[n1:n1 + n2]
+
+    def vals(n):
+        x = rng.standard_normal((n, Hkv, D)).astype(np.float32)
+        return x if dtype == "f32" else W.f32_to_bf16_bits(x)
+
+    k1, v1, k2, v2 = vals(n1), vals(n1), vals(n2), vals(n2)
+    pa.append_kv(pool, torch.from_numpy(s1).to(gpu_device), to_torch(k1, dtype, gpu_device), to_torch(v1, dtype, gpu_device), **kw)
+    s2_bad = np.concatenate([s2, np.array([nslots + 7, -3], np.int32)])
+    k2b, v2b = np.concatenate([k2, k2[:2]]), np.concatenate([v2, v2[:2]])
+    pa.append_kv(pool, torch.from_numpy(s2_bad).to(gpu_device), to_torch(k2b, dtype, gpu_device), to_torch(v2b, dtype, gpu_device), **kw)
+    gk, gv = pa.gather_kv(pool, torch.from_numpy(perm).to(gpu_device), Hkv=Hkv, D=D, dtype=tdt, **kw)
+
+    def bits(t):
+        return t.view(torch.int16 if dtype == "bf16" else torch.int32).cpu().numpy()
+
+    def ref_bits(a):
+        return a.view(np.int16 if dtype == "bf16" else np.int32)
+
+    gk, gv = bits(gk), bits(gv)
+    np.testing.assert_array_equal(gk[:n1], ref_bits(k1))
+    np.testing.assert_array_equal(gv[:n1], ref_bits(v1))
+    np.testing.assert_array_equal(gk[n1:n1 + n2], ref_bits(k2))
+    np.testing.assert_array_equal(gv[n1:n1 + n2], ref_bits(v2))
+    assert not gk[n1 + n2:].any() and not gv[n1 + n2:].any()
+
+
+# ------------------------------------------------------------------------------------ whole path, small
+
+@pytest.mark.parametrize("name", SMALL)
+@pytest.mark.parametrize("seed", [0, 1])
+def test_small_config_whole_path(pa, gpu_device, name, seed):
+    """match -> extend -> append on the reduced configs, every output element against the oracle."""
+    say(f"[case] small {name} seed={seed}")
+    wl = W.small_variant(name, seed)
+    g, o = GpuSide(wl, gpu_device), OracleSide(wl)
+    pl, si, out = g.step()
+    torch.cuda.synchronize()
+    pl_ref, si_ref = o.match()
+    assert_match_equal(wl, pl, si, pl_ref, si_ref)
+    np.testing.assert_array_equal(pl_ref, wl.designed_prefix_len)
+    ref = o.extend(pl_ref, si_ref)
+    err = np.abs(out_to_f64(out) - ref).max()
+    say(f"  max abs err {err:.3e}")
+    assert err <= TOL[wl.dtype]
+    # the appended rows must read back bit-exactly and leave the prefix rows alone
+    o.append()
+    allslots = np.concatenate([wl.pool_slots, wl.new_slots])
+    gk, gv = pa.gather_kv(g.pool, torch.from_numpy(allslots).to(gpu_device), Hkv=wl.Hkv, D=wl.D, dtype=g.tdtype, **g.kw)
+    view = torch.int32 if wl.dtype == "f32" else torch.int16
+    npview = np.int32 if wl.dtype == "f32" else np.int16
+    np.testing.assert_array_equal(gk.view(view).cpu().numpy(), o.pool_k[allslots].view(npview))
+    np.testing.assert_array_equal(gv.view(view).cpu().numpy(), o.pool_v[allslots].view(npview))
+
+
+def _random_case(rng, B, Hq, Hkv, D, p_hi, e_hi, dtype, page, nslots):
+    """Requests with independent random prefixes (slots: whole random pages each) and extends, incl. P=0."""
+    from paper_2407_00023_amd.workloads import _normal
+    P = rng.integers(0, p_hi + 1, B).astype(np.int32)
+    E = rng.integers(0, e_hi + 1, B).astype(np.int32)
+    P[0], E[-1] = 0, max(1, E[-1])
+    if B > 2:
+        E[1] = 0
+    pages = rng.permutation(nslots // page)
+    cur, slots = 0, []
+    for r in range(B):
+        npg = (P[r] + page - 1) // page
+        t = np.arange(P[r])
+        slots.append((pages[cur:cur + npg][t // page] * page + t % page).astype(np.int32) if P[r] else np.zeros(0, np.int32))
+        cur += npg
+    off = np.zeros(B + 1, np.int32)
+    off[1:] = np.cumsum(P + E)
+    si = np.full(off[-1], -1, np.int32)
+    for r in range(B):
+        si[off[r]:off[r] + P[r]] = slots[r]
+    eo = np.zeros(B + 1, np.int32)
+    eo[1:] = np.cumsum(E)
+    T = int(eo[-1])
+    ss = np.random.SeedSequence(int(rng.integers(1 << 30))).spawn(5)
+    backed = np.concatenate(slots) if B else np.zeros(0, np.int32)
+    mk = lambda s, n, h: _normal(s, n * h * D, dtype).reshape(n, h, D)
+    return dict(P=P, E=E, off=off, si=si, eo=eo, T=T, backed=backed, q=mk(ss[0], T, Hq), k=mk(ss[1], T, Hkv),
+                v=mk(ss[2], T, Hkv), pk=mk(ss[3], len(backed), Hkv), pv=mk(ss[4], len(backed), Hkv))
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,D,page,p_hi,e_hi,B", [
+    ("f32", 4, 2, 64, 1, 150, 40, 5),
+    ("f32", 2, 1, 128, 4, 70, 20, 3),
+    ("bf16", 8, 2, 128, 16, 700, 90, 6),     # several key tiles, ragged tails, packed rows > 128
+    ("bf16", 4, 4, 64, 16, 300, 200, 4),     # G = 1, D = 64
+    ("bf16", 16, 2, 128, 1, 200, 33, 4),     # G = 8, page size 1
+    ("bf16", 8, 8, 128, 16, 5000, 10, 3),    # long prefix, short extend: split path
+])
+def test_extend_random_shapes(pa, gpu_device, dtype, Hq, Hkv, D, page, p_hi, e_hi, B):
+    """Ragged prefixes and extends including prefix_len = 0 and ext_len = 0 requests."""
+    import oracle
+    say(f"[case] extend_random {dtype} Hq={Hq} Hkv={Hkv} D={D} page={page} p_hi={p_hi} e_hi={e_hi}")
+    rng = np.random.default_rng(11)
+    nslots = 16384
+    c = _random_case(rng, B, Hq, Hkv, D, p_hi, e_hi, dtype, page, nslots)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    dev = gpu_device
+    pool = torch.zeros(pa.kv_pool_bytes(nslots, Hkv, D, tdt, page), dtype=torch.uint8, device=dev)
+    kw = dict(page_size=page, num_slots=nslots)
+    pa.append_kv(pool, torch.from_numpy(c["backed"]).to(dev), to_torch(c["pk"], dtype, dev), to_torch(c["pv"], dtype, dev), **kw)
+    tt = lambda a: torch.from_numpy(a).to(dev)
+    scale = 1.0 / np.sqrt(D)
+    out = pa.extend_attention(to_torch(c["q"], dtype, dev), to_torch(c["k"], dtype, dev), to_torch(c["v"], dtype, dev), pool,
+                              tt(c["si"]), tt(c["off"]), tt(c["P"]), tt(c["E"]), tt(c["eo"]), scale,
+                              max_kv_len=int((c["P"] + c["E"]).max()), **kw)
+    torch.cuda.synchronize()
+    opk, opv = oracle.new_pool(nslots, Hkv, D, dtype)
+    oracle.append_kv(opk, opv, c["backed"], c["pk"], c["pv"], dtype)
+    ref = oracle.extend_attention(c["q"], c["k"], c["v"], opk, opv, c["si"], c["off"], c["P"], c["E"], c["eo"], scale, dtype)
+    err = np.abs(out_to_f64(out) - ref).max() if c["T"] else 0.0
+    say(f"  max abs err {err:.3e}")
+    assert err <= TOL[dtype]
+
+
+def test_extend_slot_permutation_invariance(pa, gpu_device):
+    """Moving the cached rows to other slots (and renaming slot_idx accordingly) must not change a single bit."""
+    wl = W.small_variant("tool_use", 3)
+    g = GpuSide(wl, gpu_device)
+    pl, si = g.match()
+    out1 = g.extend(pl, si).clone()
+    rng = np.random.default_rng(0)
+    remap = rng.permutation(wl.num_slots).astype(np.int32)
+    pool2 = torch.zeros_like(g.pool)
+    g.pa.append_kv(pool2, torch.from_numpy(remap[wl.pool_slots]).to(gpu_device), to_torch(wl.pool_k, wl.dtype, gpu_device),
+                   to_torch(wl.pool_v, wl.dtype, gpu_device), **g.kw)
+    si2 = torch.from_numpy(remap).to(gpu_device)[si.clamp(0, wl.num_slots - 1).long()].to(torch.int32)
+    out2 = g.pa.extend_attention(g.q, g.k, g.v, pool2, si2, g.offsets, pl, g.ext_len, g.ext_offsets, wl.scale,
+                                 max_kv_len=g.max_kv_len, **g.kw)
+    torch.cuda.synchronize()
+    assert torch.equal(out1.view(torch.int16), out2.view(torch.int16))
+
+
+# ------------------------------------------------------------------------------------ full configs
+
+@pytest.fixture(scope="module")
+def full_cache():
+    return {}
+
+
+def _full(name, device, cache):
+    if name not in cache:
+        cache.clear()  # one full config resident at a time
+        wl = W.CONFIGS[name]()
+        cache[name] = (wl, GpuSide(wl, device), OracleSide(wl))
+    return cache[name]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_config_match_bit_exact(pa, gpu_device, full_cache, name):
+    say(f"[case] full match {name}")
+    wl, g, o = _full(name, gpu_device, full_cache)
+    pl, si = g.match()
+    torch.cuda.synchronize()
+    pl_ref, si_ref = o.match()
+    assert_match_equal(wl, pl, si, pl_ref, si_ref)
+    np.testing.assert_array_equal(pl_ref, wl.designed_prefix_len)
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_config_extend_sampled_rows(pa, gpu_device, full_cache, name):
+    """Full sizes, in the launch configuration the benchmark times: sampled output rows against the oracle,
+    plus a property that holds at any size (every output element lies inside the range of the visible V)."""
+    say(f"[case] full extend {name}")
+    wl, g, o = _full(name, gpu_device, full_cache)
+    pl, si = g.match()
+    out = g.extend(pl, si)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    pl_ref, si_ref = o.match()
+    rows = sample_rows(wl, 192 if name != "agent_tree" else 384, seed=1)
+    ref = o.extend(pl_ref, si_ref, rows=rows)
+    outn = out_to_f64(out)
+    got = np.stack([outn[wl.ext_offsets[r] + i, h] for r, i, h in rows])
+    err = np.abs(got - ref).max()
+    say(f"  max abs err over {len(rows)} rows: {err:.3e}")
+    assert err <= TOL[wl.dtype]
+    # softmax weights are a convex combination: |out| can never exceed the largest |V| in the inputs
+    vmax = max(float(np.abs(W.bf16_bits_to_f32(wl.pool_v)).max()), float(np.abs(W.bf16_bits_to_f32(wl.v_ext)).max()))
+    assert float(out.float().abs().max()) <= vmax * (1 + 2 ** -7)
+
+
+def test_full_config_append_then_reuse(pa, gpu_device, full_cache):
+    """After append_kv the new tokens are cached: re-running a request whose whole prompt is now the prefix
+    of a longer one gives the same attention rows for the old positions (prefix reuse is lossless, Sec. 5)."""
+    wl = W.small_variant("agent_tree", 4)
+    g, o = GpuSide(wl, gpu_device), OracleSide(wl)
+    pl, si, out = g.step()
+    # second turn: every request's prompt is now fully cached under new_slots; extend = last 7 tokens of the old extend
+    P2 = (wl.designed_prefix_len + wl.ext_len - 7).astype(np.int32)
+    E2 = np.full(wl.B, 7, np.int32)
+    si2 = np.full_like(wl.tokens, -1)
+    rows_q = []
+    for r in range(wl.B):
+        lo, e0, Pd, E = int(wl.offsets[r]), int(wl.ext_offsets[r]), int(wl.designed_prefix_len[r]), int(wl.ext_len[r])
+        si2[lo:lo + Pd] = wl.designed_slots[lo:lo + Pd]
+        si2[lo + Pd:lo + Pd + E - 7] = wl.new_slots[e0:e0 + E - 7]
+        rows_q.append(np.arange(e0 + E - 7, e0 + E))
+    rows_q = np.concatenate(rows_q)
+    eo2 = np.arange(0, 7 * wl.B + 1, 7, dtype=np.int32)
+    dev = gpu_device
+    tt = lambda a: torch.from_numpy(a).to(dev)
+    idx = tt(rows_q).long()
+    out2 = g.pa.extend_attention(g.q[idx].contiguous(), g.k[idx].contiguous(), g.v[idx].contiguous(), g.pool, tt(si2),
+                                 g.offsets, tt(P2), tt(E2), tt(eo2), wl.scale, max_kv_len=g.max_kv_len, **g.kw)
+    torch.cuda.synchronize()
+    ref = o.extend(*o.match())
+    err = np.abs(out_to_f64(out2) - ref[rows_q]).max()
+    say(f"  reuse max abs err {err:.3e}")
+    assert err <= TOL[wl.dtype]
