@@ -27,6 +27,7 @@ namespace pa {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 constexpr int kMT = 128;  // packed query rows per workgroup (4 waves x 32)
 constexpr int kKT = 64;   // key tokens per tile
@@ -125,8 +126,38 @@ __device__ __forceinline__ void split_range(int kv_end, int chunk, int nsplit, i
     hi = (s == n_act - 1) ? kv_end : min(kv_end, (s + 1) * chunk);
 }
 
+// XOR swizzles of the 16-byte chunks of a K/V row in LDS, chosen so that the two read patterns below are
+// free of bank conflicts for 256-byte rows: K is read 16 bytes per lane down 16 consecutive rows, V is
+// read 8 bytes per lane across 64 bytes of 4 consecutive rows (the transposing LDS read).
 template <int D>
-__global__ __launch_bounds__(kThreads) void extend_bf16_kernel(
+__device__ __forceinline__ int swz_k(int row) {
+    return D == 128 ? (row & 15) : ((row >> 1) & 7);
+}
+template <int D>
+__device__ __forceinline__ int swz_v(int row) {
+    return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+}
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+// Transposing LDS read (ds_read_b64_tr_b16).  Within each group of 16 lanes the 16 x 4 16-bit values
+// addressed by the lanes form a flat array F (lane-major); lane i of the group receives F[i], F[16+i],
+// F[32+i], F[48+i].
+__device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (lds_s16x4*)(__attribute__((address_space(3))) unsigned char*)(p));
+}
+
+__device__ __forceinline__ float swap32(float x) {
+    // value of the lane 32 away (the other half of the same query row)
+    return __shfl_xor(x, 32);
+}
+
+constexpr float kRescaleThreshold = 8.f;  // log2 units: the running maximum may lag the true one by this much
+
+template <int D>
+__global__ __launch_bounds__(kThreads, 2) void extend_bf16_kernel(
     const __hip_bfloat16* __restrict__ q_ext, const __hip_bfloat16* __restrict__ k_ext,
     const __hip_bfloat16* __restrict__ v_ext, const __hip_bfloat16* __restrict__ pool,
     const int32_t* __restrict__ slot_idx, const int32_t* __restrict__ slot_offsets,
@@ -135,16 +166,20 @@ __global__ __launch_bounds__(kThreads) void extend_bf16_kernel(
     __hip_bfloat16* __restrict__ out, const int32_t* __restrict__ n_tiles, const int32_t* __restrict__ tile_req,
     const int32_t* __restrict__ tile_row0, int nsplit, int chunk, float* __restrict__ part_o,
     float* __restrict__ part_ml) {
-    constexpr int NB = D / 32;       // MFMA row blocks of the head dimension in O^T
-    constexpr int KS = D / 16;       // k-slices of the QK^T product
-    constexpr int CPR = D / 8;       // 16-byte chunks per K/V row
-    constexpr int ROWB = D * 2;      // bytes per row
-    __shared__ __attribute__((aligned(16))) unsigned char s_k[kKT * ROWB];
-    __shared__ __attribute__((aligned(16))) unsigned char s_v[kKT * ROWB];
+    constexpr int NB = D / 32;               // MFMA row blocks of the head dimension in O^T
+    constexpr int KS = D / 16;               // k-slices of the QK^T product
+    constexpr int CPR = D / 8;               // 16-byte chunks per K/V row
+    constexpr int ROWB = D * 2;              // bytes per row
+    constexpr int TILEB = kKT * ROWB;        // bytes of one K (or V) tile
+    constexpr int U = kKT * CPR / kThreads;  // 16-byte chunks each thread stages per tile and tensor
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2 buffers][K tile | V tile]
 
-    const int t = blockIdx.x / nsplit;
-    const int sp = blockIdx.x - t * nsplit;
-    const int g = blockIdx.y;
+    // block -> (row tile, key split, kv head); the kv head varies fastest so that with 8 kv heads every
+    // XCD (blocks are dealt round-robin to the 8 XCDs) serves one head and keeps its shared prefixes in L2
+    const int g = blockIdx.x % Hkv;
+    const int ts = blockIdx.x / Hkv;
+    const int t = ts / nsplit;
+    const int sp = ts - t * nsplit;
     if (t >= *n_tiles) return;
     const int r = tile_req[t];
     const int row0 = tile_row0[t];
@@ -171,7 +206,10 @@ __global__ __launch_bounds__(kThreads) void extend_bf16_kernel(
     const int qi = row_ok ? rho / G : 0;            // extend index of the row
     const int qh = g * G + (row_ok ? rho % G : 0);  // query head
     const bool wave_on = wave * 32 < rows_here;
+    const int wave_i_first = (row0 + wave * 32) / G;
     const int wave_i_last = (row0 + min(rows_here, wave * 32 + 32) - 1) / G;
+    const int wave_vis_min = min(kv_hi, P + wave_i_first + 1);  // every row of the wave sees keys [.., this)
+    const int vis_end = min(kv_hi, P + qi + 1);                 // keys [.., vis_end) are visible to this row
 
     bf16x8 qreg[KS];
     {
@@ -184,160 +222,188 @@ __global__ __launch_bounds__(kThreads) void extend_bf16_kernel(
         }
     }
 
+    // ---- staging of one K/V tile: thread -> U (row, 16-byte column) pairs per tensor ----
+    const int st_col = tid % CPR;
+    const int st_row = tid / CPR;            // + u * (kThreads / CPR)
+    constexpr int ST_ROWS = kThreads / CPR;  // rows covered per u
+    uint4 st_k[U], st_v[U];
+    int32_t sl_next[U];                      // pool slots of the tile after the staged one
+
+    auto load_slots = [&](int p0) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int p = p0 + st_row + u * ST_ROWS;
+            sl_next[u] = (p < P && p < kv_hi) ? slots[p] : 0;
+        }
+    };
+    auto issue_loads = [&](int p0) {  // consumes sl_next (slots of tile p0)
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int p = p0 + st_row + u * ST_ROWS;
+            uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+            if (p < kv_hi) {
+                if (p < P) {
+                    int64_t sl = sl_next[u];
+                    sl = sl < 0 ? 0 : (sl >= num_slots ? num_slots - 1 : sl);
+                    kk = reinterpret_cast<const uint4*>(pool + pool_row(sl, 0, g, Hkv, D, page_size))[st_col];
+                    vv = reinterpret_cast<const uint4*>(pool + pool_row(sl, 1, g, Hkv, D, page_size))[st_col];
+                } else {
+                    const int64_t off = ((e0 + (p - P)) * Hkv + g) * static_cast<int64_t>(D);
+                    kk = reinterpret_cast<const uint4*>(k_ext + off)[st_col];
+                    vv = reinterpret_cast<const uint4*>(v_ext + off)[st_col];
+                }
+            }
+            st_k[u] = kk;
+            st_v[u] = vv;
+        }
+    };
+    auto write_stage = [&](int buf) {
+        unsigned char* sk = smem + buf * 2 * TILEB;
+        unsigned char* sv = sk + TILEB;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int row = st_row + u * ST_ROWS;
+            *reinterpret_cast<uint4*>(sk + row * ROWB + ((st_col ^ swz_k<D>(row)) * 16)) = st_k[u];
+            *reinterpret_cast<uint4*>(sv + row * ROWB + ((st_col ^ swz_v<D>(row)) * 16)) = st_v[u];
+        }
+    };
+
     f32x16 oacc[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[b][i] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;  // running maximum (scaled, log2 domain) and this lane's share of the sum
 
-    for (int p0 = kv_lo; p0 < kv_hi; p0 += kKT) {
-        // ---- gather the K and V tiles into LDS (row-major, 16-byte chunks XOR-swizzled by row) ----
-        __syncthreads();  // previous tile fully consumed
+    // lane constants of the transposing V read: group lane i = 4 * e + c reads key row (4 * hh + e) + ..., and
+    // 8 bytes at head-dim offset 32 * b + 16 * par + 4 * c
+    const int tr_e = (lane >> 2) & 3, tr_c = lane & 3, tr_par = (lane >> 4) & 1;
+    const bf16x2_t ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+
+    // ---- prologue: first tile into buffer 0 ----
+    load_slots(kv_lo);
+    issue_loads(kv_lo);
+    load_slots(kv_lo + kKT);
+    write_stage(0);
+    __syncthreads();
+
+    int buf = 0;
+    for (int p0 = kv_lo; p0 < kv_hi; p0 += kKT, buf ^= 1) {
+        const bool more = p0 + kKT < kv_hi;
+        if (more) {
+            issue_loads(p0 + kKT);       // global loads of the next tile fly during this tile's arithmetic
+            load_slots(p0 + 2 * kKT);
+        }
+        if (wave_on && p0 <= P + wave_i_last) {
+            const unsigned char* sk = smem + buf * 2 * TILEB;
+            const unsigned char* sv = sk + TILEB;
+            // ---- S^T = K Q^T for two blocks of 32 keys ----
+            f32x16 sacc[2];
 #pragma unroll
-        for (int u = 0; u < kKT * CPR / kThreads; ++u) {
-            const int c = tid + u * kThreads;
-            const int row = c / CPR, col = c % CPR;
-            const int p = p0 + row;
-            uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-            if (p < kv_hi) {
-                if (p < P) {
-                    int64_t sl = slots[p];
-                    sl = sl < 0 ? 0 : (sl >= num_slots ? num_slots - 1 : sl);
-                    kk = reinterpret_cast<const uint4*>(pool + pool_row(sl, 0, g, Hkv, D, page_size))[col];
-                    vv = reinterpret_cast<const uint4*>(pool + pool_row(sl, 1, g, Hkv, D, page_size))[col];
-                } else {
-                    const int64_t off = ((e0 + (p - P)) * Hkv + g) * static_cast<int64_t>(D);
-                    kk = reinterpret_cast<const uint4*>(k_ext + off)[col];
-                    vv = reinterpret_cast<const uint4*>(v_ext + off)[col];
+            for (int mb = 0; mb < 2; ++mb) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sacc[mb][i] = 0.f;
+                const int krow = mb * 32 + n;
+#pragma unroll
+                for (int s = 0; s < KS; ++s) {
+                    const int pos = (2 * s + hh) ^ swz_k<D>(krow);
+                    const uint4 kv = *reinterpret_cast<const uint4*>(sk + krow * ROWB + pos * 16);
+                    sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv), qreg[s], sacc[mb], 0, 0, 0);
                 }
             }
-            const int pos = col ^ (row & (CPR - 1));
-            *reinterpret_cast<uint4*>(s_k + row * ROWB + pos * 16) = kk;
-            *reinterpret_cast<uint4*>(s_v + row * ROWB + pos * 16) = vv;
+
+            // ---- mask (only where the tile crosses a visibility limit), row maximum ----
+            if (p0 + kKT > wave_vis_min) {
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int p = p0 + mb * 32 + 8 * (i / 4) + 4 * hh + (i % 4);
+                        if (p >= vis_end) sacc[mb][i] = -INFINITY;
+                    }
+            }
+            float mx = fmaxf(sacc[0][0], sacc[1][0]);
+#pragma unroll
+            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, fmaxf(sacc[0][i], sacc[1][i]));
+            mx = fmaxf(mx, swap32(mx));
+            const float m_tile = mx * scale_log2e;
+            // The running maximum is only raised when some row of the wave outgrows it by the threshold;
+            // until then probabilities are formed against the older, smaller maximum (they stay <= 2^threshold).
+            if (__any(m_tile > m_run + kRescaleThreshold)) {
+                const float m_new = fmaxf(m_run, m_tile);
+                const float alpha = __builtin_amdgcn_exp2f(m_run - ((m_new == -INFINITY) ? 0.f : m_new));
+                l_run *= alpha;
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
+                m_run = m_new;
+            }
+            const float neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
+            uint32_t pb[2][8];  // probabilities as packed bf16 pairs: the B operand of the second product
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; i += 2) {
+                    const float a = __builtin_amdgcn_exp2f(fmaf(sacc[mb][i], scale_log2e, neg_m));
+                    const float b = __builtin_amdgcn_exp2f(fmaf(sacc[mb][i + 1], scale_log2e, neg_m));
+                    const uint32_t pk = pack_bf16x2(a, b);
+                    pb[mb][i / 2] = pk;
+                    // the denominator sums the rounded probabilities, the same values the numerator uses
+                    l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk), ones, l_run, false);
+                }
+
+            // ---- O^T += V^T P^T, 16 keys per MFMA; V^T fragments come from the transposing LDS read ----
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int cs = 0; cs < 2; ++cs) {
+                    const uint4 pv4 = make_uint4(pb[mb][cs * 4 + 0], pb[mb][cs * 4 + 1], pb[mb][cs * 4 + 2], pb[mb][cs * 4 + 3]);
+                    const bf16x8 pop = __builtin_bit_cast(bf16x8, pv4);
+#pragma unroll
+                    for (int b = 0; b < NB; ++b) {
+                        s16x4 frag[2];
+#pragma unroll
+                        for (int h2 = 0; h2 < 2; ++h2) {
+                            const int vrow = mb * 32 + cs * 16 + 8 * h2 + 4 * hh + tr_e;
+                            const int chunk = 4 * b + 2 * tr_par + (tr_c >> 1);
+                            frag[h2] = lds_read_tr16(sv + vrow * ROWB + ((chunk ^ swz_v<D>(vrow)) * 16) + (tr_c & 1) * 8);
+                        }
+                        typedef short s16x8 __attribute__((ext_vector_type(8)));
+                        const s16x8 a8 = __builtin_shufflevector(frag[0], frag[1], 0, 1, 2, 3, 4, 5, 6, 7);
+                        oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pop, oacc[b], 0, 0, 0);
+                    }
+                }
         }
+        if (more) write_stage(buf ^ 1);
         __syncthreads();
-        if (!wave_on || p0 > P + wave_i_last) continue;  // nothing visible to this wave in the tile
-
-        // ---- S^T = K Q^T for two blocks of 32 tokens ----
-        f32x16 sacc[2];
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sacc[mb][i] = 0.f;
-            const int krow = mb * 32 + n;
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                const int pos = (2 * s + hh) ^ (krow & (CPR - 1));
-                const uint4 kv = *reinterpret_cast<const uint4*>(s_k + krow * ROWB + pos * 16);
-                sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv), qreg[s], sacc[mb], 0, 0, 0);
-            }
-        }
-
-        // ---- scale, mask, online softmax (per lane: one query row, 32 of the 64 tokens) ----
-        const bool need_mask = (p0 + kKT > P) || (p0 + kKT > kv_hi);
-        const int vis_end = min(kv_hi, P + qi + 1);  // keys [.., vis_end) are visible to this row
-        float mx = -INFINITY;
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float s = sacc[mb][i] * scale_log2e;
-                if (need_mask) {
-                    const int p = p0 + mb * 32 + 8 * (i / 4) + 4 * hh + (i % 4);
-                    if (p >= vis_end) s = -INFINITY;
-                }
-                sacc[mb][i] = s;
-                mx = fmaxf(mx, s);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;  // row with nothing visible yet
-        const float alpha = exp2f(m_run - m_use);
-        float psum = 0.f;
-        uint32_t pb[2][8];  // probabilities as packed bf16 pairs: the B operand of the second product
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int i = 0; i < 16; i += 2) {
-                const float a = exp2f(sacc[mb][i] - m_use);
-                const float b = exp2f(sacc[mb][i + 1] - m_use);
-                psum += a + b;
-                pb[mb][i / 2] = pack_bf16x2(a, b);
-            }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
-#pragma unroll
-        for (int b = 0; b < NB; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
-
-        // ---- O^T += V^T P^T, 16 tokens per MFMA ----
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int cs = 0; cs < 2; ++cs) {
-                // token of operand element j: base + 8 * (j / 4) + 4 * hh + (j % 4)
-                const int tb = mb * 32 + cs * 16 + 4 * hh;
-                uint32_t x[8][NB / 2];  // row tok(j): head-dim elements NB * n .. NB * n + NB - 1
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int vrow = tb + 8 * (j / 4) + (j % 4);
-                    const int byte = n * NB * 2;  // offset inside the row before swizzling
-                    const int pos = (byte / 16) ^ (vrow & (CPR - 1));
-                    const unsigned char* src = s_v + vrow * ROWB + pos * 16 + (byte % 16);
-                    if constexpr (NB == 4) {
-                        const uint2 v = *reinterpret_cast<const uint2*>(src);
-                        x[j][0] = v.x;
-                        x[j][1] = v.y;
-                    } else {
-                        x[j][0] = *reinterpret_cast<const uint32_t*>(src);
-                    }
-                }
-                uint4 pv4 = make_uint4(pb[mb][cs * 4 + 0], pb[mb][cs * 4 + 1], pb[mb][cs * 4 + 2], pb[mb][cs * 4 + 3]);
-                const bf16x8 pop = __builtin_bit_cast(bf16x8, pv4);
-#pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    uint32_t w[4];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const uint32_t lo = x[2 * q][b / 2], hi = x[2 * q + 1][b / 2];
-                        w[q] = (b & 1) ? ((lo >> 16) | (hi & 0xFFFF0000u)) : ((lo & 0xFFFFu) | (hi << 16));
-                    }
-                    const uint4 a4 = make_uint4(w[0], w[1], w[2], w[3]);
-                    oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a4), pop, oacc[b], 0, 0, 0);
-                }
-            }
     }
 
-    // ---- epilogue ----
-    l_run += __shfl_xor(l_run, 32);
+    // ---- epilogue: lane holds, for block b and register i, head-dim element 32 b + 8 (i / 4) + 4 hh + i % 4 ----
+    l_run += swap32(l_run);
     if (!row_ok) return;
     if (n_act == 1) {
         const float inv = 1.f / l_run;
         __hip_bfloat16* orow = out + ((e0 + qi) * Hq + qh) * static_cast<int64_t>(D);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int mrow = 8 * (i / 4) + 4 * hh + (i % 4);
-            if constexpr (NB == 4) {
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
                 uint2 v;
-                v.x = pack_bf16x2(oacc[0][i] * inv, oacc[1][i] * inv);
-                v.y = pack_bf16x2(oacc[2][i] * inv, oacc[3][i] * inv);
-                *reinterpret_cast<uint2*>(orow + NB * mrow) = v;
-            } else {
-                *reinterpret_cast<uint32_t*>(orow + NB * mrow) = pack_bf16x2(oacc[0][i] * inv, oacc[1][i] * inv);
+                v.x = pack_bf16x2(oacc[b][4 * q4 + 0] * inv, oacc[b][4 * q4 + 1] * inv);
+                v.y = pack_bf16x2(oacc[b][4 * q4 + 2] * inv, oacc[b][4 * q4 + 3] * inv);
+                *reinterpret_cast<uint2*>(orow + 32 * b + 8 * q4 + 4 * hh) = v;
             }
-        }
     } else {
         const size_t unit = (static_cast<size_t>(t) * nsplit + sp) * Hkv + g;
         const int lrow = wave * 32 + n;
         float* prow = part_o + (unit * kMT + lrow) * D;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int mrow = 8 * (i / 4) + 4 * hh + (i % 4);
+        for (int b = 0; b < NB; ++b)
 #pragma unroll
-            for (int b = 0; b < NB; ++b) prow[NB * mrow + b] = oacc[b][i];
-        }
+            for (int q4 = 0; q4 < 4; ++q4)
+                *reinterpret_cast<float4*>(prow + 32 * b + 8 * q4 + 4 * hh) =
+                    make_float4(oacc[b][4 * q4 + 0], oacc[b][4 * q4 + 1], oacc[b][4 * q4 + 2], oacc[b][4 * q4 + 3]);
         if (hh == 0) {
             part_ml[(unit * kMT + lrow) * 2 + 0] = m_run;
             part_ml[(unit * kMT + lrow) * 2 + 1] = l_run;
@@ -426,13 +492,14 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
         hipLaunchKernelGGL(extend_tiles_kernel, dim3(1), dim3(256), 0, stream, ext_len, B, G, p.tiles_cap, n_tiles,
                            tile_req, tile_row0);
     }
-    const dim3 grid(static_cast<unsigned>(p.tiles_cap) * p.nsplit, Hkv);
+    const dim3 grid(static_cast<unsigned>(p.tiles_cap) * p.nsplit * Hkv);
+    const size_t lds_bytes = 2u * 2u * kKT * D * 2u;  // two buffers of one K tile and one V tile
     const dim3 mgrid(p.tiles_cap, Hkv);
 #define PA_LAUNCH_BF16(DD)                                                                                           \
     do {                                                                                                             \
         {                                                                                                            \
         ProfScope prof(kProfExtend, stream);                                                                         \
-        hipLaunchKernelGGL(extend_bf16_kernel<DD>, grid, dim3(kThreads), 0, stream,                                  \
+        hipLaunchKernelGGL(extend_bf16_kernel<DD>, grid, dim3(kThreads), lds_bytes, stream,                                 \
                            static_cast<const __hip_bfloat16*>(q_ext), static_cast<const __hip_bfloat16*>(k_ext),     \
                            static_cast<const __hip_bfloat16*>(v_ext), static_cast<const __hip_bfloat16*>(kv_pool),   \
                            slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots,  \
