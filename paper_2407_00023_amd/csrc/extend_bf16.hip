@@ -7,35 +7,46 @@
 //
 // Decomposition.  The G = Hq/Hkv query heads of one KV head are packed with the extend
 // rows into one row axis rho = i * G + (h mod G), so a K/V tile is read once per KV head.
-// A workgroup (4 waves) owns kMT = 128 packed rows of one (request, KV head) and walks
-// the key axis in tiles of kKT = 64 tokens: prefix positions first, then the extend
-// tokens (the same loop; only the row address differs).  Optionally the key axis is cut
-// into `nsplit` chunks handled by different workgroups, merged by a second kernel.
+// A workgroup of NW waves owns 32 * NW packed rows of one (request, KV head) and walks the
+// key axis in tiles of kKT = 64 tokens: prefix positions first, then the extend tokens
+// (the same loop; only the row address differs).  Optionally the key axis is cut into
+// `nsplit` chunks handled by different workgroups, merged by a second kernel.
+//
+// Data movement.  K and V tiles go from global memory straight into LDS (16 bytes per
+// lane, no register staging), one tile ahead of the arithmetic, into a ring of LDS
+// buffers.  A wave's load lands as 1 KB of consecutive LDS bytes, so the bank-conflict
+// swizzle is applied on the global-address side: the lane that owns LDS chunk c of a row
+// fetches the row's chunk c ^ swizzle(row).
 //
 // MFMA formulation.  Scores are produced TRANSPOSED, S^T = K * Q^T, so that in the
 // accumulator layout every lane holds one query row (column l % 32) and 16 of the 32
-// tokens of a block: row statistics of the online softmax are per-lane scalars plus one
+// keys of a block: row statistics of the online softmax are per-lane scalars plus one
 // exchange between lane l and l ^ 32, and the probabilities are already laid out as the
-// B operand of the second product O^T = V^T * P^T.  V^T rows are formed from row-major V
-// in LDS by reading 4 head-dim elements of 8 tokens and transposing 2-byte lanes in
-// registers; head-dim element d = 4 * m + b belongs to row m of MFMA block b.
+// B operand of the second product O^T = V^T * P^T.  The V^T fragments are read from the
+// row-major V tile with the transposing LDS read of gfx950.
 #include <hip/hip_bf16.h>
+
+#include <type_traits>
 
 #include "common.h"
 
 namespace pa {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-constexpr int kMT = 128;  // packed query rows per workgroup (4 waves x 32)
-constexpr int kKT = 64;   // key tokens per tile
-constexpr int kThreads = 256;
+constexpr int kKT = 64;                  // key tokens per tile
+constexpr int kStages = 2;               // LDS ring: one tile being read, one being filled
 constexpr int kTargetWorkgroups = 1024;  // split the key axis until about this many workgroups exist
 constexpr int kMinChunk = 512;           // never split below this many keys per chunk
+constexpr float kRescaleThreshold = 8.f; // log2 units: the running maximum may lag the true one by this much
 
 struct ExtendPlan {
+    int nw;          // waves per workgroup (4 or 8); a row tile has 32 * nw packed rows
     int tiles_cap;   // upper bound on the number of (request, row tile) pairs
     int nsplit;      // chunks of the key axis
     int chunk;       // keys per chunk (multiple of kKT)
@@ -47,7 +58,9 @@ static inline size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
 static ExtendPlan make_plan(int B, int64_t T, int64_t max_kv_len, int Hq, int Hkv, int D) {
     ExtendPlan p{};
     const int G = Hq / Hkv;
-    const int64_t est = (T * G + kMT - 1) / kMT;
+    p.nw = 4;
+    const int mt = 32 * p.nw;
+    const int64_t est = (T * G + mt - 1) / mt;
     p.tiles_cap = static_cast<int>(est + B);
     int64_t want = (kTargetWorkgroups + est * Hkv - 1) / (est * Hkv > 0 ? est * Hkv : 1);
     int64_t max_split = (max_kv_len + kMinChunk - 1) / kMinChunk;
@@ -64,15 +77,15 @@ static ExtendPlan make_plan(int B, int64_t T, int64_t max_kv_len, int Hq, int Hk
     p.off_row0 = p.off_req + up256(sizeof(int32_t) * p.tiles_cap);
     p.off_part_o = p.off_row0 + up256(sizeof(int32_t) * p.tiles_cap);
     const size_t units = p.nsplit > 1 ? static_cast<size_t>(p.tiles_cap) * p.nsplit * Hkv : 0;
-    p.off_part_ml = p.off_part_o + up256(units * kMT * D * sizeof(float));
-    p.total = p.off_part_ml + up256(units * kMT * 2 * sizeof(float));
+    p.off_part_ml = p.off_part_o + up256(units * mt * D * sizeof(float));
+    p.total = p.off_part_ml + up256(units * mt * 2 * sizeof(float));
     return p;
 }
 
 // ---------------------------------------------------------------------------------------
 // Row-tile table: tile t -> (request, first packed row).  One workgroup; block-wide scan.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void extend_tiles_kernel(const int32_t* __restrict__ ext_len, int B, int G,
+__global__ __launch_bounds__(256) void extend_tiles_kernel(const int32_t* __restrict__ ext_len, int B, int G, int mt,
                                                           int tiles_cap, int32_t* __restrict__ n_tiles,
                                                           int32_t* __restrict__ tile_req,
                                                           int32_t* __restrict__ tile_row0) {
@@ -86,7 +99,7 @@ __global__ __launch_bounds__(256) void extend_tiles_kernel(const int32_t* __rest
         int cnt = 0;
         if (r < B) {
             const int e = ext_len[r];
-            cnt = e > 0 ? (e * G + kMT - 1) / kMT : 0;
+            cnt = e > 0 ? (e * G + mt - 1) / mt : 0;
         }
         s_scan[tid] = cnt;
         __syncthreads();
@@ -100,7 +113,7 @@ __global__ __launch_bounds__(256) void extend_tiles_kernel(const int32_t* __rest
         for (int k = 0; k < cnt; ++k) {
             if (start + k < tiles_cap) {
                 tile_req[start + k] = r;
-                tile_row0[start + k] = k * kMT;
+                tile_row0[start + k] = k * mt;
             }
         }
         __syncthreads();
@@ -113,9 +126,8 @@ __global__ __launch_bounds__(256) void extend_tiles_kernel(const int32_t* __rest
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
     // round to nearest even; inputs are finite probabilities or outputs
     typedef float f32x2 __attribute__((ext_vector_type(2)));
-    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     f32x2 v = {a, b};
-    bf16x2 r = __builtin_convertvector(v, bf16x2);
+    bf16x2_t r = __builtin_convertvector(v, bf16x2_t);
     return __builtin_bit_cast(uint32_t, r);
 }
 
@@ -126,9 +138,9 @@ __device__ __forceinline__ void split_range(int kv_end, int chunk, int nsplit, i
     hi = (s == n_act - 1) ? kv_end : min(kv_end, (s + 1) * chunk);
 }
 
-// XOR swizzles of the 16-byte chunks of a K/V row in LDS, chosen so that the two read patterns below are
-// free of bank conflicts for 256-byte rows: K is read 16 bytes per lane down 16 consecutive rows, V is
-// read 8 bytes per lane across 64 bytes of 4 consecutive rows (the transposing LDS read).
+// XOR swizzles of the 16-byte chunks of a K/V row in LDS, chosen so that the two read patterns of the
+// arithmetic are free of bank conflicts for 256-byte rows: K is read 16 bytes per lane down 16
+// consecutive rows, V is read 8 bytes per lane across 64 bytes of 4 consecutive rows.
 template <int D>
 __device__ __forceinline__ int swz_k(int row) {
     return D == 128 ? (row & 15) : ((row >> 1) & 7);
@@ -138,41 +150,84 @@ __device__ __forceinline__ int swz_v(int row) {
     return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
 }
 
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-
 // Transposing LDS read (ds_read_b64_tr_b16).  Within each group of 16 lanes the 16 x 4 16-bit values
 // addressed by the lanes form a flat array F (lane-major); lane i of the group receives F[i], F[16+i],
 // F[32+i], F[48+i].
 __device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* p) {
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (lds_s16x4*)(__attribute__((address_space(3))) unsigned char*)(p));
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(__attribute__((address_space(3))) unsigned char*)(p));
 }
 
-__device__ __forceinline__ float swap32(float x) {
-    // value of the lane 32 away (the other half of the same query row)
-    return __shfl_xor(x, 32);
+// Both halves of a query row (lanes l and l ^ 32) combined, in every lane, without going through LDS.
+// v_permlane32_swap exchanges lanes 32..63 of its first operand with lanes 0..31 of its second: fed the
+// same value x twice it leaves (x of the low half, x of the high half) in every lane.  Written as
+// inline assembly (the compiler builtin folded its two results into one); the s_nop pairs cover the
+// wait states the instruction needs after a VALU write of its operands and before a VALU read of them.
+__device__ __forceinline__ void row_halves(float x, float& lo, float& hi) {
+    float a = x, b = x;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+    lo = a;
+    hi = b;
+}
+__device__ __forceinline__ float row_max(float x) {
+    float lo, hi;
+    row_halves(x, lo, hi);
+    return fmaxf(lo, hi);
+}
+__device__ __forceinline__ float row_sum(float x) {
+    float lo, hi;
+    row_halves(x, lo, hi);
+    return lo + hi;
 }
 
-constexpr float kRescaleThreshold = 8.f;  // log2 units: the running maximum may lag the true one by this much
+// Workgroup barrier without the memory fence of __syncthreads(): the fence would make the compiler wait
+// for every outstanding global->LDS load, including the ones meant to stay in flight.  Completion of
+// the loads that must be visible is awaited explicitly (wait_vm_all) before the barrier.
+__device__ __forceinline__ void wg_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+// s_waitcnt vmcnt(0) (expcnt and lgkmcnt left alone), as the builtin so that the compiler's own wait
+// bookkeeping sees it and does not repeat it later.
+__device__ __forceinline__ void wait_vm_all() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    asm volatile("" ::: "memory");
+}
 
-template <int D>
-__global__ __launch_bounds__(kThreads, 2) void extend_bf16_kernel(
+// Direct global -> LDS load of 16 bytes per lane: lane l of the wave writes LDS bytes
+// [lds_addr + 16 l, lds_addr + 16 l + 16) with the 16 bytes at its own global address g.  lds_addr is
+// wave-uniform.  Issued as inline assembly so that the compiler does not see an LDS store in flight: it
+// would otherwise wait for it before every later LDS read, and the load could not overlap the
+// arithmetic on the other ring slot.  The explicit wait_vm_all() + wg_barrier() order it instead.
+__device__ __forceinline__ void load_to_lds_16(const void* g, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory");
+}
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+    return static_cast<unsigned>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const unsigned char*)(p)));
+}
+
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64, 2) void extend_bf16_kernel(
     const __hip_bfloat16* __restrict__ q_ext, const __hip_bfloat16* __restrict__ k_ext,
     const __hip_bfloat16* __restrict__ v_ext, const __hip_bfloat16* __restrict__ pool,
     const int32_t* __restrict__ slot_idx, const int32_t* __restrict__ slot_offsets,
     const int32_t* __restrict__ prefix_len, const int32_t* __restrict__ ext_len,
-    const int32_t* __restrict__ ext_offsets, int Hq, int Hkv, int page_size, int64_t num_slots, float scale_log2e,
-    __hip_bfloat16* __restrict__ out, const int32_t* __restrict__ n_tiles, const int32_t* __restrict__ tile_req,
-    const int32_t* __restrict__ tile_row0, int nsplit, int chunk, float* __restrict__ part_o,
-    float* __restrict__ part_ml) {
+    const int32_t* __restrict__ ext_offsets, int Hq, int Hkv, int page_size, int page_shift, int num_slots,
+    float scale_log2e, __hip_bfloat16* __restrict__ out, const int32_t* __restrict__ n_tiles,
+    const int32_t* __restrict__ tile_req, const int32_t* __restrict__ tile_row0, int nsplit, int chunk,
+    float* __restrict__ part_o, float* __restrict__ part_ml) {
+    constexpr int MT = 32 * NW;              // packed query rows per workgroup
     constexpr int NB = D / 32;               // MFMA row blocks of the head dimension in O^T
     constexpr int KS = D / 16;               // k-slices of the QK^T product
     constexpr int CPR = D / 8;               // 16-byte chunks per K/V row
     constexpr int ROWB = D * 2;              // bytes per row
     constexpr int TILEB = kKT * ROWB;        // bytes of one K (or V) tile
-    constexpr int U = kKT * CPR / kThreads;  // 16-byte chunks each thread stages per tile and tensor
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2 buffers][K tile | V tile]
+    constexpr int STAGEB = 2 * TILEB;        // one ring slot: K tile, V tile
+    constexpr int RPB = 1024 / ROWB;         // rows per 1 KB block (what one wave-wide 16-byte load fills)
+    constexpr int UPW = kKT / RPB / NW;      // blocks per wave, tile and tensor
+    static_assert(UPW >= 1, "tile too small for this many waves");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [kStages][K tile | V tile]
 
     // block -> (row tile, key split, kv head); the kv head varies fastest so that with 8 kv heads every
     // XCD (blocks are dealt round-robin to the 8 XCDs) serves one head and keeps its shared prefixes in L2
@@ -187,7 +242,7 @@ __global__ __launch_bounds__(kThreads, 2) void extend_bf16_kernel(
     const int P = prefix_len[r];
     const int E = ext_len[r];
     const int rows_total = E * G;
-    const int rows_here = min(kMT, rows_total - row0);
+    const int rows_here = min(MT, rows_total - row0);
     const int i_last = (row0 + rows_here - 1) / G;
     const int kv_end = P + i_last + 1;
     int n_act, kv_lo, kv_hi;
@@ -195,7 +250,8 @@ __global__ __launch_bounds__(kThreads, 2) void extend_bf16_kernel(
     if (sp >= n_act) return;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, hh = lane >> 5;
     const int64_t e0 = ext_offsets[r];
     const int32_t* __restrict__ slots = slot_idx + slot_offsets[r];
@@ -222,50 +278,64 @@ __global__ __launch_bounds__(kThreads, 2) void extend_bf16_kernel(
         }
     }
 
-    // ---- staging of one K/V tile: thread -> U (row, 16-byte column) pairs per tensor ----
-    const int st_col = tid % CPR;
-    const int st_row = tid / CPR;            // + u * (kThreads / CPR)
-    constexpr int ST_ROWS = kThreads / CPR;  // rows covered per u
-    uint4 st_k[U], st_v[U];
-    int32_t sl_next[U];                      // pool slots of the tile after the staged one
+    // ---- global -> LDS tile loads.  Wave w fills blocks w * UPW + u: rows blk * RPB + lane / CPR, and the
+    // lane lands on chunk position lane % CPR of its row.
+    const int ld_pos = lane % CPR;
+    const int ld_rowl = lane / CPR;
+    const unsigned char* pool_g = reinterpret_cast<const unsigned char*>(pool) + static_cast<size_t>(g) * page_size * ROWB;
+    const size_t page_stride = static_cast<size_t>(2) * Hkv * page_size * ROWB;  // bytes from one page to the next
+    const size_t v_off = static_cast<size_t>(Hkv) * page_size * ROWB;            // from a K row to its V row
+    const unsigned char* kx_g = reinterpret_cast<const unsigned char*>(k_ext) + (e0 * Hkv + g) * static_cast<int64_t>(ROWB);
+    const unsigned char* vx_g = reinterpret_cast<const unsigned char*>(v_ext) + (e0 * Hkv + g) * static_cast<int64_t>(ROWB);
+    const size_t x_stride = static_cast<size_t>(Hkv) * ROWB;  // bytes from one extend token to the next
+    const unsigned smem_addr = __builtin_amdgcn_readfirstlane(lds_address(smem));
+    int32_t sl_next[UPW];  // pool slots of the rows this lane loads in the tile after the one in flight
 
     auto load_slots = [&](int p0) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int p = p0 + st_row + u * ST_ROWS;
-            sl_next[u] = (p < P && p < kv_hi) ? slots[p] : 0;
+        for (int u = 0; u < UPW; ++u) {
+            // positions past the end of the key range repeat the last valid one (see issue_tile)
+            const int p = min(p0 + (wave * UPW + u) * RPB + ld_rowl, kv_hi - 1);
+            sl_next[u] = p < P ? slots[p] : 0;
         }
     };
-    auto issue_loads = [&](int p0) {  // consumes sl_next (slots of tile p0)
+    auto pool_row_ptr = [&](int sl) -> const unsigned char* {
+        sl = min(max(sl, 0), num_slots - 1);  // a slot outside the pool must not fault
+        const unsigned page = page_shift >= 0 ? static_cast<unsigned>(sl) >> page_shift
+                                              : static_cast<unsigned>(sl) / static_cast<unsigned>(page_size);
+        const unsigned o = static_cast<unsigned>(sl) - page * static_cast<unsigned>(page_size);
+        return pool_g + page * page_stride + o * static_cast<unsigned>(ROWB);
+    };
+    // kPrefixOnly: every row of the tile is a prefix position below kv_hi (no clamping, no source select)
+    auto issue_tile = [&](int p0, int ring, auto prefix_only) {
+        constexpr bool kPrefixOnly = decltype(prefix_only)::value;
+        const unsigned sk = smem_addr + ring * STAGEB;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int p = p0 + st_row + u * ST_ROWS;
-            uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-            if (p < kv_hi) {
-                if (p < P) {
-                    int64_t sl = sl_next[u];
-                    sl = sl < 0 ? 0 : (sl >= num_slots ? num_slots - 1 : sl);
-                    kk = reinterpret_cast<const uint4*>(pool + pool_row(sl, 0, g, Hkv, D, page_size))[st_col];
-                    vv = reinterpret_cast<const uint4*>(pool + pool_row(sl, 1, g, Hkv, D, page_size))[st_col];
-                } else {
-                    const int64_t off = ((e0 + (p - P)) * Hkv + g) * static_cast<int64_t>(D);
-                    kk = reinterpret_cast<const uint4*>(k_ext + off)[st_col];
-                    vv = reinterpret_cast<const uint4*>(v_ext + off)[st_col];
-                }
+        for (int u = 0; u < UPW; ++u) {
+            const int blk = wave * UPW + u;
+            const int row = blk * RPB + ld_rowl;
+            const unsigned char *ka, *va;
+            if constexpr (kPrefixOnly) {
+                ka = pool_row_ptr(sl_next[u]);
+                va = ka + v_off;
+            } else {
+                // rows past the end of the key range repeat the last valid row: finite values that the mask zeroes
+                const int p = min(p0 + row, kv_hi - 1);
+                const unsigned char* kp = pool_row_ptr(sl_next[u]);
+                const size_t xo = static_cast<size_t>(max(p - P, 0)) * x_stride;
+                const bool in_pool = p < P;
+                ka = in_pool ? kp : kx_g + xo;
+                va = in_pool ? kp + v_off : vx_g + xo;
             }
-            st_k[u] = kk;
-            st_v[u] = vv;
+            ka += (ld_pos ^ swz_k<D>(row)) * 16;
+            va += (ld_pos ^ swz_v<D>(row)) * 16;
+            load_to_lds_16(ka, sk + blk * 1024);
+            load_to_lds_16(va, sk + TILEB + blk * 1024);
         }
     };
-    auto write_stage = [&](int buf) {
-        unsigned char* sk = smem + buf * 2 * TILEB;
-        unsigned char* sv = sk + TILEB;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int row = st_row + u * ST_ROWS;
-            *reinterpret_cast<uint4*>(sk + row * ROWB + ((st_col ^ swz_k<D>(row)) * 16)) = st_k[u];
-            *reinterpret_cast<uint4*>(sv + row * ROWB + ((st_col ^ swz_v<D>(row)) * 16)) = st_v[u];
-        }
+    auto issue = [&](int p0, int ring) {
+        if (p0 + kKT <= min(P, kv_hi)) issue_tile(p0, ring, std::true_type{});
+        else issue_tile(p0, ring, std::false_type{});
     };
 
     f32x16 oacc[NB];
@@ -280,22 +350,21 @@ __global__ __launch_bounds__(kThreads, 2) void extend_bf16_kernel(
     const int tr_e = (lane >> 2) & 3, tr_c = lane & 3, tr_par = (lane >> 4) & 1;
     const bf16x2_t ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
 
-    // ---- prologue: first tile into buffer 0 ----
+    // ---- prologue: first tile into ring slot 0 ----
     load_slots(kv_lo);
-    issue_loads(kv_lo);
+    issue(kv_lo, 0);
     load_slots(kv_lo + kKT);
-    write_stage(0);
-    __syncthreads();
+    wait_vm_all();
+    wg_barrier();
 
-    int buf = 0;
-    for (int p0 = kv_lo; p0 < kv_hi; p0 += kKT, buf ^= 1) {
-        const bool more = p0 + kKT < kv_hi;
-        if (more) {
-            issue_loads(p0 + kKT);       // global loads of the next tile fly during this tile's arithmetic
+    int ring = 0;
+    for (int p0 = kv_lo; p0 < kv_hi; p0 += kKT, ring ^= 1) {
+        if (p0 + kKT < kv_hi) {
+            issue(p0 + kKT, ring ^ 1);  // the next tile flies during this tile's arithmetic
             load_slots(p0 + 2 * kKT);
         }
         if (wave_on && p0 <= P + wave_i_last) {
-            const unsigned char* sk = smem + buf * 2 * TILEB;
+            const unsigned char* sk = smem + ring * STAGEB;
             const unsigned char* sv = sk + TILEB;
             // ---- S^T = K Q^T for two blocks of 32 keys ----
             f32x16 sacc[2];
@@ -325,8 +394,7 @@ __global__ __launch_bounds__(kThreads, 2) void extend_bf16_kernel(
             float mx = fmaxf(sacc[0][0], sacc[1][0]);
 #pragma unroll
             for (int i = 1; i < 16; ++i) mx = fmaxf(mx, fmaxf(sacc[0][i], sacc[1][i]));
-            mx = fmaxf(mx, swap32(mx));
-            const float m_tile = mx * scale_log2e;
+            const float m_tile = row_max(mx) * scale_log2e;
             // The running maximum is only raised when some row of the wave outgrows it by the threshold;
             // until then probabilities are formed against the older, smaller maximum (they stay <= 2^threshold).
             if (__any(m_tile > m_run + kRescaleThreshold)) {
@@ -353,7 +421,7 @@ __global__ __launch_bounds__(kThreads, 2) void extend_bf16_kernel(
                     l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk), ones, l_run, false);
                 }
 
-            // ---- O^T += V^T P^T, 16 keys per MFMA; V^T fragments come from the transposing LDS read ----
+            // ---- O^T += V^T P^T, 16 keys per MFMA ----
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -366,21 +434,20 @@ __global__ __launch_bounds__(kThreads, 2) void extend_bf16_kernel(
 #pragma unroll
                         for (int h2 = 0; h2 < 2; ++h2) {
                             const int vrow = mb * 32 + cs * 16 + 8 * h2 + 4 * hh + tr_e;
-                            const int chunk = 4 * b + 2 * tr_par + (tr_c >> 1);
-                            frag[h2] = lds_read_tr16(sv + vrow * ROWB + ((chunk ^ swz_v<D>(vrow)) * 16) + (tr_c & 1) * 8);
+                            const int chunk16 = 4 * b + 2 * tr_par + (tr_c >> 1);
+                            frag[h2] = lds_read_tr16(sv + vrow * ROWB + ((chunk16 ^ swz_v<D>(vrow)) * 16) + (tr_c & 1) * 8);
                         }
-                        typedef short s16x8 __attribute__((ext_vector_type(8)));
                         const s16x8 a8 = __builtin_shufflevector(frag[0], frag[1], 0, 1, 2, 3, 4, 5, 6, 7);
                         oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pop, oacc[b], 0, 0, 0);
                     }
                 }
         }
-        if (more) write_stage(buf ^ 1);
-        __syncthreads();
+        wait_vm_all();  // this wave's part of the next tile has landed ...
+        wg_barrier();   // ... and so has everyone else's; nobody still reads the tile just finished
     }
 
     // ---- epilogue: lane holds, for block b and register i, head-dim element 32 b + 8 (i / 4) + 4 hh + i % 4 ----
-    l_run += swap32(l_run);
+    l_run = row_sum(l_run);
     if (!row_ok) return;
     if (n_act == 1) {
         const float inv = 1.f / l_run;
@@ -397,7 +464,7 @@ __global__ __launch_bounds__(kThreads, 2) void extend_bf16_kernel(
     } else {
         const size_t unit = (static_cast<size_t>(t) * nsplit + sp) * Hkv + g;
         const int lrow = wave * 32 + n;
-        float* prow = part_o + (unit * kMT + lrow) * D;
+        float* prow = part_o + (unit * MT + lrow) * D;
 #pragma unroll
         for (int b = 0; b < NB; ++b)
 #pragma unroll
@@ -405,8 +472,8 @@ __global__ __launch_bounds__(kThreads, 2) void extend_bf16_kernel(
                 *reinterpret_cast<float4*>(prow + 32 * b + 8 * q4 + 4 * hh) =
                     make_float4(oacc[b][4 * q4 + 0], oacc[b][4 * q4 + 1], oacc[b][4 * q4 + 2], oacc[b][4 * q4 + 3]);
         if (hh == 0) {
-            part_ml[(unit * kMT + lrow) * 2 + 0] = m_run;
-            part_ml[(unit * kMT + lrow) * 2 + 1] = l_run;
+            part_ml[(unit * MT + lrow) * 2 + 0] = m_run;
+            part_ml[(unit * MT + lrow) * 2 + 1] = l_run;
         }
     }
 }
@@ -419,15 +486,15 @@ __global__ __launch_bounds__(256) void extend_merge_kernel(const int32_t* __rest
                                                           __hip_bfloat16* __restrict__ out,
                                                           const int32_t* __restrict__ n_tiles,
                                                           const int32_t* __restrict__ tile_req,
-                                                          const int32_t* __restrict__ tile_row0, int nsplit, int chunk,
-                                                          const float* __restrict__ part_o,
+                                                          const int32_t* __restrict__ tile_row0, int mt, int nsplit,
+                                                          int chunk, const float* __restrict__ part_o,
                                                           const float* __restrict__ part_ml) {
     const int t = blockIdx.x, g = blockIdx.y;
     if (t >= *n_tiles) return;
     const int r = tile_req[t], row0 = tile_row0[t];
     const int G = Hq / Hkv;
     const int P = prefix_len[r], E = ext_len[r];
-    const int rows_here = min(kMT, E * G - row0);
+    const int rows_here = min(mt, E * G - row0);
     const int kv_end = P + (row0 + rows_here - 1) / G + 1;
     int n_act, lo, hi;
     split_range(kv_end, chunk, nsplit, 0, n_act, lo, hi);
@@ -439,16 +506,16 @@ __global__ __launch_bounds__(256) void extend_merge_kernel(const int32_t* __rest
         float m = -INFINITY;
         for (int s = 0; s < n_act; ++s) {
             const size_t unit = (static_cast<size_t>(t) * nsplit + s) * Hkv + g;
-            m = fmaxf(m, part_ml[(unit * kMT + lrow) * 2]);
+            m = fmaxf(m, part_ml[(unit * mt + lrow) * 2]);
         }
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         float l = 0.f;
         for (int s = 0; s < n_act; ++s) {
             const size_t unit = (static_cast<size_t>(t) * nsplit + s) * Hkv + g;
-            const float ms = part_ml[(unit * kMT + lrow) * 2];
+            const float ms = part_ml[(unit * mt + lrow) * 2];
             const float w = (ms == -INFINITY) ? 0.f : exp2f(ms - m);
-            l += w * part_ml[(unit * kMT + lrow) * 2 + 1];
-            const float4 o = reinterpret_cast<const float4*>(part_o + (unit * kMT + lrow) * D)[c];
+            l += w * part_ml[(unit * mt + lrow) * 2 + 1];
+            const float4 o = reinterpret_cast<const float4*>(part_o + (unit * mt + lrow) * D)[c];
             acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
         }
         const float inv = 1.f / l;
@@ -459,6 +526,37 @@ __global__ __launch_bounds__(256) void extend_merge_kernel(const int32_t* __rest
         v.y = pack_bf16x2(acc.z * inv, acc.w * inv);
         reinterpret_cast<uint2*>(orow)[c] = v;
     }
+}
+
+template <int D, int NW>
+static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_ext, const void* v_ext,
+                         const void* kv_pool, const int32_t* slot_idx, const int32_t* slot_offsets,
+                         const int32_t* prefix_len, const int32_t* ext_len, const int32_t* ext_offsets, int Hq, int Hkv,
+                         int page_size, int64_t num_slots, float scale_log2e, void* out, int32_t* n_tiles,
+                         int32_t* tile_req, int32_t* tile_row0, float* part_o, float* part_ml, hipStream_t stream) {
+    constexpr size_t lds_bytes = static_cast<size_t>(kStages) * 2 * kKT * D * 2;
+    int page_shift = -1;
+    if ((page_size & (page_size - 1)) == 0) {
+        page_shift = 0;
+        while ((1 << page_shift) < page_size) ++page_shift;
+    }
+    const dim3 grid(static_cast<unsigned>(p.tiles_cap) * p.nsplit * Hkv);
+    {
+        ProfScope prof(kProfExtend, stream);
+        hipLaunchKernelGGL((extend_bf16_kernel<D, NW>), grid, dim3(NW * 64), lds_bytes, stream,
+                           static_cast<const __hip_bfloat16*>(q_ext), static_cast<const __hip_bfloat16*>(k_ext),
+                           static_cast<const __hip_bfloat16*>(v_ext), static_cast<const __hip_bfloat16*>(kv_pool), slot_idx,
+                           slot_offsets, prefix_len, ext_len, ext_offsets, Hq, Hkv, page_size, page_shift,
+                           static_cast<int>(num_slots), scale_log2e, static_cast<__hip_bfloat16*>(out), n_tiles, tile_req,
+                           tile_row0, p.nsplit, p.chunk, part_o, part_ml);
+    }
+    if (p.nsplit > 1) {
+        ProfScope prof(kProfMerge, stream);
+        hipLaunchKernelGGL((extend_merge_kernel<D>), dim3(p.tiles_cap, Hkv), dim3(256), 0, stream, prefix_len, ext_len,
+                           ext_offsets, Hq, Hkv, static_cast<__hip_bfloat16*>(out), n_tiles, tile_req, tile_row0, 32 * NW,
+                           p.nsplit, p.chunk, part_o, part_ml);
+    }
+    return PA_OK;
 }
 
 }  // namespace pa
@@ -474,6 +572,8 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
                              int Hq, int Hkv, int D, int page_size, int64_t num_slots, float scale, void* out,
                              void* workspace, size_t workspace_bytes, hipStream_t stream) {
     using namespace pa;
+    PA_REQUIRE(scale > 0.f && scale < INFINITY, "pa_extend_attention: scale must be positive and finite");
+    PA_REQUIRE(num_slots <= INT32_MAX, "pa_extend_attention: num_slots exceeds the int32 range of slot ids");
     const ExtendPlan p = make_plan(B, T, max_kv_len, Hq, Hkv, D);
     if (workspace_bytes < p.total || workspace == nullptr)
         return fail(PA_ENOMEM, "pa_extend_attention: workspace of %zu bytes given, %zu needed", workspace_bytes, p.total);
@@ -486,36 +586,17 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
     float* part_ml = reinterpret_cast<float*>(ws + p.off_part_ml);
     const int G = Hq / Hkv;
     const float scale_log2e = scale * 1.4426950408889634f;
-
     {
         ProfScope prof(kProfTiles, stream);
-        hipLaunchKernelGGL(extend_tiles_kernel, dim3(1), dim3(256), 0, stream, ext_len, B, G, p.tiles_cap, n_tiles,
-                           tile_req, tile_row0);
+        hipLaunchKernelGGL(extend_tiles_kernel, dim3(1), dim3(256), 0, stream, ext_len, B, G, 32 * p.nw, p.tiles_cap,
+                           n_tiles, tile_req, tile_row0);
     }
-    const dim3 grid(static_cast<unsigned>(p.tiles_cap) * p.nsplit * Hkv);
-    const size_t lds_bytes = 2u * 2u * kKT * D * 2u;  // two buffers of one K tile and one V tile
-    const dim3 mgrid(p.tiles_cap, Hkv);
-#define PA_LAUNCH_BF16(DD)                                                                                           \
-    do {                                                                                                             \
-        {                                                                                                            \
-        ProfScope prof(kProfExtend, stream);                                                                         \
-        hipLaunchKernelGGL(extend_bf16_kernel<DD>, grid, dim3(kThreads), lds_bytes, stream,                                 \
-                           static_cast<const __hip_bfloat16*>(q_ext), static_cast<const __hip_bfloat16*>(k_ext),     \
-                           static_cast<const __hip_bfloat16*>(v_ext), static_cast<const __hip_bfloat16*>(kv_pool),   \
-                           slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots,  \
-                           scale_log2e, static_cast<__hip_bfloat16*>(out), n_tiles, tile_req, tile_row0, p.nsplit,   \
-                           p.chunk, part_o, part_ml);                                                                \
-        }                                                                                                            \
-        if (p.nsplit > 1) {                                                                                          \
-            ProfScope prof(kProfMerge, stream);                                                                      \
-            hipLaunchKernelGGL(extend_merge_kernel<DD>, mgrid, dim3(256), 0, stream, prefix_len, ext_len,            \
-                               ext_offsets, Hq, Hkv, static_cast<__hip_bfloat16*>(out), n_tiles, tile_req,           \
-                               tile_row0, p.nsplit, p.chunk, part_o, part_ml);                                       \
-        }                                                                                                            \
-    } while (0)
-    if (D == 64) PA_LAUNCH_BF16(64);
-    else PA_LAUNCH_BF16(128);
-#undef PA_LAUNCH_BF16
+    if (D == 64)
+        launch_extend<64, 4>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, Hq,
+                             Hkv, page_size, num_slots, scale_log2e, out, n_tiles, tile_req, tile_row0, part_o, part_ml, stream);
+    else
+        launch_extend<128, 4>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, Hq,
+                              Hkv, page_size, num_slots, scale_log2e, out, n_tiles, tile_req, tile_row0, part_o, part_ml, stream);
     PA_HIP(hipGetLastError());
     return PA_OK;
 }
