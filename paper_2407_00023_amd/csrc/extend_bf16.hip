@@ -150,12 +150,9 @@ __device__ __forceinline__ int swz_v(int row) {
     return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
 }
 
-// Transposing LDS read (ds_read_b64_tr_b16).  Within each group of 16 lanes the 16 x 4 16-bit values
-// addressed by the lanes form a flat array F (lane-major); lane i of the group receives F[i], F[16+i],
-// F[32+i], F[48+i].
-__device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* p) {
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(__attribute__((address_space(3))) unsigned char*)(p));
-}
+// The V^T fragments come from the transposing LDS read ds_read_b64_tr_b16: within each group of 16 lanes the
+// 16 x 4 16-bit values addressed by the lanes form a flat array F (lane-major); lane i of the group receives
+// F[i], F[16 + i], F[32 + i], F[48 + i].
 
 // Both halves of a query row (lanes l and l ^ 32) combined, in every lane, without going through LDS.
 // v_permlane32_swap exchanges lanes 32..63 of its first operand with lanes 0..31 of its second: fed the
@@ -291,7 +288,7 @@ __global__ __launch_bounds__(NW * 64, 2) void extend_bf16_kernel(
     const unsigned smem_addr = __builtin_amdgcn_readfirstlane(lds_address(smem));
     int32_t sl_next[UPW];  // pool slots of the rows this lane loads in the tile after the one in flight
 
-    auto load_slots = [&](int p0) {
+    auto load_slots = [&](int p0) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < UPW; ++u) {
             // positions past the end of the key range repeat the last valid one (see issue_tile)
@@ -299,43 +296,52 @@ __global__ __launch_bounds__(NW * 64, 2) void extend_bf16_kernel(
             sl_next[u] = p < P ? slots[p] : 0;
         }
     };
-    auto pool_row_ptr = [&](int sl) -> const unsigned char* {
-        sl = min(max(sl, 0), num_slots - 1);  // a slot outside the pool must not fault
-        const unsigned page = page_shift >= 0 ? static_cast<unsigned>(sl) >> page_shift
-                                              : static_cast<unsigned>(sl) / static_cast<unsigned>(page_size);
-        const unsigned o = static_cast<unsigned>(sl) - page * static_cast<unsigned>(page_size);
-        return pool_g + page * page_stride + o * static_cast<unsigned>(ROWB);
-    };
-    // kPrefixOnly: every row of the tile is a prefix position below kv_hi (no clamping, no source select)
-    auto issue_tile = [&](int p0, int ring, auto prefix_only) {
+    // byte offsets, inside a K/V row pair of the pool, of the 16 bytes this lane fetches for block u
+    unsigned ld_koff[UPW], ld_voff[UPW];
+#pragma unroll
+    for (int u = 0; u < UPW; ++u) {
+        const int row = (wave * UPW + u) * RPB + ld_rowl;
+        ld_koff[u] = (ld_pos ^ swz_k<D>(row)) * 16;
+        ld_voff[u] = (ld_pos ^ swz_v<D>(row)) * 16;
+    }
+    const unsigned v_off32 = static_cast<unsigned>(v_off);
+    // kPrefixOnly: every row of the tile is a prefix position below kv_hi (no clamping, no source select).
+    // kPow2: page_size is a power of two (page_shift valid).
+    auto issue_tile = [&](int p0, int ring, auto prefix_only, auto pow2) __attribute__((always_inline)) {
         constexpr bool kPrefixOnly = decltype(prefix_only)::value;
+        constexpr bool kPow2 = decltype(pow2)::value;
         const unsigned sk = smem_addr + ring * STAGEB;
 #pragma unroll
         for (int u = 0; u < UPW; ++u) {
             const int blk = wave * UPW + u;
-            const int row = blk * RPB + ld_rowl;
-            const unsigned char *ka, *va;
-            if constexpr (kPrefixOnly) {
-                ka = pool_row_ptr(sl_next[u]);
-                va = ka + v_off;
-            } else {
+            const unsigned sl = static_cast<unsigned>(min(max(sl_next[u], 0), num_slots - 1));  // never outside the pool
+            const unsigned page = kPow2 ? sl >> page_shift : sl / static_cast<unsigned>(page_size);
+            const unsigned o = kPow2 ? sl & static_cast<unsigned>(page_size - 1) : sl - page * static_cast<unsigned>(page_size);
+            const unsigned char* base = pool_g + page * page_stride;  // one 32x32->64 multiply-add
+            const unsigned char* ka = base + (o * static_cast<unsigned>(ROWB) + ld_koff[u]);
+            const unsigned char* va = base + (o * static_cast<unsigned>(ROWB) + ld_voff[u] + v_off32);
+            if constexpr (!kPrefixOnly) {
                 // rows past the end of the key range repeat the last valid row: finite values that the mask zeroes
-                const int p = min(p0 + row, kv_hi - 1);
-                const unsigned char* kp = pool_row_ptr(sl_next[u]);
-                const size_t xo = static_cast<size_t>(max(p - P, 0)) * x_stride;
-                const bool in_pool = p < P;
-                ka = in_pool ? kp : kx_g + xo;
-                va = in_pool ? kp + v_off : vx_g + xo;
+                const int p = min(p0 + blk * RPB + ld_rowl, kv_hi - 1);
+                if (p >= P) {
+                    const size_t xo = static_cast<size_t>(p - P) * x_stride;
+                    ka = kx_g + xo + ld_koff[u];
+                    va = vx_g + xo + ld_voff[u];
+                }
             }
-            ka += (ld_pos ^ swz_k<D>(row)) * 16;
-            va += (ld_pos ^ swz_v<D>(row)) * 16;
             load_to_lds_16(ka, sk + blk * 1024);
             load_to_lds_16(va, sk + TILEB + blk * 1024);
         }
     };
-    auto issue = [&](int p0, int ring) {
-        if (p0 + kKT <= min(P, kv_hi)) issue_tile(p0, ring, std::true_type{});
-        else issue_tile(p0, ring, std::false_type{});
+    auto issue = [&](int p0, int ring) __attribute__((always_inline)) {
+        const bool prefix_only = p0 + kKT <= min(P, kv_hi);
+        if (page_shift >= 0) {
+            if (prefix_only) issue_tile(p0, ring, std::true_type{}, std::true_type{});
+            else issue_tile(p0, ring, std::false_type{}, std::true_type{});
+        } else {
+            if (prefix_only) issue_tile(p0, ring, std::true_type{}, std::false_type{});
+            else issue_tile(p0, ring, std::false_type{}, std::false_type{});
+        }
     };
 
     f32x16 oacc[NB];
@@ -345,10 +351,117 @@ __global__ __launch_bounds__(NW * 64, 2) void extend_bf16_kernel(
         for (int i = 0; i < 16; ++i) oacc[b][i] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;  // running maximum (scaled, log2 domain) and this lane's share of the sum
 
-    // lane constants of the transposing V read: group lane i = 4 * e + c reads key row (4 * hh + e) + ..., and
-    // 8 bytes at head-dim offset 32 * b + 16 * par + 4 * c
-    const int tr_e = (lane >> 2) & 3, tr_c = lane & 3, tr_par = (lane >> 4) & 1;
+    // ---- LDS read addresses (byte offsets in one ring slot), fixed per lane.
+    // K: row n (+32 for the second key block), 16-byte chunk 2 s + hh of the row.
+    // V, transposing read: group lane i = 4 e + c reads key row 8 h2 + 4 hh + e (+ 16 cs + 32 mb) and 8 bytes at
+    // head-dim offset 32 b + 16 par + 4 c.  The swizzles do not depend on mb / cs, which become immediates.
+    typedef __attribute__((address_space(3))) const unsigned char lds_cbyte;
+    lds_cbyte* lds = (lds_cbyte*)smem;
+    unsigned k_rd[KS], v_rd[NB][2];
+    {
+        const int tr_e = (lane >> 2) & 3, tr_c = lane & 3, tr_par = (lane >> 4) & 1;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            k_rd[s] = n * ROWB + (((2 * s + hh) ^ swz_k<D>(n)) * 16);
+            asm volatile("" : "+v"(k_rd[s]));  // keep it in a register instead of recomputing it every tile
+        }
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2) {
+                const int vrow = 8 * h2 + 4 * hh + tr_e;
+                const int chunk16 = 4 * b + 2 * tr_par + (tr_c >> 1);
+                v_rd[b][h2] = TILEB + vrow * ROWB + ((chunk16 ^ swz_v<D>(vrow)) * 16) + (tr_c & 1) * 8;
+                asm volatile("" : "+v"(v_rd[b][h2]));
+            }
+    }
     const bf16x2_t ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+
+    // one tile of arithmetic on ring slot RING (a compile-time constant, so that it folds into the LDS offsets)
+    auto compute_tile = [&](int p0, auto ring_c) __attribute__((always_inline)) {
+        constexpr int RING = decltype(ring_c)::value;
+        // ---- S^T = K Q^T for two blocks of 32 keys ----
+        f32x16 sacc[2];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sacc[mb][i] = 0.f;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const bf16x8 kf = *(const __attribute__((address_space(3))) bf16x8*)(lds + k_rd[s] + (RING * STAGEB + mb * 32 * ROWB));
+                sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qreg[s], sacc[mb], 0, 0, 0);
+            }
+        }
+
+        // ---- mask (only where the tile crosses a visibility limit), row maximum ----
+        if (p0 + kKT > wave_vis_min) {
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int p = p0 + mb * 32 + 8 * (i / 4) + 4 * hh + (i % 4);
+                    if (p >= vis_end) sacc[mb][i] = -INFINITY;
+                }
+        }
+        float mx = fmaxf(sacc[0][0], sacc[1][0]);
+#pragma unroll
+        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, fmaxf(sacc[0][i], sacc[1][i]));
+        const float m_tile = row_max(mx) * scale_log2e;
+        // The running maximum is only raised when some row of the wave outgrows it by the threshold;
+        // until then probabilities are formed against the older, smaller maximum (they stay <= 2^threshold).
+        if (__any(m_tile > m_run + kRescaleThreshold)) {
+            const float m_new = fmaxf(m_run, m_tile);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - ((m_new == -INFINITY) ? 0.f : m_new));
+            l_run *= alpha;
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
+            m_run = m_new;
+        }
+        const float neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
+        uint32_t pb[2][8];  // probabilities as packed bf16 pairs: the B operand of the second product
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                const float a = __builtin_amdgcn_exp2f(fmaf(sacc[mb][i], scale_log2e, neg_m));
+                const float b = __builtin_amdgcn_exp2f(fmaf(sacc[mb][i + 1], scale_log2e, neg_m));
+                const uint32_t pk = pack_bf16x2(a, b);
+                pb[mb][i / 2] = pk;
+                // the denominator sums the rounded probabilities, the same values the numerator uses
+                l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk), ones, l_run, false);
+            }
+
+        // ---- O^T += V^T P^T, 16 keys per MFMA ----
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int cs = 0; cs < 2; ++cs) {
+                const uint4 pv4 = make_uint4(pb[mb][cs * 4 + 0], pb[mb][cs * 4 + 1], pb[mb][cs * 4 + 2], pb[mb][cs * 4 + 3]);
+                const bf16x8 pop = __builtin_bit_cast(bf16x8, pv4);
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    s16x4 frag[2];
+#pragma unroll
+                    for (int h2 = 0; h2 < 2; ++h2)
+                        frag[h2] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (lds_s16x4*)(lds + v_rd[b][h2] + (RING * STAGEB + (mb * 32 + cs * 16) * ROWB)));
+                    const s16x8 a8 = __builtin_shufflevector(frag[0], frag[1], 0, 1, 2, 3, 4, 5, 6, 7);
+                    oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pop, oacc[b], 0, 0, 0);
+                }
+            }
+    };
+    auto tile_step = [&](int p0, auto ring_c) __attribute__((always_inline)) {
+        constexpr int RING = decltype(ring_c)::value;
+        if (p0 + kKT < kv_hi) {
+            issue(p0 + kKT, RING ^ 1);  // the next tile flies during this tile's arithmetic
+            load_slots(p0 + 2 * kKT);
+        }
+        if (wave_on && p0 <= P + wave_i_last) compute_tile(p0, ring_c);
+        wait_vm_all();  // this wave's part of the next tile has landed ...
+        wg_barrier();   // ... and so has everyone else's; nobody still reads the tile just finished
+    };
 
     // ---- prologue: first tile into ring slot 0 ----
     load_slots(kv_lo);
@@ -357,93 +470,10 @@ __global__ __launch_bounds__(NW * 64, 2) void extend_bf16_kernel(
     wait_vm_all();
     wg_barrier();
 
-    int ring = 0;
-    for (int p0 = kv_lo; p0 < kv_hi; p0 += kKT, ring ^= 1) {
-        if (p0 + kKT < kv_hi) {
-            issue(p0 + kKT, ring ^ 1);  // the next tile flies during this tile's arithmetic
-            load_slots(p0 + 2 * kKT);
-        }
-        if (wave_on && p0 <= P + wave_i_last) {
-            const unsigned char* sk = smem + ring * STAGEB;
-            const unsigned char* sv = sk + TILEB;
-            // ---- S^T = K Q^T for two blocks of 32 keys ----
-            f32x16 sacc[2];
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) sacc[mb][i] = 0.f;
-                const int krow = mb * 32 + n;
-#pragma unroll
-                for (int s = 0; s < KS; ++s) {
-                    const int pos = (2 * s + hh) ^ swz_k<D>(krow);
-                    const uint4 kv = *reinterpret_cast<const uint4*>(sk + krow * ROWB + pos * 16);
-                    sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv), qreg[s], sacc[mb], 0, 0, 0);
-                }
-            }
-
-            // ---- mask (only where the tile crosses a visibility limit), row maximum ----
-            if (p0 + kKT > wave_vis_min) {
-#pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int p = p0 + mb * 32 + 8 * (i / 4) + 4 * hh + (i % 4);
-                        if (p >= vis_end) sacc[mb][i] = -INFINITY;
-                    }
-            }
-            float mx = fmaxf(sacc[0][0], sacc[1][0]);
-#pragma unroll
-            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, fmaxf(sacc[0][i], sacc[1][i]));
-            const float m_tile = row_max(mx) * scale_log2e;
-            // The running maximum is only raised when some row of the wave outgrows it by the threshold;
-            // until then probabilities are formed against the older, smaller maximum (they stay <= 2^threshold).
-            if (__any(m_tile > m_run + kRescaleThreshold)) {
-                const float m_new = fmaxf(m_run, m_tile);
-                const float alpha = __builtin_amdgcn_exp2f(m_run - ((m_new == -INFINITY) ? 0.f : m_new));
-                l_run *= alpha;
-#pragma unroll
-                for (int b = 0; b < NB; ++b)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
-                m_run = m_new;
-            }
-            const float neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
-            uint32_t pb[2][8];  // probabilities as packed bf16 pairs: the B operand of the second product
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int i = 0; i < 16; i += 2) {
-                    const float a = __builtin_amdgcn_exp2f(fmaf(sacc[mb][i], scale_log2e, neg_m));
-                    const float b = __builtin_amdgcn_exp2f(fmaf(sacc[mb][i + 1], scale_log2e, neg_m));
-                    const uint32_t pk = pack_bf16x2(a, b);
-                    pb[mb][i / 2] = pk;
-                    // the denominator sums the rounded probabilities, the same values the numerator uses
-                    l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk), ones, l_run, false);
-                }
-
-            // ---- O^T += V^T P^T, 16 keys per MFMA ----
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int cs = 0; cs < 2; ++cs) {
-                    const uint4 pv4 = make_uint4(pb[mb][cs * 4 + 0], pb[mb][cs * 4 + 1], pb[mb][cs * 4 + 2], pb[mb][cs * 4 + 3]);
-                    const bf16x8 pop = __builtin_bit_cast(bf16x8, pv4);
-#pragma unroll
-                    for (int b = 0; b < NB; ++b) {
-                        s16x4 frag[2];
-#pragma unroll
-                        for (int h2 = 0; h2 < 2; ++h2) {
-                            const int vrow = mb * 32 + cs * 16 + 8 * h2 + 4 * hh + tr_e;
-                            const int chunk16 = 4 * b + 2 * tr_par + (tr_c >> 1);
-                            frag[h2] = lds_read_tr16(sv + vrow * ROWB + ((chunk16 ^ swz_v<D>(vrow)) * 16) + (tr_c & 1) * 8);
-                        }
-                        const s16x8 a8 = __builtin_shufflevector(frag[0], frag[1], 0, 1, 2, 3, 4, 5, 6, 7);
-                        oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pop, oacc[b], 0, 0, 0);
-                    }
-                }
-        }
-        wait_vm_all();  // this wave's part of the next tile has landed ...
-        wg_barrier();   // ... and so has everyone else's; nobody still reads the tile just finished
+    for (int p0 = kv_lo; p0 < kv_hi; p0 += 2 * kKT) {
+        tile_step(p0, std::integral_constant<int, 0>{});
+        if (p0 + kKT >= kv_hi) break;
+        tile_step(p0 + kKT, std::integral_constant<int, 1>{});
     }
 
     // ---- epilogue: lane holds, for block b and register i, head-dim element 32 b + 8 (i / 4) + 4 hh + i % 4 ----
