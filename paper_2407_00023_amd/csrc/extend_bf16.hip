@@ -46,7 +46,8 @@ constexpr int kMinChunk = 512;           // never split below this many keys per
 constexpr float kRescaleThreshold = 8.f; // log2 units: the running maximum may lag the true one by this much
 
 struct ExtendPlan {
-    int nw;          // waves per workgroup (4 or 8); a row tile has 32 * nw packed rows
+    int nw;          // waves per workgroup
+    int rb;          // blocks of 32 packed rows per wave; a row tile has 32 * rb * nw packed rows
     int tiles_cap;   // upper bound on the number of (request, row tile) pairs
     int nsplit;      // chunks of the key axis
     int chunk;       // keys per chunk (multiple of kKT)
@@ -59,7 +60,8 @@ static ExtendPlan make_plan(int B, int64_t T, int64_t max_kv_len, int Hq, int Hk
     ExtendPlan p{};
     const int G = Hq / Hkv;
     p.nw = 4;
-    const int mt = 32 * p.nw;
+    p.rb = 1;
+    const int mt = 32 * p.rb * p.nw;
     const int64_t est = (T * G + mt - 1) / mt;
     p.tiles_cap = static_cast<int>(est + B);
     int64_t want = (kTargetWorkgroups + est * Hkv - 1) / (est * Hkv > 0 ? est * Hkv : 1);
@@ -204,8 +206,8 @@ __device__ __forceinline__ unsigned lds_address(const void* p) {
     return static_cast<unsigned>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const unsigned char*)(p)));
 }
 
-template <int D, int NW>
-__global__ __launch_bounds__(NW * 64, 2) void extend_bf16_kernel(
+template <int D, int NW, int RB>
+__global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     const __hip_bfloat16* __restrict__ q_ext, const __hip_bfloat16* __restrict__ k_ext,
     const __hip_bfloat16* __restrict__ v_ext, const __hip_bfloat16* __restrict__ pool,
     const int32_t* __restrict__ slot_idx, const int32_t* __restrict__ slot_offsets,
@@ -214,7 +216,8 @@ __global__ __launch_bounds__(NW * 64, 2) void extend_bf16_kernel(
     float scale_log2e, __hip_bfloat16* __restrict__ out, const int32_t* __restrict__ n_tiles,
     const int32_t* __restrict__ tile_req, const int32_t* __restrict__ tile_row0, int nsplit, int chunk,
     float* __restrict__ part_o, float* __restrict__ part_ml) {
-    constexpr int MT = 32 * NW;              // packed query rows per workgroup
+    constexpr int WR = 32 * RB;              // packed query rows per wave (RB blocks of 32)
+    constexpr int MT = WR * NW;              // packed query rows per workgroup
     constexpr int NB = D / 32;               // MFMA row blocks of the head dimension in O^T
     constexpr int KS = D / 16;               // k-slices of the QK^T product
     constexpr int CPR = D / 8;               // 16-byte chunks per K/V row
@@ -253,25 +256,28 @@ __global__ __launch_bounds__(NW * 64, 2) void extend_bf16_kernel(
     const int64_t e0 = ext_offsets[r];
     const int32_t* __restrict__ slots = slot_idx + slot_offsets[r];
 
-    // this lane's query row
-    const int rho = row0 + wave * 32 + n;
-    const bool row_ok = rho < rows_total;
-    const int qi = row_ok ? rho / G : 0;            // extend index of the row
-    const int qh = g * G + (row_ok ? rho % G : 0);  // query head
-    const bool wave_on = wave * 32 < rows_here;
-    const int wave_i_first = (row0 + wave * 32) / G;
-    const int wave_i_last = (row0 + min(rows_here, wave * 32 + 32) - 1) / G;
-    const int wave_vis_min = min(kv_hi, P + wave_i_first + 1);  // every row of the wave sees keys [.., this)
-    const int vis_end = min(kv_hi, P + qi + 1);                 // keys [.., vis_end) are visible to this row
-
-    bf16x8 qreg[KS];
-    {
-        const uint4* qp = reinterpret_cast<const uint4*>(q_ext + ((e0 + qi) * Hq + qh) * static_cast<int64_t>(D));
+    // this lane's query rows: one per row block
+    const bool wave_on = wave * WR < rows_here;
+    const int wave_i_last = (row0 + min(rows_here, wave * WR + WR) - 1) / G;
+    bool row_ok[RB];
+    int qi[RB], qh[RB];          // extend index and query head of the row
+    int vis_end[RB];             // keys [.., vis_end) are visible to the row
+    int blk_vis_min[RB];         // every row of the block sees keys [.., this)
+    bf16x8 qreg[RB][KS];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const int rho = row0 + wave * WR + rb * 32 + n;
+        row_ok[rb] = rho < rows_total;
+        qi[rb] = row_ok[rb] ? rho / G : 0;
+        qh[rb] = g * G + (row_ok[rb] ? rho % G : 0);
+        vis_end[rb] = min(kv_hi, P + qi[rb] + 1);
+        blk_vis_min[rb] = min(kv_hi, P + (row0 + wave * WR + rb * 32) / G + 1);
+        const uint4* qp = reinterpret_cast<const uint4*>(q_ext + ((e0 + qi[rb]) * Hq + qh[rb]) * static_cast<int64_t>(D));
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (row_ok) v = qp[2 * s + hh];
-            qreg[s] = __builtin_bit_cast(bf16x8, v);
+            if (row_ok[rb]) v = qp[2 * s + hh];
+            qreg[rb][s] = __builtin_bit_cast(bf16x8, v);
         }
     }
 
@@ -281,7 +287,7 @@ __global__ __launch_bounds__(NW * 64, 2) void extend_bf16_kernel(
     const int ld_rowl = lane / CPR;
     const unsigned char* pool_g = reinterpret_cast<const unsigned char*>(pool) + static_cast<size_t>(g) * page_size * ROWB;
     const size_t page_stride = static_cast<size_t>(2) * Hkv * page_size * ROWB;  // bytes from one page to the next
-    const size_t v_off = static_cast<size_t>(Hkv) * page_size * ROWB;            // from a K row to its V row
+    const unsigned v_off32 = static_cast<unsigned>(Hkv) * page_size * ROWB;      // from a K row to its V row
     const unsigned char* kx_g = reinterpret_cast<const unsigned char*>(k_ext) + (e0 * Hkv + g) * static_cast<int64_t>(ROWB);
     const unsigned char* vx_g = reinterpret_cast<const unsigned char*>(v_ext) + (e0 * Hkv + g) * static_cast<int64_t>(ROWB);
     const size_t x_stride = static_cast<size_t>(Hkv) * ROWB;  // bytes from one extend token to the next
@@ -304,7 +310,6 @@ __global__ __launch_bounds__(NW * 64, 2) void extend_bf16_kernel(
         ld_koff[u] = (ld_pos ^ swz_k<D>(row)) * 16;
         ld_voff[u] = (ld_pos ^ swz_v<D>(row)) * 16;
     }
-    const unsigned v_off32 = static_cast<unsigned>(v_off);
     // kPrefixOnly: every row of the tile is a prefix position below kv_hi (no clamping, no source select).
     // kPow2: page_size is a power of two (page_shift valid).
     auto issue_tile = [&](int p0, int ring, auto prefix_only, auto pow2) __attribute__((always_inline)) {
@@ -344,12 +349,17 @@ __global__ __launch_bounds__(NW * 64, 2) void extend_bf16_kernel(
         }
     };
 
-    f32x16 oacc[NB];
+    f32x16 oacc[RB][NB];
+    float m_run[RB], l_run[RB];  // running maximum (scaled, log2 domain) and this lane's share of the sum
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int rb = 0; rb < RB; ++rb) {
+        m_run[rb] = -INFINITY;
+        l_run[rb] = 0.f;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) oacc[b][i] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;  // running maximum (scaled, log2 domain) and this lane's share of the sum
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) oacc[rb][b][i] = 0.f;
+    }
 
     // ---- LDS read addresses (byte offsets in one ring slot), fixed per lane.
     // K: row n (+32 for the second key block), 16-byte chunk 2 s + hh of the row.
@@ -377,88 +387,143 @@ __global__ __launch_bounds__(NW * 64, 2) void extend_bf16_kernel(
     }
     const bf16x2_t ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
 
-    // one tile of arithmetic on ring slot RING (a compile-time constant, so that it folds into the LDS offsets)
-    auto compute_tile = [&](int p0, auto ring_c) __attribute__((always_inline)) {
-        constexpr int RING = decltype(ring_c)::value;
-        // ---- S^T = K Q^T for two blocks of 32 keys ----
-        f32x16 sacc[2];
+    // ---- pieces of one tile's arithmetic; MB = which block of 32 keys of the tile, RING = ring slot ----
+    // S^T = K Q^T for one block of 32 keys and all row blocks: each K fragment read from LDS feeds RB MFMAs
+    auto qk_block = [&](auto ring_c, auto mb_c, f32x16 (&sacc)[RB]) __attribute__((always_inline)) {
+        constexpr int OFF = decltype(ring_c)::value * STAGEB + decltype(mb_c)::value * 32 * ROWB;
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
+        for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) sacc[mb][i] = 0.f;
+            for (int i = 0; i < 16; ++i) sacc[rb][i] = 0.f;
 #pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                const bf16x8 kf = *(const __attribute__((address_space(3))) bf16x8*)(lds + k_rd[s] + (RING * STAGEB + mb * 32 * ROWB));
-                sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qreg[s], sacc[mb], 0, 0, 0);
-            }
+        for (int s = 0; s < KS; ++s) {
+            const bf16x8 kf = *(const __attribute__((address_space(3))) bf16x8*)(lds + k_rd[s] + OFF);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+                sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qreg[rb][s], sacc[rb], 0, 0, 0);
         }
-
-        // ---- mask (only where the tile crosses a visibility limit), row maximum ----
-        if (p0 + kKT > wave_vis_min) {
+    };
+    // mask the keys a row must not see (only called where the block crosses a visibility limit)
+    auto mask_block = [&](int pb0, f32x16 (&sacc)[RB]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
+        for (int rb = 0; rb < RB; ++rb)
+            if (pb0 + 32 > blk_vis_min[rb]) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int p = p0 + mb * 32 + 8 * (i / 4) + 4 * hh + (i % 4);
-                    if (p >= vis_end) sacc[mb][i] = -INFINITY;
-                }
-        }
-        float mx = fmaxf(sacc[0][0], sacc[1][0]);
-#pragma unroll
-        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, fmaxf(sacc[0][i], sacc[1][i]));
-        const float m_tile = row_max(mx) * scale_log2e;
-        // The running maximum is only raised when some row of the wave outgrows it by the threshold;
-        // until then probabilities are formed against the older, smaller maximum (they stay <= 2^threshold).
-        if (__any(m_tile > m_run + kRescaleThreshold)) {
-            const float m_new = fmaxf(m_run, m_tile);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - ((m_new == -INFINITY) ? 0.f : m_new));
-            l_run *= alpha;
-#pragma unroll
-            for (int b = 0; b < NB; ++b)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
-            m_run = m_new;
-        }
-        const float neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
-        uint32_t pb[2][8];  // probabilities as packed bf16 pairs: the B operand of the second product
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int i = 0; i < 16; i += 2) {
-                const float a = __builtin_amdgcn_exp2f(fmaf(sacc[mb][i], scale_log2e, neg_m));
-                const float b = __builtin_amdgcn_exp2f(fmaf(sacc[mb][i + 1], scale_log2e, neg_m));
-                const uint32_t pk = pack_bf16x2(a, b);
-                pb[mb][i / 2] = pk;
-                // the denominator sums the rounded probabilities, the same values the numerator uses
-                l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk), ones, l_run, false);
-            }
-
-        // ---- O^T += V^T P^T, 16 keys per MFMA ----
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int cs = 0; cs < 2; ++cs) {
-                const uint4 pv4 = make_uint4(pb[mb][cs * 4 + 0], pb[mb][cs * 4 + 1], pb[mb][cs * 4 + 2], pb[mb][cs * 4 + 3]);
-                const bf16x8 pop = __builtin_bit_cast(bf16x8, pv4);
-#pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    s16x4 frag[2];
-#pragma unroll
-                    for (int h2 = 0; h2 < 2; ++h2)
-                        frag[h2] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (lds_s16x4*)(lds + v_rd[b][h2] + (RING * STAGEB + (mb * 32 + cs * 16) * ROWB)));
-                    const s16x8 a8 = __builtin_shufflevector(frag[0], frag[1], 0, 1, 2, 3, 4, 5, 6, 7);
-                    oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pop, oacc[b], 0, 0, 0);
+                    const int p = pb0 + 8 * (i / 4) + 4 * hh + (i % 4);
+                    if (p >= vis_end[rb]) sacc[rb][i] = -INFINITY;
                 }
             }
     };
+    // row maximum of one key block, scaled to the log2 domain, in every lane of the row
+    auto block_max = [&](const f32x16 (&sacc)[RB], float (&m_blk)[RB]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            float mx = fmaxf(sacc[rb][0], sacc[rb][1]);
+#pragma unroll
+            for (int i = 2; i < 16; ++i) mx = fmaxf(mx, sacc[rb][i]);
+            m_blk[rb] = row_max(mx) * scale_log2e;
+        }
+    };
+    // probabilities of one key block against the current running maximum, packed to bf16 pairs (the B operand
+    // of the second product); lsum receives the sum of the ROUNDED probabilities, the values the numerator uses
+    auto block_exp = [&](const f32x16 (&sacc)[RB], uint32_t (&pb)[RB][8], float (&lsum)[RB]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            const float neg_m = (m_run[rb] == -INFINITY) ? 0.f : -m_run[rb];
+            float acc = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                const float a = __builtin_amdgcn_exp2f(fmaf(sacc[rb][i], scale_log2e, neg_m));
+                const float b = __builtin_amdgcn_exp2f(fmaf(sacc[rb][i + 1], scale_log2e, neg_m));
+                const uint32_t pk = pack_bf16x2(a, b);
+                pb[rb][i / 2] = pk;
+                acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk), ones, acc, false);
+            }
+            lsum[rb] = acc;
+        }
+    };
+    // The probabilities above are formed BEFORE it is known whether the running maximum is still good
+    // enough, so that their arithmetic can overlap the matrix products.  The maximum may lag the true one
+    // by kRescaleThreshold (probabilities then reach 2^threshold, harmless in bf16/fp32).  If some row of
+    // the wave outgrew it by more, this raises the maximum, rescales what was accumulated so far and forms
+    // the block's probabilities again.  Rare: with a stable maximum it happens for the first block only.
+    auto block_commit = [&](const f32x16 (&sacc)[RB], const float (&m_blk)[RB], uint32_t (&pb)[RB][8],
+                            float (&lsum)[RB]) __attribute__((always_inline)) {
+        bool grow = false;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) grow |= m_blk[rb] > m_run[rb] + kRescaleThreshold;
+        if (__any(grow)) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                const float m_new = fmaxf(m_run[rb], m_blk[rb]);
+                const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - ((m_new == -INFINITY) ? 0.f : m_new));
+                l_run[rb] *= alpha;
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) oacc[rb][b][i] *= alpha;
+                m_run[rb] = m_new;
+            }
+            block_exp(sacc, pb, lsum);
+        }
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) l_run[rb] += lsum[rb];
+    };
+    // O^T += V^T P^T for one block of 32 keys, 16 keys per MFMA: each V^T fragment feeds RB MFMAs
+    auto pv_block = [&](auto ring_c, auto mb_c, const uint32_t (&pb)[RB][8]) __attribute__((always_inline)) {
+        constexpr int OFF = decltype(ring_c)::value * STAGEB + decltype(mb_c)::value * 32 * ROWB;
+#pragma unroll
+        for (int cs = 0; cs < 2; ++cs) {
+            bf16x8 pop[RB];
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+                pop[rb] = __builtin_bit_cast(bf16x8, make_uint4(pb[rb][cs * 4 + 0], pb[rb][cs * 4 + 1], pb[rb][cs * 4 + 2], pb[rb][cs * 4 + 3]));
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                s16x4 frag[2];
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2)
+                    frag[h2] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(lds + v_rd[b][h2] + (OFF + cs * 16 * ROWB)));
+                const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(frag[0], frag[1], 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+                    oacc[rb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pop[rb], oacc[rb][b], 0, 0, 0);
+            }
+        }
+    };
+
+    // One tile.  Order of the matrix work: QK(block 0), QK(block 1), PV(block 0), PV(block 1); the exponentials
+    // of block 0 are independent of QK(block 1) and those of block 1 of PV(block 0), so the scheduler can
+    // run them in the shadow of those MFMAs.  The next tile's loads are issued after the first MFMAs so that
+    // their address arithmetic overlaps too.
     auto tile_step = [&](int p0, auto ring_c) __attribute__((always_inline)) {
         constexpr int RING = decltype(ring_c)::value;
+        const bool compute = wave_on && p0 <= P + wave_i_last;
+        f32x16 s0[RB], s1[RB];
+        uint32_t pb0[RB][8], pb1[RB][8];
+        float mb0[RB], mb1[RB], ls0[RB], ls1[RB];
+        if (compute) qk_block(ring_c, std::integral_constant<int, 0>{}, s0);
         if (p0 + kKT < kv_hi) {
             issue(p0 + kKT, RING ^ 1);  // the next tile flies during this tile's arithmetic
             load_slots(p0 + 2 * kKT);
         }
-        if (wave_on && p0 <= P + wave_i_last) compute_tile(p0, ring_c);
+        if (compute) {
+            bool need_mask = false;
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) need_mask |= p0 + kKT > blk_vis_min[rb];
+            if (need_mask) mask_block(p0, s0);
+            qk_block(ring_c, std::integral_constant<int, 1>{}, s1);
+            block_max(s0, mb0);
+            block_exp(s0, pb0, ls0);
+            block_commit(s0, mb0, pb0, ls0);
+            if (need_mask) mask_block(p0 + 32, s1);
+            pv_block(ring_c, std::integral_constant<int, 0>{}, pb0);
+            block_max(s1, mb1);
+            block_exp(s1, pb1, ls1);
+            block_commit(s1, mb1, pb1, ls1);
+            pv_block(ring_c, std::integral_constant<int, 1>{}, pb1);
+        }
         wait_vm_all();  // this wave's part of the next tile has landed ...
         wg_barrier();   // ... and so has everyone else's; nobody still reads the tile just finished
     };
@@ -477,33 +542,36 @@ __global__ __launch_bounds__(NW * 64, 2) void extend_bf16_kernel(
     }
 
     // ---- epilogue: lane holds, for block b and register i, head-dim element 32 b + 8 (i / 4) + 4 hh + i % 4 ----
-    l_run = row_sum(l_run);
-    if (!row_ok) return;
-    if (n_act == 1) {
-        const float inv = 1.f / l_run;
-        __hip_bfloat16* orow = out + ((e0 + qi) * Hq + qh) * static_cast<int64_t>(D);
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
+    for (int rb = 0; rb < RB; ++rb) {
+        const float l_row = row_sum(l_run[rb]);
+        if (!row_ok[rb]) continue;
+        if (n_act == 1) {
+            const float inv = 1.f / l_row;
+            __hip_bfloat16* orow = out + ((e0 + qi[rb]) * Hq + qh[rb]) * static_cast<int64_t>(D);
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                uint2 v;
-                v.x = pack_bf16x2(oacc[b][4 * q4 + 0] * inv, oacc[b][4 * q4 + 1] * inv);
-                v.y = pack_bf16x2(oacc[b][4 * q4 + 2] * inv, oacc[b][4 * q4 + 3] * inv);
-                *reinterpret_cast<uint2*>(orow + 32 * b + 8 * q4 + 4 * hh) = v;
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    uint2 v;
+                    v.x = pack_bf16x2(oacc[rb][b][4 * q4 + 0] * inv, oacc[rb][b][4 * q4 + 1] * inv);
+                    v.y = pack_bf16x2(oacc[rb][b][4 * q4 + 2] * inv, oacc[rb][b][4 * q4 + 3] * inv);
+                    *reinterpret_cast<uint2*>(orow + 32 * b + 8 * q4 + 4 * hh) = v;
+                }
+        } else {
+            const size_t unit = (static_cast<size_t>(t) * nsplit + sp) * Hkv + g;
+            const int lrow = wave * WR + rb * 32 + n;
+            float* prow = part_o + (unit * MT + lrow) * D;
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    *reinterpret_cast<float4*>(prow + 32 * b + 8 * q4 + 4 * hh) = make_float4(
+                        oacc[rb][b][4 * q4 + 0], oacc[rb][b][4 * q4 + 1], oacc[rb][b][4 * q4 + 2], oacc[rb][b][4 * q4 + 3]);
+            if (hh == 0) {
+                part_ml[(unit * MT + lrow) * 2 + 0] = m_run[rb];
+                part_ml[(unit * MT + lrow) * 2 + 1] = l_row;
             }
-    } else {
-        const size_t unit = (static_cast<size_t>(t) * nsplit + sp) * Hkv + g;
-        const int lrow = wave * 32 + n;
-        float* prow = part_o + (unit * MT + lrow) * D;
-#pragma unroll
-        for (int b = 0; b < NB; ++b)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4)
-                *reinterpret_cast<float4*>(prow + 32 * b + 8 * q4 + 4 * hh) =
-                    make_float4(oacc[b][4 * q4 + 0], oacc[b][4 * q4 + 1], oacc[b][4 * q4 + 2], oacc[b][4 * q4 + 3]);
-        if (hh == 0) {
-            part_ml[(unit * MT + lrow) * 2 + 0] = m_run;
-            part_ml[(unit * MT + lrow) * 2 + 1] = l_run;
         }
     }
 }
@@ -558,7 +626,7 @@ __global__ __launch_bounds__(256) void extend_merge_kernel(const int32_t* __rest
     }
 }
 
-template <int D, int NW>
+template <int D, int NW, int RB>
 static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_ext, const void* v_ext,
                          const void* kv_pool, const int32_t* slot_idx, const int32_t* slot_offsets,
                          const int32_t* prefix_len, const int32_t* ext_len, const int32_t* ext_offsets, int Hq, int Hkv,
@@ -573,7 +641,7 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
     const dim3 grid(static_cast<unsigned>(p.tiles_cap) * p.nsplit * Hkv);
     {
         ProfScope prof(kProfExtend, stream);
-        hipLaunchKernelGGL((extend_bf16_kernel<D, NW>), grid, dim3(NW * 64), lds_bytes, stream,
+        hipLaunchKernelGGL((extend_bf16_kernel<D, NW, RB>), grid, dim3(NW * 64), lds_bytes, stream,
                            static_cast<const __hip_bfloat16*>(q_ext), static_cast<const __hip_bfloat16*>(k_ext),
                            static_cast<const __hip_bfloat16*>(v_ext), static_cast<const __hip_bfloat16*>(kv_pool), slot_idx,
                            slot_offsets, prefix_len, ext_len, ext_offsets, Hq, Hkv, page_size, page_shift,
@@ -583,7 +651,7 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
     if (p.nsplit > 1) {
         ProfScope prof(kProfMerge, stream);
         hipLaunchKernelGGL((extend_merge_kernel<D>), dim3(p.tiles_cap, Hkv), dim3(256), 0, stream, prefix_len, ext_len,
-                           ext_offsets, Hq, Hkv, static_cast<__hip_bfloat16*>(out), n_tiles, tile_req, tile_row0, 32 * NW,
+                           ext_offsets, Hq, Hkv, static_cast<__hip_bfloat16*>(out), n_tiles, tile_req, tile_row0, 32 * RB * NW,
                            p.nsplit, p.chunk, part_o, part_ml);
     }
     return PA_OK;
@@ -618,14 +686,14 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
     const float scale_log2e = scale * 1.4426950408889634f;
     {
         ProfScope prof(kProfTiles, stream);
-        hipLaunchKernelGGL(extend_tiles_kernel, dim3(1), dim3(256), 0, stream, ext_len, B, G, 32 * p.nw, p.tiles_cap,
+        hipLaunchKernelGGL(extend_tiles_kernel, dim3(1), dim3(256), 0, stream, ext_len, B, G, 32 * p.rb * p.nw, p.tiles_cap,
                            n_tiles, tile_req, tile_row0);
     }
     if (D == 64)
-        launch_extend<64, 4>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, Hq,
+        launch_extend<64, 4, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, Hq,
                              Hkv, page_size, num_slots, scale_log2e, out, n_tiles, tile_req, tile_row0, part_o, part_ml, stream);
     else
-        launch_extend<128, 4>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, Hq,
+        launch_extend<128, 4, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, Hq,
                               Hkv, page_size, num_slots, scale_log2e, out, n_tiles, tile_req, tile_row0, part_o, part_ml, stream);
     PA_HIP(hipGetLastError());
     return PA_OK;
