@@ -286,7 +286,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     const int ld_pos = lane % CPR;
     const int ld_rowl = lane / CPR;
     const unsigned char* pool_g = reinterpret_cast<const unsigned char*>(pool) + static_cast<size_t>(g) * page_size * ROWB;
-    const size_t page_stride = static_cast<size_t>(2) * Hkv * page_size * ROWB;  // bytes from one page to the next
+    const unsigned page_stride = 2u * Hkv * page_size * ROWB;  // bytes from one page to the next (< 4 GB, checked on the host)
     const unsigned v_off32 = static_cast<unsigned>(Hkv) * page_size * ROWB;      // from a K row to its V row
     const unsigned char* kx_g = reinterpret_cast<const unsigned char*>(k_ext) + (e0 * Hkv + g) * static_cast<int64_t>(ROWB);
     const unsigned char* vx_g = reinterpret_cast<const unsigned char*>(v_ext) + (e0 * Hkv + g) * static_cast<int64_t>(ROWB);
@@ -302,14 +302,13 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
             sl_next[u] = p < P ? slots[p] : 0;
         }
     };
-    // byte offsets, inside a K/V row pair of the pool, of the 16 bytes this lane fetches for block u
-    unsigned ld_koff[UPW], ld_voff[UPW];
-#pragma unroll
-    for (int u = 0; u < UPW; ++u) {
-        const int row = (wave * UPW + u) * RPB + ld_rowl;
-        ld_koff[u] = (ld_pos ^ swz_k<D>(row)) * 16;
-        ld_voff[u] = (ld_pos ^ swz_v<D>(row)) * 16;
-    }
+    // Byte offset, inside its K (V) row, of the 16 bytes this lane fetches for block u.  Block u of the wave holds
+    // rows 16 w + 4 u + lane / 16 (D = 128), so its swizzle differs from that of block 0 by an XOR with 4 u (K) or
+    // u (V); for D = 64 (rows 16 w + 8 u + lane / 8) by an XOR with 4 u (K) or 2 u (V).
+    const unsigned ld_koff0 = (ld_pos ^ swz_k<D>(wave * UPW * RPB + ld_rowl)) * 16;
+    const unsigned ld_voff0 = (ld_pos ^ swz_v<D>(wave * UPW * RPB + ld_rowl)) * 16;
+    auto ld_koff = [&](int u) __attribute__((always_inline)) { return ld_koff0 ^ (64u * u); };
+    auto ld_voff = [&](int u) __attribute__((always_inline)) { return ld_voff0 ^ ((D == 128 ? 16u : 32u) * u); };
     // kPrefixOnly: every row of the tile is a prefix position below kv_hi (no clamping, no source select).
     // kPow2: page_size is a power of two (page_shift valid).
     auto issue_tile = [&](int p0, int ring, auto prefix_only, auto pow2) __attribute__((always_inline)) {
@@ -322,16 +321,16 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
             const unsigned sl = static_cast<unsigned>(min(max(sl_next[u], 0), num_slots - 1));  // never outside the pool
             const unsigned page = kPow2 ? sl >> page_shift : sl / static_cast<unsigned>(page_size);
             const unsigned o = kPow2 ? sl & static_cast<unsigned>(page_size - 1) : sl - page * static_cast<unsigned>(page_size);
-            const unsigned char* base = pool_g + page * page_stride;  // one 32x32->64 multiply-add
-            const unsigned char* ka = base + (o * static_cast<unsigned>(ROWB) + ld_koff[u]);
-            const unsigned char* va = base + (o * static_cast<unsigned>(ROWB) + ld_voff[u] + v_off32);
+            const unsigned char* base = pool_g + static_cast<size_t>(page) * page_stride;  // one 32x32->64 multiply-add
+            const unsigned char* ka = base + (o * static_cast<unsigned>(ROWB) + ld_koff(u));
+            const unsigned char* va = base + (o * static_cast<unsigned>(ROWB) + ld_voff(u) + v_off32);
             if constexpr (!kPrefixOnly) {
                 // rows past the end of the key range repeat the last valid row: finite values that the mask zeroes
                 const int p = min(p0 + blk * RPB + ld_rowl, kv_hi - 1);
                 if (p >= P) {
                     const size_t xo = static_cast<size_t>(p - P) * x_stride;
-                    ka = kx_g + xo + ld_koff[u];
-                    va = vx_g + xo + ld_voff[u];
+                    ka = kx_g + xo + ld_koff(u);
+                    va = vx_g + xo + ld_voff(u);
                 }
             }
             load_to_lds_16(ka, sk + blk * 1024);
@@ -366,13 +365,13 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     // V, transposing read: group lane i = 4 e + c reads key row 8 h2 + 4 hh + e (+ 16 cs + 32 mb) and 8 bytes at
     // head-dim offset 32 b + 16 par + 4 c.  The swizzles do not depend on mb / cs, which become immediates.
     typedef __attribute__((address_space(3))) const unsigned char lds_cbyte;
-    lds_cbyte* lds = (lds_cbyte*)smem;
+    lds_cbyte* lds = (lds_cbyte*)nullptr;  // k_rd / v_rd hold absolute LDS addresses
     unsigned k_rd[KS], v_rd[NB][2];
     {
         const int tr_e = (lane >> 2) & 3, tr_c = lane & 3, tr_par = (lane >> 4) & 1;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            k_rd[s] = n * ROWB + (((2 * s + hh) ^ swz_k<D>(n)) * 16);
+            k_rd[s] = smem_addr + n * ROWB + (((2 * s + hh) ^ swz_k<D>(n)) * 16);
             asm volatile("" : "+v"(k_rd[s]));  // keep it in a register instead of recomputing it every tile
         }
 #pragma unroll
@@ -381,7 +380,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
             for (int h2 = 0; h2 < 2; ++h2) {
                 const int vrow = 8 * h2 + 4 * hh + tr_e;
                 const int chunk16 = 4 * b + 2 * tr_par + (tr_c >> 1);
-                v_rd[b][h2] = TILEB + vrow * ROWB + ((chunk16 ^ swz_v<D>(vrow)) * 16) + (tr_c & 1) * 8;
+                v_rd[b][h2] = smem_addr + TILEB + vrow * ROWB + ((chunk16 ^ swz_v<D>(vrow)) * 16) + (tr_c & 1) * 8;
                 asm volatile("" : "+v"(v_rd[b][h2]));
             }
     }
@@ -452,7 +451,13 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
                             float (&lsum)[RB]) __attribute__((always_inline)) {
         bool grow = false;
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) grow |= m_blk[rb] > m_run[rb] + kRescaleThreshold;
+        for (int rb = 0; rb < RB; ++rb) {
+            grow |= m_blk[rb] > m_run[rb] + kRescaleThreshold;
+            // pin the speculative probabilities in front of the branch (the compiler would otherwise sink
+            // their computation below it, out of the shadow of the MFMAs)
+            asm volatile("" : "+v"(pb[rb][0]), "+v"(pb[rb][1]), "+v"(pb[rb][2]), "+v"(pb[rb][3]), "+v"(pb[rb][4]),
+                         "+v"(pb[rb][5]), "+v"(pb[rb][6]), "+v"(pb[rb][7]), "+v"(lsum[rb]));
+        }
         if (__any(grow)) {
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
@@ -493,6 +498,152 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
         }
     };
 
+    // ------------------------------------------------------------------------------------------------
+    // The steady-state tile, scheduled by hand (RB == 1).  A wave issues in order, so arithmetic only runs
+    // in the shadow of an MFMA (32 cycles) if it follows that MFMA in the instruction stream.  The tile is
+    // written as 32 slots, each one MFMA followed by a piece of per-lane work that does not depend on it, and
+    // the compiler's scheduler is fenced off between slots.  LDS reads run kPD slots ahead of their MFMA.
+    //   slots  0.. 7  S0 = K(block 0) Q^T     | addresses + issue of the next tile's global -> LDS loads
+    //   slots  8..15  S1 = K(block 1) Q^T     | exponentials of block 0 (against the current maximum), its maximum
+    //   (commit block 0: raise the maximum and redo the block if it was outgrown - rare)
+    //   slots 16..23  O += V(block 0) P0      | exponentials of block 1, its maximum
+    //   (commit block 1)
+    //   slots 24..31  O += V(block 1) P1      | -
+    // Only for tiles that need no mask, with a power-of-two page size.
+    // ------------------------------------------------------------------------------------------------
+    auto tile_fast = [&](int p0, auto ring_c) __attribute__((always_inline)) {
+        static_assert(KS == 2 * UPW || RB != 1, "slot plan assumes one tile-load piece per QK slot of block 0");
+        constexpr int RING = decltype(ring_c)::value;
+        constexpr int kPD = 2;    // K fragments in flight ahead of their MFMA
+        constexpr int kPDV = 2;   // V fragments in flight ahead of their MFMA
+        constexpr int NPV = 2 * NB;  // MFMAs per PV block (2 groups of 16 keys x NB head-dim blocks)
+        const int pn = p0 + kKT;  // first key of the next tile
+        auto fence = [&]() __attribute__((always_inline)) { __builtin_amdgcn_sched_barrier(0); };
+        auto rd_k = [&](int blk, int sl) __attribute__((always_inline)) -> bf16x8 {
+            return *(const __attribute__((address_space(3))) bf16x8*)(lds + k_rd[sl] + (RING * STAGEB + blk * 32 * ROWB));
+        };
+        auto rd_v = [&](int blk, int j) __attribute__((always_inline)) -> bf16x8 {  // j = cs * NB + b
+            const int off = RING * STAGEB + (blk * 32 + (j / NB) * 16) * ROWB;
+            const s16x4 f0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(lds + v_rd[j % NB][0] + off));
+            const s16x4 f1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(lds + v_rd[j % NB][1] + off));
+            return __builtin_bit_cast(bf16x8, __builtin_shufflevector(f0, f1, 0, 1, 2, 3, 4, 5, 6, 7));
+        };
+        // one piece of the next tile's load: block u of this wave, K (which = 0) then V (which = 1)
+        const unsigned char* row_base = nullptr;  // pool page (row inside the pool) or k_ext (row outside)
+        unsigned row_off = 0;                     // byte offset of the row from row_base
+        bool row_in_pool = true;
+        const unsigned x_stride32 = static_cast<unsigned>(x_stride);
+        auto load_piece = [&](int u, int which) __attribute__((always_inline)) {
+            const int blk = wave * UPW + u;
+            if (which == 0) {
+                const int pp = min(pn + blk * RPB + ld_rowl, kv_hi - 1);  // rows past the end repeat the last valid one
+                const unsigned sl = static_cast<unsigned>(min(max(sl_next[u], 0), num_slots - 1));
+                const unsigned page = sl >> page_shift;
+                const unsigned o = sl & static_cast<unsigned>(page_size - 1);
+                const unsigned char* pool_base = pool_g + static_cast<size_t>(page) * page_stride;
+                row_in_pool = pp < P;
+                row_base = row_in_pool ? pool_base : kx_g;
+                row_off = row_in_pool ? o * static_cast<unsigned>(ROWB) : static_cast<unsigned>(pp - P) * x_stride32;
+                load_to_lds_16(row_base + (row_off + ld_koff(u)), smem_addr + (RING ^ 1) * STAGEB + blk * 1024);
+            } else {
+                // V row: v_off32 past the K row inside the pool, the same row of v_ext outside
+                const unsigned char* vb_ = row_in_pool ? row_base : row_base + (vx_g - kx_g);
+                const unsigned vo = row_off + ld_voff(u) + (row_in_pool ? v_off32 : 0u);
+                load_to_lds_16(vb_ + vo, smem_addr + (RING ^ 1) * STAGEB + TILEB + blk * 1024);
+            }
+        };
+        // exponentials of elements 2 e, 2 e + 1 of a block's scores, and their share of the block maximum
+        auto exp_piece = [&](const f32x16& sc, int e, float neg_m, uint32_t (&pb)[RB][8], float& lsum, float& mx)
+                             __attribute__((always_inline)) {
+            const float x0 = sc[2 * e], x1 = sc[2 * e + 1];
+            const float a = __builtin_amdgcn_exp2f(fmaf(x0, scale_log2e, neg_m));
+            const float b = __builtin_amdgcn_exp2f(fmaf(x1, scale_log2e, neg_m));
+            const uint32_t pk = pack_bf16x2(a, b);
+            pb[0][e] = pk;
+            lsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk), ones, lsum, false);
+            mx = fmaxf(fmaxf(mx, x0), x1);
+        };
+
+        f32x16 sc0[RB], sc1[RB];
+        uint32_t pb0[RB][8], pb1[RB][8];
+        float mb[RB], ls[RB];
+        bf16x8 ka[KS], kb[KS], va[NPV], vb[NPV];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sc0[0][i] = sc1[0][i] = 0.f;
+
+        // ---- slots 0..KS-1: S0, next tile's loads ----
+#pragma unroll
+        for (int sl = 0; sl < kPD; ++sl) ka[sl] = rd_k(0, sl);
+        fence();
+#pragma unroll
+        for (int sl = 0; sl < KS; ++sl) {
+            sc0[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[sl], qreg[0][sl], sc0[0], 0, 0, 0);
+            if (sl + kPD < KS) ka[sl + kPD] = rd_k(0, sl + kPD);
+            else kb[sl + kPD - KS] = rd_k(1, sl + kPD - KS);
+            load_piece(sl / 2, sl % 2);  // also after the last tile (rows clamp to the last valid one): no branch
+            fence();
+        }
+        // ---- slots KS..2KS-1: S1, exponentials of block 0 ----
+        {
+            const float neg_m = (m_run[0] == -INFINITY) ? 0.f : -m_run[0];
+            float mx = -INFINITY, lsum = 0.f;
+#pragma unroll
+            for (int sl = 0; sl < KS; ++sl) {
+                sc1[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[sl], qreg[0][sl], sc1[0], 0, 0, 0);
+                if (sl + kPD < KS) kb[sl + kPD] = rd_k(1, sl + kPD);
+                else va[sl + kPD - KS] = rd_v(0, sl + kPD - KS);
+#pragma unroll
+                for (int e = sl * 8 / KS; e < (sl + 1) * 8 / KS; ++e) exp_piece(sc0[0], e, neg_m, pb0, lsum, mx);
+                if (sl < UPW) {  // slot of this lane's row in the tile after the next one (no branch: rows outside
+                                 // the prefix read a dummy word, their slot is never used)
+                    const int pp = min(pn + kKT + (wave * UPW + sl) * RPB + ld_rowl, kv_hi - 1);
+                    const int32_t* ap = pp < P ? slots + pp : prefix_len + r;
+                    sl_next[sl] = *ap;
+                }
+                fence();
+            }
+            mb[0] = row_max(mx) * scale_log2e;
+            ls[0] = lsum;
+            block_commit(sc0, mb, pb0, ls);
+        }
+        fence();
+        // ---- PV of block 0, exponentials of block 1 ----
+        {
+            const float neg_m = (m_run[0] == -INFINITY) ? 0.f : -m_run[0];
+            float mx = -INFINITY, lsum = 0.f;
+            bf16x8 pop[2];
+#pragma unroll
+            for (int cs = 0; cs < 2; ++cs)
+                pop[cs] = __builtin_bit_cast(bf16x8, make_uint4(pb0[0][cs * 4 + 0], pb0[0][cs * 4 + 1], pb0[0][cs * 4 + 2], pb0[0][cs * 4 + 3]));
+#pragma unroll
+            for (int j = 0; j < NPV; ++j) {
+                oacc[0][j % NB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[j], pop[j / NB], oacc[0][j % NB], 0, 0, 0);
+                if (j + kPDV < NPV) va[j + kPDV] = rd_v(0, j + kPDV);
+                else vb[j + kPDV - NPV] = rd_v(1, j + kPDV - NPV);
+#pragma unroll
+                for (int e = j * 8 / NPV; e < (j + 1) * 8 / NPV; ++e) exp_piece(sc1[0], e, neg_m, pb1, lsum, mx);
+                fence();
+            }
+            mb[0] = row_max(mx) * scale_log2e;
+            ls[0] = lsum;
+            block_commit(sc1, mb, pb1, ls);
+        }
+        fence();
+        // ---- PV of block 1 ----
+        {
+            bf16x8 pop[2];
+#pragma unroll
+            for (int cs = 0; cs < 2; ++cs)
+                pop[cs] = __builtin_bit_cast(bf16x8, make_uint4(pb1[0][cs * 4 + 0], pb1[0][cs * 4 + 1], pb1[0][cs * 4 + 2], pb1[0][cs * 4 + 3]));
+#pragma unroll
+            for (int j = 0; j < NPV; ++j) {
+                oacc[0][j % NB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[j], pop[j / NB], oacc[0][j % NB], 0, 0, 0);
+                if (j + kPDV < NPV) vb[j + kPDV] = rd_v(1, j + kPDV);
+                fence();
+            }
+        }
+    };
+
     // One tile.  Order of the matrix work: QK(block 0), QK(block 1), PV(block 0), PV(block 1); the exponentials
     // of block 0 are independent of QK(block 1) and those of block 1 of PV(block 0), so the scheduler can
     // run them in the shadow of those MFMAs.  The next tile's loads are issued after the first MFMAs so that
@@ -500,6 +651,17 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     auto tile_step = [&](int p0, auto ring_c) __attribute__((always_inline)) {
         constexpr int RING = decltype(ring_c)::value;
         const bool compute = wave_on && p0 <= P + wave_i_last;
+        if constexpr (RB == 1) {
+            bool no_mask = true;
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) no_mask &= p0 + kKT <= blk_vis_min[rb];
+            if (compute && no_mask && page_shift >= 0) {
+                tile_fast(p0, ring_c);
+                wait_vm_all();
+                wg_barrier();
+                return;
+            }
+        }
         f32x16 s0[RB], s1[RB];
         uint32_t pb0[RB][8], pb1[RB][8];
         float mb0[RB], mb1[RB], ls0[RB], ls1[RB];
@@ -672,6 +834,7 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
     using namespace pa;
     PA_REQUIRE(scale > 0.f && scale < INFINITY, "pa_extend_attention: scale must be positive and finite");
     PA_REQUIRE(num_slots <= INT32_MAX, "pa_extend_attention: num_slots exceeds the int32 range of slot ids");
+    PA_REQUIRE(static_cast<int64_t>(page_size) * Hkv * D * 4 < (int64_t{1} << 31), "pa_extend_attention: a page of %d tokens x %d heads is too large", page_size, Hkv);
     const ExtendPlan p = make_plan(B, T, max_kv_len, Hq, Hkv, D);
     if (workspace_bytes < p.total || workspace == nullptr)
         return fail(PA_ENOMEM, "pa_extend_attention: workspace of %zu bytes given, %zu needed", workspace_bytes, p.total);
