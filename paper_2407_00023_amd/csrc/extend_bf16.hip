@@ -202,6 +202,10 @@ __device__ __forceinline__ void wait_vm_all() {
 __device__ __forceinline__ void load_to_lds_16(const void* g, unsigned lds_addr) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory");
 }
+// The same with the global address given as a wave-uniform base plus a 32-bit unsigned byte offset per lane.
+__device__ __forceinline__ void load_to_lds_16(const void* base, unsigned off, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_addr) : "memory");
+}
 __device__ __forceinline__ unsigned lds_address(const void* p) {
     return static_cast<unsigned>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const unsigned char*)(p)));
 }
@@ -213,7 +217,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     const int32_t* __restrict__ slot_idx, const int32_t* __restrict__ slot_offsets,
     const int32_t* __restrict__ prefix_len, const int32_t* __restrict__ ext_len,
     const int32_t* __restrict__ ext_offsets, int Hq, int Hkv, int page_size, int page_shift, int num_slots,
-    float scale_log2e, __hip_bfloat16* __restrict__ out, const int32_t* __restrict__ n_tiles,
+    int fast_ok, float scale_log2e, __hip_bfloat16* __restrict__ out, const int32_t* __restrict__ n_tiles,
     const int32_t* __restrict__ tile_req, const int32_t* __restrict__ tile_row0, int nsplit, int chunk,
     float* __restrict__ part_o, float* __restrict__ part_ml) {
     constexpr int WR = 32 * RB;              // packed query rows per wave (RB blocks of 32)
@@ -511,9 +515,14 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     //   slots 24..31  O += V(block 1) P1      | -
     // Only for tiles that need no mask, with a power-of-two page size.
     // ------------------------------------------------------------------------------------------------
-    auto tile_fast = [&](int p0, auto ring_c) __attribute__((always_inline)) {
+    // EXT = the next tile lies wholly in the extend tokens (rows of k_ext / v_ext), else wholly in the prefix
+    // (rows of the pool; the host has checked that the pool spans less than 4 GB so that 32-bit offsets do).
+    const unsigned x_stride32 = static_cast<unsigned>(x_stride);
+    auto mul24 = [](unsigned a, unsigned b) __attribute__((always_inline)) { return __umul24(a, b); };
+    auto tile_fast = [&](int p0, auto ring_c, auto ext_c) __attribute__((always_inline)) {
         static_assert(KS == 2 * UPW || RB != 1, "slot plan assumes one tile-load piece per QK slot of block 0");
         constexpr int RING = decltype(ring_c)::value;
+        constexpr bool EXT = decltype(ext_c)::value;
         constexpr int kPD = 2;    // K fragments in flight ahead of their MFMA
         constexpr int kPDV = 2;   // V fragments in flight ahead of their MFMA
         constexpr int NPV = 2 * NB;  // MFMAs per PV block (2 groups of 16 keys x NB head-dim blocks)
@@ -528,28 +537,27 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
             const s16x4 f1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(lds + v_rd[j % NB][1] + off));
             return __builtin_bit_cast(bf16x8, __builtin_shufflevector(f0, f1, 0, 1, 2, 3, 4, 5, 6, 7));
         };
-        // one piece of the next tile's load: block u of this wave, K (which = 0) then V (which = 1)
-        const unsigned char* row_base = nullptr;  // pool page (row inside the pool) or k_ext (row outside)
-        unsigned row_off = 0;                     // byte offset of the row from row_base
-        bool row_in_pool = true;
-        const unsigned x_stride32 = static_cast<unsigned>(x_stride);
+        // one piece of the next tile's load: block u of this wave, K (which = 0) then V (which = 1);
+        // rows past the end of the key range repeat the last valid one
+        unsigned row_off = 0;  // byte offset of the row from the pool base (from k_ext of the request); low 8 bits clear
         auto load_piece = [&](int u, int which) __attribute__((always_inline)) {
             const int blk = wave * UPW + u;
+            const unsigned lds_k = smem_addr + (RING ^ 1) * STAGEB + blk * 1024;
             if (which == 0) {
-                const int pp = min(pn + blk * RPB + ld_rowl, kv_hi - 1);  // rows past the end repeat the last valid one
-                const unsigned sl = static_cast<unsigned>(min(max(sl_next[u], 0), num_slots - 1));
-                const unsigned page = sl >> page_shift;
-                const unsigned o = sl & static_cast<unsigned>(page_size - 1);
-                const unsigned char* pool_base = pool_g + static_cast<size_t>(page) * page_stride;
-                row_in_pool = pp < P;
-                row_base = row_in_pool ? pool_base : kx_g;
-                row_off = row_in_pool ? o * static_cast<unsigned>(ROWB) : static_cast<unsigned>(pp - P) * x_stride32;
-                load_to_lds_16(row_base + (row_off + ld_koff(u)), smem_addr + (RING ^ 1) * STAGEB + blk * 1024);
+                if constexpr (EXT) {
+                    const int pp = min(pn + blk * RPB + ld_rowl, kv_hi - 1);
+                    row_off = mul24(static_cast<unsigned>(pp - P), x_stride32);
+                    load_to_lds_16(kx_g, row_off | ld_koff(u), lds_k);
+                } else {
+                    const unsigned sl = static_cast<unsigned>(min(max(sl_next[u], 0), num_slots - 1));
+                    const unsigned page = sl >> page_shift;
+                    const unsigned o = sl & static_cast<unsigned>(page_size - 1);
+                    row_off = mul24(page, page_stride) + (o << (D == 128 ? 8 : 7));
+                    load_to_lds_16(pool_g, row_off | ld_koff(u), lds_k);
+                }
             } else {
-                // V row: v_off32 past the K row inside the pool, the same row of v_ext outside
-                const unsigned char* vb_ = row_in_pool ? row_base : row_base + (vx_g - kx_g);
-                const unsigned vo = row_off + ld_voff(u) + (row_in_pool ? v_off32 : 0u);
-                load_to_lds_16(vb_ + vo, smem_addr + (RING ^ 1) * STAGEB + TILEB + blk * 1024);
+                if constexpr (EXT) load_to_lds_16(vx_g, row_off | ld_voff(u), lds_k + TILEB);
+                else load_to_lds_16(pool_g, (row_off | ld_voff(u)) + v_off32, lds_k + TILEB);
             }
         };
         // exponentials of elements 2 e, 2 e + 1 of a block's scores, and their share of the block maximum
@@ -564,9 +572,23 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
             mx = fmaxf(fmaxf(mx, x0), x1);
         };
 
+        // mx = this lane's maximum over its 16 keys of the block: some lane of a row sees the row maximum, so
+        // "no lane outgrew the running maximum" needs no exchange between the halves of a row
+        auto commit_light = [&](const f32x16 (&sc)[RB], float mx, uint32_t (&pb)[RB][8], float (&lsum)[RB])
+                                __attribute__((always_inline)) {
+            asm volatile("" : "+v"(pb[0][0]), "+v"(pb[0][1]), "+v"(pb[0][2]), "+v"(pb[0][3]), "+v"(pb[0][4]), "+v"(pb[0][5]),
+                         "+v"(pb[0][6]), "+v"(pb[0][7]), "+v"(lsum[0]));
+            if (__any(mx * scale_log2e > m_run[0] + kRescaleThreshold)) {
+                float m_blk[RB];
+                m_blk[0] = row_max(mx) * scale_log2e;
+                block_commit(sc, m_blk, pb, lsum);
+            } else {
+                l_run[0] += lsum[0];
+            }
+        };
         f32x16 sc0[RB], sc1[RB];
         uint32_t pb0[RB][8], pb1[RB][8];
-        float mb[RB], ls[RB];
+        float ls[RB];
         bf16x8 ka[KS], kb[KS], va[NPV], vb[NPV];
 #pragma unroll
         for (int i = 0; i < 16; ++i) sc0[0][i] = sc1[0][i] = 0.f;
@@ -594,17 +616,16 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
                 else va[sl + kPD - KS] = rd_v(0, sl + kPD - KS);
 #pragma unroll
                 for (int e = sl * 8 / KS; e < (sl + 1) * 8 / KS; ++e) exp_piece(sc0[0], e, neg_m, pb0, lsum, mx);
-                if (sl < UPW) {  // slot of this lane's row in the tile after the next one (no branch: rows outside
-                                 // the prefix read a dummy word, their slot is never used)
-                    const int pp = min(pn + kKT + (wave * UPW + sl) * RPB + ld_rowl, kv_hi - 1);
-                    const int32_t* ap = pp < P ? slots + pp : prefix_len + r;
-                    sl_next[sl] = *ap;
+                if (!EXT && sl < UPW) {
+                    // slot of this lane's row in the tile after the next one; rows outside the prefix read the
+                    // last prefix slot and never use it (P >= 1 here: the next tile is a prefix tile)
+                    const int pp = min(pn + kKT + (wave * UPW + sl) * RPB + ld_rowl, P - 1);
+                    sl_next[sl] = slots[pp];
                 }
                 fence();
             }
-            mb[0] = row_max(mx) * scale_log2e;
             ls[0] = lsum;
-            block_commit(sc0, mb, pb0, ls);
+            commit_light(sc0, mx, pb0, ls);
         }
         fence();
         // ---- PV of block 0, exponentials of block 1 ----
@@ -624,9 +645,8 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
                 for (int e = j * 8 / NPV; e < (j + 1) * 8 / NPV; ++e) exp_piece(sc1[0], e, neg_m, pb1, lsum, mx);
                 fence();
             }
-            mb[0] = row_max(mx) * scale_log2e;
             ls[0] = lsum;
-            block_commit(sc1, mb, pb1, ls);
+            commit_light(sc1, mx, pb1, ls);
         }
         fence();
         // ---- PV of block 1 ----
@@ -655,11 +675,21 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
             bool no_mask = true;
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) no_mask &= p0 + kKT <= blk_vis_min[rb];
-            if (compute && no_mask && page_shift >= 0) {
-                tile_fast(p0, ring_c);
-                wait_vm_all();
-                wg_barrier();
-                return;
+            if (compute && no_mask && fast_ok) {
+                // kind of the next tile (its rows clamp to the last valid key): wholly prefix, wholly extend, or mixed
+                const int first = min(p0 + kKT, kv_hi - 1), last = min(p0 + 2 * kKT - 1, kv_hi - 1);
+                if (last < P) {
+                    tile_fast(p0, ring_c, std::false_type{});
+                    wait_vm_all();
+                    wg_barrier();
+                    return;
+                }
+                if (first >= P) {
+                    tile_fast(p0, ring_c, std::true_type{});
+                    wait_vm_all();
+                    wg_barrier();
+                    return;
+                }
             }
         }
         f32x16 s0[RB], s1[RB];
@@ -792,7 +822,7 @@ template <int D, int NW, int RB>
 static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_ext, const void* v_ext,
                          const void* kv_pool, const int32_t* slot_idx, const int32_t* slot_offsets,
                          const int32_t* prefix_len, const int32_t* ext_len, const int32_t* ext_offsets, int Hq, int Hkv,
-                         int page_size, int64_t num_slots, float scale_log2e, void* out, int32_t* n_tiles,
+                         int page_size, int64_t num_slots, int64_t T_total, float scale_log2e, void* out, int32_t* n_tiles,
                          int32_t* tile_req, int32_t* tile_row0, float* part_o, float* part_ml, hipStream_t stream) {
     constexpr size_t lds_bytes = static_cast<size_t>(kStages) * 2 * kKT * D * 2;
     int page_shift = -1;
@@ -801,13 +831,20 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
         while ((1 << page_shift) < page_size) ++page_shift;
     }
     const dim3 grid(static_cast<unsigned>(p.tiles_cap) * p.nsplit * Hkv);
+    // The hand-scheduled tile addresses K/V rows with 32-bit byte offsets and 24-bit multiplies: it needs a
+    // power-of-two page size, a pool below 4 GB, and extend tensors below 4 GB.
+    const int64_t rowb = static_cast<int64_t>(D) * 2;
+    const int64_t pool_bytes = num_slots * 2 * Hkv * rowb;
+    const int64_t page_bytes = static_cast<int64_t>(page_size) * 2 * Hkv * rowb;
+    const int fast_ok = page_shift >= 0 && pool_bytes < (int64_t{1} << 32) && page_bytes < (1 << 24) &&
+                        num_slots / page_size < (1 << 24) && T_total < (1 << 24) && T_total * Hkv * rowb < (int64_t{1} << 32);
     {
         ProfScope prof(kProfExtend, stream);
         hipLaunchKernelGGL((extend_bf16_kernel<D, NW, RB>), grid, dim3(NW * 64), lds_bytes, stream,
                            static_cast<const __hip_bfloat16*>(q_ext), static_cast<const __hip_bfloat16*>(k_ext),
                            static_cast<const __hip_bfloat16*>(v_ext), static_cast<const __hip_bfloat16*>(kv_pool), slot_idx,
                            slot_offsets, prefix_len, ext_len, ext_offsets, Hq, Hkv, page_size, page_shift,
-                           static_cast<int>(num_slots), scale_log2e, static_cast<__hip_bfloat16*>(out), n_tiles, tile_req,
+                           static_cast<int>(num_slots), fast_ok, scale_log2e, static_cast<__hip_bfloat16*>(out), n_tiles, tile_req,
                            tile_row0, p.nsplit, p.chunk, part_o, part_ml);
     }
     if (p.nsplit > 1) {
@@ -854,10 +891,10 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
     }
     if (D == 64)
         launch_extend<64, 4, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, Hq,
-                             Hkv, page_size, num_slots, scale_log2e, out, n_tiles, tile_req, tile_row0, part_o, part_ml, stream);
+                             Hkv, page_size, num_slots, T, scale_log2e, out, n_tiles, tile_req, tile_row0, part_o, part_ml, stream);
     else
         launch_extend<128, 4, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, Hq,
-                              Hkv, page_size, num_slots, scale_log2e, out, n_tiles, tile_req, tile_row0, part_o, part_ml, stream);
+                              Hkv, page_size, num_slots, T, scale_log2e, out, n_tiles, tile_req, tile_row0, part_o, part_ml, stream);
     PA_HIP(hipGetLastError());
     return PA_OK;
 }
