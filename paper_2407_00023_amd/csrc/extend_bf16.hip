@@ -468,10 +468,19 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
                 const float m_new = fmaxf(m_run[rb], m_blk[rb]);
                 const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - ((m_new == -INFINITY) ? 0.f : m_new));
                 l_run[rb] *= alpha;
+                // The accumulators are scaled IN PLACE (tied asm operands): written as ordinary multiplies, the
+                // scaled values get new registers and the join after this rare branch copies all of them on the
+                // common path.  The s_nops cover the wait states between an MFMA write of the accumulators and a
+                // vector-ALU read, which the compiler does not insert for operands of inline assembly.
+                asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
 #pragma unroll
                 for (int b = 0; b < NB; ++b)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) oacc[rb][b][i] *= alpha;
+                    for (int i = 0; i < 16; ++i) {
+                        float x = oacc[rb][b][i];
+                        asm volatile("v_mul_f32 %0, %0, %1" : "+v"(x) : "v"(alpha));
+                        oacc[rb][b][i] = x;
+                    }
                 m_run[rb] = m_new;
             }
             block_exp(sacc, pb, lsum);
