@@ -233,6 +233,47 @@ def test_extend_random_shapes(pa, gpu_device, dtype, Hq, Hkv, D, page, p_hi, e_h
     assert err <= TOL[dtype]
 
 
+@pytest.mark.parametrize("direction", ["growing", "shrinking"])
+def test_extend_running_maximum_rescale(pa, gpu_device, direction):
+    """Scores whose magnitude grows (or shrinks) along the key axis by far more than the lag the kernel allows its
+    running maximum: the accumulators have to be rescaled many times after the first tile (the online-softmax
+    path that random N(0,1) data never takes).  Same bar as everywhere: 2e-2 against the fp64 oracle."""
+    import oracle
+    rng = np.random.default_rng(21)
+    Hq, Hkv, D, page, nslots, B = 8, 2, 128, 16, 8192, 3
+    c = _random_case(rng, B, Hq, Hkv, D, 1500, 150, "bf16", page, nslots)
+    # multiply key j of every request by a ramp, so that |q.k| scale sweeps over two orders of magnitude
+    def ramp(n):
+        r = np.linspace(0.05, 6.0, max(n, 1))[:n]
+        return r if direction == "growing" else r[::-1]
+    pk = W.bf16_bits_to_f32(c["pk"]).copy()
+    k = W.bf16_bits_to_f32(c["k"]).copy()
+    cur = 0
+    for r in range(B):
+        P, E = int(c["P"][r]), int(c["E"][r])
+        f = ramp(P + E)
+        pk[cur:cur + P] *= f[:P, None, None]
+        k[c["eo"][r]:c["eo"][r] + E] *= f[P:, None, None]
+        cur += P
+    c["pk"], c["k"] = W.f32_to_bf16_bits(pk), W.f32_to_bf16_bits(k)
+    dev = gpu_device
+    pool = torch.zeros(pa.kv_pool_bytes(nslots, Hkv, D, torch.bfloat16, page), dtype=torch.uint8, device=dev)
+    kw = dict(page_size=page, num_slots=nslots)
+    pa.append_kv(pool, torch.from_numpy(c["backed"]).to(dev), to_torch(c["pk"], "bf16", dev), to_torch(c["pv"], "bf16", dev), **kw)
+    tt = lambda a: torch.from_numpy(a).to(dev)
+    scale = 1.0 / np.sqrt(D)
+    out = pa.extend_attention(to_torch(c["q"], "bf16", dev), to_torch(c["k"], "bf16", dev), to_torch(c["v"], "bf16", dev), pool,
+                              tt(c["si"]), tt(c["off"]), tt(c["P"]), tt(c["E"]), tt(c["eo"]), scale,
+                              max_kv_len=int((c["P"] + c["E"]).max()), **kw)
+    torch.cuda.synchronize()
+    opk, opv = oracle.new_pool(nslots, Hkv, D, "bf16")
+    oracle.append_kv(opk, opv, c["backed"], c["pk"], c["pv"], "bf16")
+    ref = oracle.extend_attention(c["q"], c["k"], c["v"], opk, opv, c["si"], c["off"], c["P"], c["E"], c["eo"], scale, "bf16")
+    err = np.abs(out_to_f64(out) - ref).max()
+    say(f"  {direction}: max abs err {err:.3e}")
+    assert np.isfinite(out_to_f64(out)).all() and err <= TOL["bf16"]
+
+
 def test_extend_slot_permutation_invariance(pa, gpu_device):
     """Moving the cached rows to other slots (and renaming slot_idx accordingly) must not change a single bit."""
     wl = W.small_variant("tool_use", 3)
