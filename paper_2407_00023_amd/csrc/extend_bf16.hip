@@ -799,32 +799,32 @@ __global__ __launch_bounds__(256) void extend_merge_kernel(const int32_t* __rest
     split_range(kv_end, chunk, nsplit, 0, n_act, lo, hi);
     if (n_act <= 1) return;
     const int64_t e0 = ext_offsets[r];
-    constexpr int V4 = D / 4;
-    for (int x = threadIdx.x; x < rows_here * V4; x += 256) {
-        const int lrow = x / V4, c = x % V4;
-        float m = -INFINITY;
-        for (int s = 0; s < n_act; ++s) {
-            const size_t unit = (static_cast<size_t>(t) * nsplit + s) * Hkv + g;
-            m = fmaxf(m, part_ml[(unit * mt + lrow) * 2]);
-        }
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        float l = 0.f;
-        for (int s = 0; s < n_act; ++s) {
-            const size_t unit = (static_cast<size_t>(t) * nsplit + s) * Hkv + g;
-            const float ms = part_ml[(unit * mt + lrow) * 2];
-            const float w = (ms == -INFINITY) ? 0.f : exp2f(ms - m);
-            l += w * part_ml[(unit * mt + lrow) * 2 + 1];
-            const float4 o = reinterpret_cast<const float4*>(part_o + (unit * mt + lrow) * D)[c];
-            acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
-        }
-        const float inv = 1.f / l;
-        const int rho = row0 + lrow;
-        __hip_bfloat16* orow = out + ((e0 + rho / G) * Hq + g * G + rho % G) * static_cast<int64_t>(D);
-        uint2 v;
-        v.x = pack_bf16x2(acc.x * inv, acc.y * inv);
-        v.y = pack_bf16x2(acc.z * inv, acc.w * inv);
-        reinterpret_cast<uint2*>(orow)[c] = v;
+    constexpr int V4 = D / 4;           // 16-byte pieces per partial row
+    constexpr int RPBK = 256 / V4;      // rows per block: one thread per (row, piece)
+    const int lrow = blockIdx.z * RPBK + threadIdx.x / V4, c = threadIdx.x % V4;
+    if (lrow >= rows_here) return;
+    float m = -INFINITY;
+    for (int s = 0; s < n_act; ++s) {
+        const size_t unit = (static_cast<size_t>(t) * nsplit + s) * Hkv + g;
+        m = fmaxf(m, part_ml[(unit * mt + lrow) * 2]);
     }
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float l = 0.f;
+    for (int s = 0; s < n_act; ++s) {
+        const size_t unit = (static_cast<size_t>(t) * nsplit + s) * Hkv + g;
+        const float2 ml = reinterpret_cast<const float2*>(part_ml)[unit * mt + lrow];
+        const float w = (ml.x == -INFINITY) ? 0.f : exp2f(ml.x - m);
+        l += w * ml.y;
+        const float4 o = reinterpret_cast<const float4*>(part_o + (unit * mt + lrow) * D)[c];
+        acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
+    }
+    const float inv = 1.f / l;
+    const int rho = row0 + lrow;
+    __hip_bfloat16* orow = out + ((e0 + rho / G) * Hq + g * G + rho % G) * static_cast<int64_t>(D);
+    uint2 v;
+    v.x = pack_bf16x2(acc.x * inv, acc.y * inv);
+    v.y = pack_bf16x2(acc.z * inv, acc.w * inv);
+    reinterpret_cast<uint2*>(orow)[c] = v;
 }
 
 template <int D, int NW, int RB>
@@ -858,7 +858,7 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
     }
     if (p.nsplit > 1) {
         ProfScope prof(kProfMerge, stream);
-        hipLaunchKernelGGL((extend_merge_kernel<D>), dim3(p.tiles_cap, Hkv), dim3(256), 0, stream, prefix_len, ext_len,
+        hipLaunchKernelGGL((extend_merge_kernel<D>), dim3(p.tiles_cap, Hkv, (32 * RB * NW) / (256 / (D / 4))), dim3(256), 0, stream, prefix_len, ext_len,
                            ext_offsets, Hq, Hkv, static_cast<__hip_bfloat16*>(out), n_tiles, tile_req, tile_row0, 32 * RB * NW,
                            p.nsplit, p.chunk, part_o, part_ml);
     }
