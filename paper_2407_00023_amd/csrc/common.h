@@ -32,6 +32,17 @@ inline bool shape_ok(int Hq, int Hkv, int D) {
     return Hkv > 0 && Hq > 0 && Hq % Hkv == 0 && (D == 64 || D == 128);
 }
 
+// Entry of the positional index of the flattened tree (see DeviceTree).
+struct __attribute__((aligned(32))) PathEntry {
+    unsigned long long hash;  // of the token path up to and including the first token of the node's edge
+    int32_t depth;            // depth of that token
+    int32_t node;             // -1 = empty entry
+    int32_t edge_start;       // index of the node's first edge token in edge_tok / edge_slot
+    int32_t edge_len;
+    int32_t parent;
+    int32_t pad;
+};
+
 // Flattened radix tree in device memory.
 //   Node n (0 = the empty virtual root) owns edge tokens edge_tok[node_start[n] .. +node_len[n])
 //   and, in parallel, the KV slot of each of those tokens in edge_slot.
@@ -47,6 +58,15 @@ struct DeviceTree {
     const int32_t* ht_val;
     uint32_t ht_mask;
     int32_t n_nodes;
+    // Second index, by position: a node is also reachable through the hash of the whole token path from
+    // the root up to and including the FIRST token of its edge, together with the depth of that token.
+    // A prompt can therefore look up every node boundary on its path at once from its own prefix hashes.
+    //   ph_entry: open addressing, linear probing, empty = node -1, mask = ph_mask; one 32-byte entry holds
+    //             everything a lookup needs, so that a probe is a single memory round trip
+    //   node_endhash[n] = hash of the path up to and including the LAST token of the node's edge
+    const PathEntry* ph_entry;
+    const unsigned long long* node_endhash;
+    uint32_t ph_mask;
 };
 
 constexpr unsigned long long kEmptyKey = ~0ull;
@@ -57,6 +77,15 @@ __host__ __device__ inline uint32_t hash_key(unsigned long long k) {
     k ^= k >> 27; k *= 0x94d049bb133111ebull;
     k ^= k >> 31;
     return static_cast<uint32_t>(k);
+}
+
+// Polynomial hash of a token path: h(empty) = 0, h(p + t) = h(p) * kPathHashBase + (uint32(t) + 1), mod 2^64.
+constexpr unsigned long long kPathHashBase = 0x9E3779B97F4A7C15ull;  // odd
+__host__ __device__ inline unsigned long long path_hash_push(unsigned long long h, int32_t tok) {
+    return h * kPathHashBase + (static_cast<unsigned long long>(static_cast<uint32_t>(tok)) + 1ull);
+}
+__host__ __device__ inline uint32_t path_slot(unsigned long long h, int32_t depth) {
+    return hash_key(h ^ (static_cast<unsigned long long>(static_cast<uint32_t>(depth)) * 0xD6E8FEB86659FD93ull));
 }
 
 // Pool layout: [page][K=0 | V=1][kv head][token in page][D] elements.

@@ -2,19 +2,15 @@
 //
 // Algorithm 1 of the paper starts by matching the request to the radix tree and taking
 // cached_len = the sum of the matched lengths along the path; Sec. 3.2 defines the match as
-// "from the beginning until no match exists", a partly matched node counting for the
-// tokens that do match.  One workgroup walks one request: the child of the current node is
-// found through a 64-lane-wide probe of the hash table, then the whole workgroup compares
-// the child's edge against the prompt, kTokPerRound tokens per round trip to memory, and
-// copies the edge's KV slots into the output as it goes.
+// running from the beginning until no match exists, a partly matched node counting for the
+// tokens that do match.  One workgroup of 1024 threads matches one request.  The child of the
+// current node is found through a 64-lane-wide probe of the (parent, first token) table.  If its edge is
+// long, the whole workgroup compares it against the prompt, 4096 tokens per round trip to memory,
+// copying the edge's KV slots to the output as it goes.  If it is short, the path is likely to run
+// through many short nodes, and a window of 1024 prompt positions is resolved at once (below).
 #include "common.h"
 
 namespace pa {
-
-constexpr int kMatchThreads = 1024;
-constexpr int kMatchUnroll = 4;
-constexpr int kTokPerRound = kMatchThreads * kMatchUnroll;
-constexpr int kMatchWaves = kMatchThreads / 64;
 
 // Child of `node` whose edge starts with `tok`, or -1.  Executed by a full wave; every lane returns the result.
 __device__ __forceinline__ int32_t find_child(const DeviceTree& t, int32_t node, int32_t tok) {
@@ -38,61 +34,271 @@ __device__ __forceinline__ int32_t find_child(const DeviceTree& t, int32_t node,
     return -1;
 }
 
-__global__ __launch_bounds__(kMatchThreads) void match_prefixes_kernel(DeviceTree t, const int32_t* __restrict__ tokens,
-                                                                      const int32_t* __restrict__ offsets,
-                                                                      int32_t* __restrict__ prefix_len,
-                                                                      int32_t* __restrict__ slot_idx) {
-    __shared__ int32_t s_first_mismatch[2][kMatchWaves];
+// ---------------------------------------------------------------------------------------------------
+// Windows: all node boundaries of a stretch of the prompt's path at once, instead of one node after the
+// other (a step from node to node costs several dependent memory round trips; a path through a tree with
+// many branch points has hundreds of nodes).
+//
+// The tree carries a second index: node -> (hash of the token path up to and including the first token
+// of the node's edge, depth of that token).  A window is the kWin prompt positions from the current match
+// position on.  The workgroup forms the prefix hash of the prompt at every position of the window (a scan
+// seeded with the stored hash of the path that ends at the current node) and looks every (hash, position)
+// up: a hit NOMINATES a node whose edge would start there.  The edges of all nominated nodes are compared
+// with the prompt in parallel.  Then the nodes that really lie on the path are marked by pointer doubling
+// over the links "edge fully matched, and the node nominated at its end names this node as its parent",
+// starting from position 0, which holds the child found exactly.  The slots of all marked nodes are copied
+// in parallel.  Whatever ends the chain (a mismatch, no nomination, a very long edge, the window's end), the
+// loop head takes over from the last confirmed position with an exact child lookup, so the result never
+// depends on the hash being free of collisions: a collision can only cost time.
+// ---------------------------------------------------------------------------------------------------
+constexpr int kWin = 1024;        // prompt positions per window = threads per workgroup
+constexpr int kGroupEdge = 64;    // edges with at most this many tokens to compare are compared by 16 lanes, in one round
+constexpr int kWaveEdge = 1024;   // ... by one wave, 256 tokens per round; longer ones by the whole workgroup
+constexpr int kDirectEdge = 256;  // a next edge at least this long is compared directly, without opening a window
+constexpr int kWideUnroll = 4;    // tokens per thread and round of a wave- or workgroup-wide comparison
+
+// Workgroup barrier that orders LDS accesses only.  __syncthreads() also waits until the global stores of
+// the slot ids are acknowledged, a long round trip the matcher has no reason to wait for.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+__global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, const int32_t* __restrict__ tokens,
+                                                                 const int32_t* __restrict__ offsets,
+                                                                 int32_t* __restrict__ prefix_len,
+                                                                 int32_t* __restrict__ slot_idx) {
+    constexpr int kWaves = kWin / 64;
+    __shared__ unsigned long long s_wtot[kWaves];
+    // per window position: {candidate node or -1, its parent, its edge length, tokens of the edge that match the
+    // prompt (-2 = not compared yet: very long edge)}
+    __shared__ int4 s_rec[kWin];
+    __shared__ int32_t s_es[kWin];      // index of the candidate's first edge token
+    __shared__ int32_t s_list[kWin];    // window positions of candidates compared by 16 lanes
+    __shared__ int32_t s_list2[kWin];   // ... by one wave
+    __shared__ int32_t s_jump[kWin];    // position reached from a window position after 2^round valid hops, -1 = none
+    __shared__ int32_t s_mark[kWin];    // 1 = the position starts a node on the prompt's path
+    __shared__ int32_t s_wmax[kWaves];
+    __shared__ int32_t s_count, s_count2;
+    __shared__ int32_t s_red[2][kWaves];
     const int r = blockIdx.x;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int32_t base = offsets[r];
     const int32_t n = offsets[r + 1] - base;
     const int32_t* __restrict__ prompt = tokens + base;
     int32_t* __restrict__ out_slots = slot_idx + base;
 
-    int32_t pos = 0, node = 0;
-    int round = 0;
-    while (pos < n) {
-        const int32_t child = find_child(t, node, prompt[pos]);
+    // B^(2^k), and B^(lane + 1)
+    unsigned long long bp2[7];
+    bp2[0] = kPathHashBase;
+#pragma unroll
+    for (int k = 1; k < 7; ++k) bp2[k] = bp2[k - 1] * bp2[k - 1];
+    unsigned long long bpow_lane1 = 1ull;
+#pragma unroll
+    for (int k = 0; k < 7; ++k)
+        if ((lane + 1) >> k & 1) bpow_lane1 *= bp2[k];
+
+    int32_t pos = 0, cur = 0;        // matched so far; node whose edge ends at pos
+    int red_round = 0;
+    bool done = false;
+    while (!done && pos < n) {
+        // The next node, found exactly (child table keyed by parent and first token).  A long edge is compared
+        // right away by the whole workgroup; a short one opens a window.
+        const int32_t child = find_child(t, cur, prompt[pos]);
         if (child < 0) break;
-        const int32_t es = t.node_start[child];
-        const int32_t el = t.node_len[child];
-        const int32_t lim = min(el, n - pos);  // tokens of this edge that can match at all
-        int32_t matched = lim;                 // becomes the index of the first mismatch, if any
-        for (int32_t c0 = 0; c0 < lim; c0 += kTokPerRound) {
-            int32_t mine = INT32_MAX;
-            int32_t et[kMatchUnroll], pt[kMatchUnroll], sl[kMatchUnroll];
+        const int32_t c_es = t.node_start[child];
+        const int32_t c_len = t.node_len[child];
+        if (c_len >= kDirectEdge) {
+            const int32_t lim = min(c_len, n - pos);
+            int32_t m = lim;
+            for (int32_t c0 = 0; c0 < lim; c0 += kWin * kWideUnroll) {
+                int32_t et[kWideUnroll], pt[kWideUnroll], sl[kWideUnroll];
 #pragma unroll
-            for (int u = 0; u < kMatchUnroll; ++u) {
-                const int32_t k = c0 + u * kMatchThreads + tid;
-                const bool in = k < lim;
-                et[u] = in ? t.edge_tok[es + k] : 0;
-                pt[u] = in ? prompt[pos + k] : 0;
-                sl[u] = in ? t.edge_slot[es + k] : 0;
-            }
-#pragma unroll
-            for (int u = kMatchUnroll - 1; u >= 0; --u) {
-                const int32_t k = c0 + u * kMatchThreads + tid;
-                if (k < lim) {
-                    out_slots[pos + k] = sl[u];  // entries past the final match are unspecified by contract
-                    if (et[u] != pt[u]) mine = k;
+                for (int u = 0; u < kWideUnroll; ++u) {
+                    const int32_t k = c0 + u * kWin + tid;
+                    const bool in = k < lim;
+                    et[u] = in ? t.edge_tok[c_es + k] : 0;
+                    pt[u] = in ? prompt[pos + k] : 0;
+                    sl[u] = in ? t.edge_slot[c_es + k] : 0;
                 }
+                int32_t mine = INT32_MAX;
+#pragma unroll
+                for (int u = kWideUnroll - 1; u >= 0; --u) {
+                    const int32_t k = c0 + u * kWin + tid;
+                    if (k < lim) {
+                        out_slots[pos + k] = sl[u];  // entries past the final match are unspecified by contract
+                        if (et[u] != pt[u]) mine = k;
+                    }
+                }
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) mine = min(mine, __shfl_xor(mine, off));
+                if (lane == 0) s_red[red_round & 1][wave] = mine;
+                lds_barrier();
+                int32_t first = INT32_MAX;
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) first = min(first, s_red[red_round & 1][w]);
+                ++red_round;
+                if (first != INT32_MAX) { m = first; break; }
             }
-            // workgroup minimum of `mine`: wave reduction, then one LDS slot per wave (double-buffered by round)
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) mine = min(mine, __shfl_xor(mine, off));
-            if (lane == 0) s_first_mismatch[round & 1][wave] = mine;
-            __syncthreads();
-            int32_t first = INT32_MAX;
-#pragma unroll
-            for (int w = 0; w < kMatchWaves; ++w) first = min(first, s_first_mismatch[round & 1][w]);
-            ++round;
-            if (first != INT32_MAX) { matched = first; break; }
+            pos += m;
+            if (m < c_len) break;  // mismatch inside the edge, or the prompt ended inside it
+            cur = child;
+            continue;
         }
-        pos += matched;
-        if (matched < el) break;  // mismatch inside the edge, or the prompt ended inside it
-        node = child;
+        const unsigned long long h = t.node_endhash[cur];  // hash of prompt[0 .. pos)
+        const int32_t w0 = pos;
+        const int32_t p = w0 + tid;
+        // ---- A. prefix hashes of the window: inclusive scan of x -> x * B + (token + 1); within a wave by
+        // shuffles (after step k a lane holds the hash of the 2^(k+1) positions ending at it), then across waves
+        unsigned long long c = p < n ? static_cast<unsigned long long>(static_cast<uint32_t>(prompt[p])) + 1ull : 0ull;
+#pragma unroll
+        for (int k = 0; k < 6; ++k) {
+            const unsigned long long left = __shfl_up(c, 1u << k);
+            if (lane >= (1 << k)) c = left * bp2[k] + c;
+        }
+        if (lane == 63) s_wtot[wave] = c;
+        if (tid == 0) { s_count = 0; s_count2 = 0; }
+        lds_barrier();
+        unsigned long long before = h;  // hash of everything before this wave's 64 positions
+        for (int v = 0; v < wave; ++v) before = before * bp2[6] + s_wtot[v];
+        const unsigned long long hp = before * bpow_lane1 + c;  // hash of prompt[0 .. p]
+        // ---- B. candidates: nodes whose edge starts at p after exactly this prefix (by hash) ----
+        int4 rec = make_int4(-1, -1, 0, 0);
+        if (p < n) {
+            uint32_t at = path_slot(hp, p) & t.ph_mask;
+            for (uint32_t probes = 0; probes <= t.ph_mask; ++probes) {
+                const uint4 lo = reinterpret_cast<const uint4*>(t.ph_entry + at)[0];  // hash, depth, node
+                const int32_t nd = static_cast<int32_t>(lo.w);
+                if (nd < 0) break;
+                const unsigned long long eh = (static_cast<unsigned long long>(lo.y) << 32) | lo.x;
+                if (eh == hp && static_cast<int32_t>(lo.z) == p) {
+                    const uint4 hi = reinterpret_cast<const uint4*>(t.ph_entry + at)[1];  // edge start, length, parent
+                    rec = make_int4(nd, static_cast<int32_t>(hi.z), static_cast<int32_t>(hi.y), -2);
+                    s_es[tid] = static_cast<int32_t>(hi.x);
+                    break;
+                }
+                at = (at + 1) & t.ph_mask;
+            }
+        }
+        if (tid == 0) {  // position 0 holds the node found exactly above, whatever the probe said
+            rec = make_int4(child, cur, c_len, -2);
+            s_es[0] = c_es;
+        }
+        s_rec[tid] = rec;
+        if (rec.x >= 0) {
+            const int32_t lim = min(rec.z, n - p);
+            if (lim <= kGroupEdge) s_list[atomicAdd(&s_count, 1)] = tid;
+            else if (lim <= kWaveEdge) s_list2[atomicAdd(&s_count2, 1)] = tid;
+        }
+        lds_barrier();
+        // ---- C. compare the candidates' edges with the prompt, all candidates at once ----
+        {
+            const int n1 = s_count, n2 = s_count2;
+            const int sub = tid & 15;
+            for (int j = tid >> 4; j < n1; j += kWin / 16) {  // 16 lanes per candidate, one round of <= 64 tokens
+                const int rel = s_list[j];
+                const int32_t es = s_es[rel];
+                const int32_t lim = min(s_rec[rel].z, n - (w0 + rel));
+                bool bad[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int32_t k = sub + 16 * u;
+                    bad[u] = k < lim && t.edge_tok[es + k] != prompt[w0 + rel + k];
+                }
+                int32_t m = lim;
+#pragma unroll
+                for (int u = 3; u >= 0; --u) {
+                    const unsigned mine = static_cast<unsigned>(__ballot(bad[u]) >> (lane & 48)) & 0xFFFFu;
+                    if (mine) m = 16 * u + __ffs(mine) - 1;
+                }
+                if (sub == 0) s_rec[rel].w = m;
+            }
+            for (int j = wave; j < n2; j += kWaves) {  // one wave per candidate, 256 tokens per round
+                const int rel = s_list2[j];
+                const int32_t es = s_es[rel];
+                const int32_t lim = min(s_rec[rel].z, n - (w0 + rel));
+                int32_t m = lim;
+                for (int32_t c0 = 0; c0 < lim; c0 += 64 * kWideUnroll) {
+                    bool bad[kWideUnroll];
+#pragma unroll
+                    for (int u = 0; u < kWideUnroll; ++u) {
+                        const int32_t k = c0 + 64 * u + lane;
+                        bad[u] = k < lim && t.edge_tok[es + k] != prompt[w0 + rel + k];
+                    }
+                    int32_t first = -1;
+#pragma unroll
+                    for (int u = kWideUnroll - 1; u >= 0; --u) {
+                        const unsigned long long b = __ballot(bad[u]);
+                        if (b) first = c0 + 64 * u + __ffsll(static_cast<long long>(b)) - 1;
+                    }
+                    if (first >= 0) { m = first; break; }
+                }
+                if (lane == 0) s_rec[rel].w = m;
+            }
+        }
+        lds_barrier();
+        // ---- D. which candidates lie on the prompt's path: follow "edge fully matched, and the candidate at its
+        // end is a child of this node" links from position 0, by pointer doubling ----
+        {
+            rec = s_rec[tid];
+            int32_t link = -1;
+            if (rec.x >= 0 && rec.w == rec.z && tid + rec.z < kWin) {
+                const int4 nx = s_rec[tid + rec.z];
+                if (nx.x >= 0 && nx.y == rec.x) link = tid + rec.z;
+            }
+            s_jump[tid] = link;
+            s_mark[tid] = tid == 0 ? 1 : 0;
+            lds_barrier();
+#pragma unroll 1
+            for (int round = 0; round < 10; ++round) {
+                const int32_t j = s_jump[tid];
+                if (j >= 0 && s_mark[tid]) s_mark[j] = 1;
+                const int32_t jj = j >= 0 ? s_jump[j] : -1;
+                lds_barrier();
+                s_jump[tid] = jj;
+                lds_barrier();
+            }
+        }
+        // ---- E. slots of the matched positions: position i belongs to the last path node starting at or before it ----
+        int32_t cov = s_mark[tid] ? tid : -1;
+#pragma unroll
+        for (int k = 0; k < 6; ++k) {
+            const int32_t left = __shfl_up(cov, 1u << k);
+            if (lane >= (1 << k)) cov = max(cov, left);
+        }
+        if (lane == 63) s_wmax[wave] = cov;
+        lds_barrier();
+        int32_t z = -1;  // last path node of the window
+        for (int v = 0; v < kWaves; ++v) {
+            const int32_t x = s_wmax[v];
+            if (v < wave) cov = max(cov, x);
+            z = max(z, x);
+        }
+        if (cov >= 0) {
+            const int4 cr = s_rec[cov];
+            if (cr.w >= 0 && tid < cov + cr.w) out_slots[w0 + tid] = t.edge_slot[s_es[cov] + (tid - cov)];
+        }
+        // ---- F. where the walk stands after this window (the same in every thread).  The loop head decides
+        // what follows: the hash only nominated the nodes, the child table has the last word. ----
+        {
+            const int4 zr = s_rec[z];
+            if (zr.w < 0) {
+                pos = w0 + z;  // very long edge, not compared here: the loop head takes it
+                cur = zr.y;
+            } else {
+                const int32_t m = zr.w;
+                const int32_t es = s_es[z];
+                // the part of the last node's edge that reaches past the window
+                for (int32_t k = kWin - z + tid; k < m; k += kWin) out_slots[w0 + z + k] = t.edge_slot[es + k];
+                pos = w0 + z + m;
+                if (m == zr.z) cur = zr.x;
+                else if (m == 0) cur = zr.y;  // the nominated node is not the child (only a hash collision does that)
+                else done = true;             // mismatch inside the edge, or the prompt ended inside it
+            }
+            if (pos == w0) done = true;  // cannot happen: position 0 holds a true child, whose first token matches
+        }
+        lds_barrier();  // the window arrays are rebuilt next
     }
     if (tid == 0) prefix_len[r] = pos;
 }
@@ -110,8 +316,8 @@ extern "C" int pa_match_prefixes(const pa_tree* tree, const int32_t* tokens, con
     // tokens / slot_idx may be NULL only if every prompt is empty (offsets[B] == 0), which the host cannot see
     {
         pa::ProfScope prof(pa::kProfMatch, static_cast<hipStream_t>(stream));
-        hipLaunchKernelGGL(pa::match_prefixes_kernel, dim3(B), dim3(pa::kMatchThreads), 0,
-                           static_cast<hipStream_t>(stream), *view, tokens, offsets, prefix_len, slot_idx);
+        hipLaunchKernelGGL(pa::match_prefixes_pos_kernel, dim3(B), dim3(pa::kWin), 0, static_cast<hipStream_t>(stream),
+                           *view, tokens, offsets, prefix_len, slot_idx);
     }
     PA_HIP(hipGetLastError());
     return PA_OK;

@@ -151,7 +151,9 @@ extern "C" int pa_tree_upload(pa_tree* tree, void* stream_) {
     const size_t o_len = o_start + up(nn * 4);
     const size_t o_key = o_len + up(nn * 4);
     const size_t o_val = o_key + up(cap * 8);
-    const size_t total = o_val + up(cap * 4);
+    const size_t o_phe = o_val + up(cap * 4);
+    const size_t o_end = o_phe + up(cap * sizeof(pa::PathEntry));
+    const size_t total = o_end + up(nn * 8);
 
     std::vector<unsigned char> blob;
     try {
@@ -187,6 +189,40 @@ extern "C" int pa_tree_upload(pa_tree* tree, void* stream_) {
         }
     }
 
+    // positional index: depth-first walk carrying the hash of the path so far (explicit stack: paths can be deep)
+    pa::PathEntry* h_phe = reinterpret_cast<pa::PathEntry*>(blob.data() + o_phe);
+    unsigned long long* h_end = reinterpret_cast<unsigned long long*>(blob.data() + o_end);
+    for (uint64_t i = 0; i < cap; ++i) h_phe[i].node = -1;
+    try {
+        struct Item { int32_t node; int32_t parent; int32_t depth; unsigned long long hash; };  // depth, hash: of the path BEFORE the node's edge
+        std::vector<Item> stack;
+        stack.push_back({0, -1, 0, 0ull});
+        h_end[0] = 0ull;
+        while (!stack.empty()) {
+            const Item it = stack.back();
+            stack.pop_back();
+            const auto& nd = nodes[it.node];
+            unsigned long long h = it.hash;
+            if (it.node != 0) {
+                const unsigned long long key = pa::path_hash_push(h, nd.tok[0]);
+                uint64_t at = pa::path_slot(key, it.depth) & (cap - 1);
+                while (h_phe[at].node != -1) at = (at + 1) & (cap - 1);
+                h_phe[at].hash = key;
+                h_phe[at].depth = it.depth;
+                h_phe[at].node = it.node;
+                h_phe[at].edge_start = h_start[it.node];
+                h_phe[at].edge_len = h_len[it.node];
+                h_phe[at].parent = it.parent;
+                for (int32_t t : nd.tok) h = pa::path_hash_push(h, t);
+                h_end[it.node] = h;
+            }
+            const int32_t end_depth = it.depth + static_cast<int32_t>(nd.tok.size());
+            for (const auto& kv : nd.child) stack.push_back({kv.second, it.node, end_depth, h});
+        }
+    } catch (const std::bad_alloc&) {
+        return pa::fail(PA_ENOMEM, "pa_tree_upload: out of host memory");
+    }
+
     release_device(tree);
     PA_HIP(hipGetDevice(&tree->device));
     void* d = nullptr;
@@ -205,6 +241,9 @@ extern "C" int pa_tree_upload(pa_tree* tree, void* stream_) {
     tree->view.ht_key = reinterpret_cast<const unsigned long long*>(b + o_key);
     tree->view.ht_val = reinterpret_cast<const int32_t*>(b + o_val);
     tree->view.ht_mask = static_cast<uint32_t>(cap - 1);
+    tree->view.ph_entry = reinterpret_cast<const pa::PathEntry*>(b + o_phe);
+    tree->view.node_endhash = reinterpret_cast<const unsigned long long*>(b + o_end);
+    tree->view.ph_mask = static_cast<uint32_t>(cap - 1);
     tree->view.n_nodes = static_cast<int32_t>(nn);
     tree->uploaded = true;
     return PA_OK;
