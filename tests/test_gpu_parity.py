@@ -90,6 +90,59 @@ def test_match_random_small_vocab(pa, gpu_device, vocab, seed):
         np.testing.assert_array_equal(si[off[r]:off[r] + pl_ref[r]], si_ref[off[r]:off[r] + pl_ref[r]])
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_match_long_paths_of_mixed_edge_lengths(pa, gpu_device, seed):
+    """A trunk with branch points at spacings from 1 to thousands of tokens: the prompt's path runs through
+    hundreds of nodes whose edges are short, medium and very long in turn, stops at node boundaries, inside
+    edges of every class, at the trunk's end and inside side branches; bit-exact vs the oracle trie."""
+    import oracle
+    rng = np.random.default_rng(100 + seed)
+    vocab = 50000
+    spacing = []
+    while sum(spacing) < 9000:
+        kind = rng.integers(0, 4)
+        lo, hi = [(1, 9), (20, 200), (260, 1000), (1100, 3000)][kind]
+        run = int(rng.integers(20, 150)) if kind == 0 else 1
+        spacing += [int(rng.integers(lo, hi)) for _ in range(run)]
+    trunk = rng.integers(0, vocab, sum(spacing) + 50).astype(np.int32)
+    cuts = np.cumsum(spacing)
+    cached, nslot = [], 0
+
+    def add(seq):
+        nonlocal nslot
+        cached.append((seq.astype(np.int32), np.arange(nslot, nslot + len(seq), dtype=np.int32)))
+        nslot += len(seq)
+
+    add(trunk)
+    for c in cuts:
+        branch = rng.integers(0, vocab, int(rng.integers(1, 600))).astype(np.int32)
+        branch[0] = (trunk[c] + 1) % vocab  # leaves the trunk exactly at c
+        add(np.concatenate([trunk[:c], branch]))
+    prompts = [trunk.copy(), trunk[:1], trunk[: cuts[0]], np.concatenate([trunk, rng.integers(0, vocab, 7).astype(np.int32)])]
+    for _ in range(60):
+        which = int(rng.integers(0, len(cached)))
+        base = cached[which][0]
+        mode = rng.integers(0, 3)
+        cut = int(cuts[rng.integers(0, len(cuts))]) if mode == 0 else int(rng.integers(0, len(base) + 1))
+        cut = min(cut, len(base))
+        tail = rng.integers(0, vocab, int(rng.integers(0, 30))).astype(np.int32)
+        prompts.append(np.concatenate([base[:cut], tail]))
+    toks = np.concatenate(prompts).astype(np.int32)
+    off = np.zeros(len(prompts) + 1, np.int32)
+    off[1:] = np.cumsum([len(p) for p in prompts])
+    pl_ref, si_ref = oracle.match_prefixes(cached, toks, off)
+    assert pl_ref.max() >= len(trunk) and len(cuts) > 100
+    tree = pa.Tree()
+    for c in cached:
+        tree.insert(*c)
+    tree.upload()
+    pl, si = pa.match_prefixes(tree, torch.from_numpy(toks).to(gpu_device), torch.from_numpy(off).to(gpu_device))
+    pl, si = pl.cpu().numpy(), si.cpu().numpy()
+    np.testing.assert_array_equal(pl, pl_ref)
+    for r in range(len(prompts)):
+        np.testing.assert_array_equal(si[off[r]:off[r] + pl_ref[r]], si_ref[off[r]:off[r] + pl_ref[r]])
+
+
 def test_match_empty_tree_and_empty_batch(pa, gpu_device):
     tree = pa.Tree()
     tree.upload()
