@@ -31,6 +31,8 @@ def _hipcc() -> str:
 def build(verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
     hipcc = _hipcc()
+    # the assembly of the steady-state tile runs is written by a generator that sits beside the sources
+    subprocess.check_call([sys.executable, os.path.join(CSRC, "gen_fast_run.py")], stdout=subprocess.DEVNULL)
 
     def compile_one(src):
         obj = os.path.join(OBJ, src.rsplit(".", 1)[0] + ".o")

@@ -39,11 +39,22 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
+typedef __bf16 bf16x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x32 __attribute__((ext_vector_type(32)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// fast_run_pool_d128 / fast_run_ext_d128: runs of steady-state tiles as assembly with fixed registers
+#include "fast_run_d128.inc"
+
 constexpr int kKT = 64;                  // key tokens per tile
 constexpr int kStages = 2;               // LDS ring: one tile being read, one being filled
 constexpr int kTargetWorkgroups = 1024;  // split the key axis until about this many workgroups exist
 constexpr int kMinChunk = 512;           // never split below this many keys per chunk
 constexpr float kRescaleThreshold = 8.f; // log2 units: the running maximum may lag the true one by this much
+// The steady-state tiles (fast_run_*.inc) never move the running maximum: a run is left, for the general tile, when
+// the probabilities of one lane and key block sum to more than 2^40.  The exponent range of fp32 and bf16 leaves that
+// much room: a probability of 2^40 is as precise as one of 1, and what then underflows next to it is < 2^-100 of it.
 
 struct ExtendPlan {
     int nw;          // waves per workgroup
@@ -313,42 +324,24 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     const unsigned ld_voff0 = (ld_pos ^ swz_v<D>(wave * UPW * RPB + ld_rowl)) * 16;
     auto ld_koff = [&](int u) __attribute__((always_inline)) { return ld_koff0 ^ (64u * u); };
     auto ld_voff = [&](int u) __attribute__((always_inline)) { return ld_voff0 ^ ((D == 128 ? 16u : 32u) * u); };
-    // kPrefixOnly: every row of the tile is a prefix position below kv_hi (no clamping, no source select).
-    // kPow2: page_size is a power of two (page_shift valid).
-    auto issue_tile = [&](int p0, int ring, auto prefix_only, auto pow2) __attribute__((always_inline)) {
-        constexpr bool kPrefixOnly = decltype(prefix_only)::value;
-        constexpr bool kPow2 = decltype(pow2)::value;
-        const unsigned sk = smem_addr + ring * STAGEB;
+    // The next tile's loads, general: every lane takes its row from the pool (through the slot prefetched for it) or
+    // from the extend tensors, by position; rows past the end of the key range repeat the last valid row (finite
+    // values that the mask zeroes).  Page sizes are powers of two (checked on the host).
+    auto issue = [&](int p0, int ring) __attribute__((always_inline)) {
+        const unsigned sk = __builtin_amdgcn_readfirstlane(smem_addr + ring * STAGEB);  // wave-uniform (goes to M0)
 #pragma unroll
         for (int u = 0; u < UPW; ++u) {
             const int blk = wave * UPW + u;
+            const int p = min(p0 + blk * RPB + ld_rowl, kv_hi - 1);
+            const bool ext = p >= P;
             const unsigned sl = static_cast<unsigned>(min(max(sl_next[u], 0), num_slots - 1));  // never outside the pool
-            const unsigned page = kPow2 ? sl >> page_shift : sl / static_cast<unsigned>(page_size);
-            const unsigned o = kPow2 ? sl & static_cast<unsigned>(page_size - 1) : sl - page * static_cast<unsigned>(page_size);
-            const unsigned char* base = pool_g + static_cast<size_t>(page) * page_stride;  // one 32x32->64 multiply-add
-            const unsigned char* ka = base + (o * static_cast<unsigned>(ROWB) + ld_koff(u));
-            const unsigned char* va = base + (o * static_cast<unsigned>(ROWB) + ld_voff(u) + v_off32);
-            if constexpr (!kPrefixOnly) {
-                // rows past the end of the key range repeat the last valid row: finite values that the mask zeroes
-                const int p = min(p0 + blk * RPB + ld_rowl, kv_hi - 1);
-                if (p >= P) {
-                    const size_t xo = static_cast<size_t>(p - P) * x_stride;
-                    ka = kx_g + xo + ld_koff(u);
-                    va = vx_g + xo + ld_voff(u);
-                }
-            }
+            const size_t pool_off = static_cast<size_t>(sl >> page_shift) * page_stride +
+                                    (sl & static_cast<unsigned>(page_size - 1)) * static_cast<unsigned>(ROWB);
+            const size_t off = ext ? static_cast<size_t>(p - P) * x_stride : pool_off;
+            const unsigned char* ka = (ext ? kx_g : pool_g) + off + ld_koff(u);
+            const unsigned char* va = (ext ? vx_g : pool_g + v_off32) + off + ld_voff(u);
             load_to_lds_16(ka, sk + blk * 1024);
             load_to_lds_16(va, sk + TILEB + blk * 1024);
-        }
-    };
-    auto issue = [&](int p0, int ring) __attribute__((always_inline)) {
-        const bool prefix_only = p0 + kKT <= min(P, kv_hi);
-        if (page_shift >= 0) {
-            if (prefix_only) issue_tile(p0, ring, std::true_type{}, std::true_type{});
-            else issue_tile(p0, ring, std::false_type{}, std::true_type{});
-        } else {
-            if (prefix_only) issue_tile(p0, ring, std::true_type{}, std::false_type{});
-            else issue_tile(p0, ring, std::false_type{}, std::false_type{});
         }
     };
 
@@ -364,7 +357,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
             for (int i = 0; i < 16; ++i) oacc[rb][b][i] = 0.f;
     }
 
-    // ---- LDS read addresses (byte offsets in one ring slot), fixed per lane.
+    // ---- LDS read addresses of this lane in the ring slot that holds the current tile (toggled after every tile).
     // K: row n (+32 for the second key block), 16-byte chunk 2 s + hh of the row.
     // V, transposing read: group lane i = 4 e + c reads key row 8 h2 + 4 hh + e (+ 16 cs + 32 mb) and 8 bytes at
     // head-dim offset 32 b + 16 par + 4 c.  The swizzles do not depend on mb / cs, which become immediates.
@@ -390,49 +383,54 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     }
     const bf16x2_t ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
 
-    // ---- pieces of one tile's arithmetic; MB = which block of 32 keys of the tile, RING = ring slot ----
-    // S^T = K Q^T for one block of 32 keys and all row blocks: each K fragment read from LDS feeds RB MFMAs
-    auto qk_block = [&](auto ring_c, auto mb_c, f32x16 (&sacc)[RB]) __attribute__((always_inline)) {
-        constexpr int OFF = decltype(ring_c)::value * STAGEB + decltype(mb_c)::value * 32 * ROWB;
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sacc[rb][i] = 0.f;
+    // ---- One block of 32 keys of the current tile, general: masks, any running maximum.  Kept small in registers
+    // (one score block alive, no overlap of its phases inside the wave; the other wave of the SIMD fills the gaps):
+    // it runs for the first tile, the tile where prefix and extend tokens meet, the tiles on the causal diagonal, and
+    // wherever the hand-scheduled tile does not apply.  mb = 0 / 1: first / second block of the tile.
+    auto general_block = [&](int p0, int mb, bool need_mask) __attribute__((always_inline)) {
+        const unsigned off = static_cast<unsigned>(mb) * (32 * ROWB);
+        const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        f32x16 sacc[RB];
+        // S^T = K Q^T: each K fragment read from LDS feeds RB MFMAs
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            const bf16x8 kf = *(const __attribute__((address_space(3))) bf16x8*)(lds + k_rd[s] + OFF);
+            const bf16x8 kf = *(const __attribute__((address_space(3))) bf16x8*)(lds + (k_rd[s] + off));
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
-                sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qreg[rb][s], sacc[rb], 0, 0, 0);
+                sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qreg[rb][s], s == 0 ? zero16 : sacc[rb], 0, 0, 0);
         }
-    };
-    // mask the keys a row must not see (only called where the block crosses a visibility limit)
-    auto mask_block = [&](int pb0, f32x16 (&sacc)[RB]) __attribute__((always_inline)) {
+        const int pb0 = p0 + 32 * mb;
+        uint32_t pb[RB][8];
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-            if (pb0 + 32 > blk_vis_min[rb]) {
+        for (int rb = 0; rb < RB; ++rb) {
+            // the keys a row must not see (only where the block crosses a visibility limit)
+            if (need_mask && pb0 + 32 > blk_vis_min[rb]) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int p = pb0 + 8 * (i / 4) + 4 * hh + (i % 4);
                     if (p >= vis_end[rb]) sacc[rb][i] = -INFINITY;
                 }
             }
-    };
-    // row maximum of one key block, scaled to the log2 domain, in every lane of the row
-    auto block_max = [&](const f32x16 (&sacc)[RB], float (&m_blk)[RB]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
+            // row maximum of the block, in every lane of the row
             float mx = fmaxf(sacc[rb][0], sacc[rb][1]);
 #pragma unroll
             for (int i = 2; i < 16; ++i) mx = fmaxf(mx, sacc[rb][i]);
-            m_blk[rb] = row_max(mx) * scale_log2e;
-        }
-    };
-    // probabilities of one key block against the current running maximum, packed to bf16 pairs (the B operand
-    // of the second product); lsum receives the sum of the ROUNDED probabilities, the values the numerator uses
-    auto block_exp = [&](const f32x16 (&sacc)[RB], uint32_t (&pb)[RB][8], float (&lsum)[RB]) __attribute__((always_inline)) {
+            const float m_blk = row_max(mx) * scale_log2e;  // log2 domain (scale > 0)
+            // The running maximum may lag the true one by kRescaleThreshold (probabilities then reach 2^threshold,
+            // harmless in bf16/fp32).  If some row of the wave outgrew it by more, raise it and rescale what was
+            // accumulated so far.  With a stable maximum this happens for the first block only.
+            if (__any(m_blk > m_run[rb] + kRescaleThreshold)) {
+                const float m_new = fmaxf(m_run[rb], m_blk);
+                const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - ((m_new == -INFINITY) ? 0.f : m_new));
+                l_run[rb] *= alpha;
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
+                for (int b = 0; b < NB; ++b)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) oacc[rb][b][i] *= alpha;
+                m_run[rb] = m_new;
+            }
+            // probabilities, packed to bf16 pairs (the B operand of the second product); the row sum takes the
+            // ROUNDED probabilities, the values the numerator uses
             const float neg_m = (m_run[rb] == -INFINITY) ? 0.f : -m_run[rb];
             float acc = 0.f;
 #pragma unroll
@@ -443,54 +441,9 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
                 pb[rb][i / 2] = pk;
                 acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk), ones, acc, false);
             }
-            lsum[rb] = acc;
+            l_run[rb] += acc;
         }
-    };
-    // The probabilities above are formed BEFORE it is known whether the running maximum is still good
-    // enough, so that their arithmetic can overlap the matrix products.  The maximum may lag the true one
-    // by kRescaleThreshold (probabilities then reach 2^threshold, harmless in bf16/fp32).  If some row of
-    // the wave outgrew it by more, this raises the maximum, rescales what was accumulated so far and forms
-    // the block's probabilities again.  Rare: with a stable maximum it happens for the first block only.
-    auto block_commit = [&](const f32x16 (&sacc)[RB], const float (&m_blk)[RB], uint32_t (&pb)[RB][8],
-                            float (&lsum)[RB]) __attribute__((always_inline)) {
-        bool grow = false;
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            grow |= m_blk[rb] > m_run[rb] + kRescaleThreshold;
-            // pin the speculative probabilities in front of the branch (the compiler would otherwise sink
-            // their computation below it, out of the shadow of the MFMAs)
-            asm volatile("" : "+v"(pb[rb][0]), "+v"(pb[rb][1]), "+v"(pb[rb][2]), "+v"(pb[rb][3]), "+v"(pb[rb][4]),
-                         "+v"(pb[rb][5]), "+v"(pb[rb][6]), "+v"(pb[rb][7]), "+v"(lsum[rb]));
-        }
-        if (__any(grow)) {
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                const float m_new = fmaxf(m_run[rb], m_blk[rb]);
-                const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - ((m_new == -INFINITY) ? 0.f : m_new));
-                l_run[rb] *= alpha;
-                // The accumulators are scaled IN PLACE (tied asm operands): written as ordinary multiplies, the
-                // scaled values get new registers and the join after this rare branch copies all of them on the
-                // common path.  The s_nops cover the wait states between an MFMA write of the accumulators and a
-                // vector-ALU read, which the compiler does not insert for operands of inline assembly.
-                asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
-#pragma unroll
-                for (int b = 0; b < NB; ++b)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        float x = oacc[rb][b][i];
-                        asm volatile("v_mul_f32 %0, %0, %1" : "+v"(x) : "v"(alpha));
-                        oacc[rb][b][i] = x;
-                    }
-                m_run[rb] = m_new;
-            }
-            block_exp(sacc, pb, lsum);
-        }
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) l_run[rb] += lsum[rb];
-    };
-    // O^T += V^T P^T for one block of 32 keys, 16 keys per MFMA: each V^T fragment feeds RB MFMAs
-    auto pv_block = [&](auto ring_c, auto mb_c, const uint32_t (&pb)[RB][8]) __attribute__((always_inline)) {
-        constexpr int OFF = decltype(ring_c)::value * STAGEB + decltype(mb_c)::value * 32 * ROWB;
+        // O^T += V^T P^T, 16 keys per MFMA: each V^T fragment feeds RB MFMAs
 #pragma unroll
         for (int cs = 0; cs < 2; ++cs) {
             bf16x8 pop[RB];
@@ -502,7 +455,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
                 s16x4 frag[2];
 #pragma unroll
                 for (int h2 = 0; h2 < 2; ++h2)
-                    frag[h2] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(lds + v_rd[b][h2] + (OFF + cs * 16 * ROWB)));
+                    frag[h2] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(lds + (v_rd[b][h2] + off + cs * 16 * ROWB)));
                 const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(frag[0], frag[1], 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb)
@@ -511,222 +464,31 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
         }
     };
 
-    // ------------------------------------------------------------------------------------------------
-    // The steady-state tile, scheduled by hand (RB == 1).  A wave issues in order, so arithmetic only runs
-    // in the shadow of an MFMA (32 cycles) if it follows that MFMA in the instruction stream.  The tile is
-    // written as 32 slots, each one MFMA followed by a piece of per-lane work that does not depend on it, and
-    // the compiler's scheduler is fenced off between slots.  LDS reads run kPD slots ahead of their MFMA.
-    //   slots  0.. 7  S0 = K(block 0) Q^T     | addresses + issue of the next tile's global -> LDS loads
-    //   slots  8..15  S1 = K(block 1) Q^T     | exponentials of block 0 (against the current maximum), its maximum
-    //   (commit block 0: raise the maximum and redo the block if it was outgrown - rare)
-    //   slots 16..23  O += V(block 0) P0      | exponentials of block 1, its maximum
-    //   (commit block 1)
-    //   slots 24..31  O += V(block 1) P1      | -
-    // Only for tiles that need no mask, with a power-of-two page size.
-    // ------------------------------------------------------------------------------------------------
-    // EXT = the next tile lies wholly in the extend tokens (rows of k_ext / v_ext), else wholly in the prefix
-    // (rows of the pool; the host has checked that the pool spans less than 4 GB so that 32-bit offsets do).
-    const unsigned x_stride32 = static_cast<unsigned>(x_stride);
-    auto mul24 = [](unsigned a, unsigned b) __attribute__((always_inline)) { return __umul24(a, b); };
-    auto tile_fast = [&](int p0, auto ring_c, auto ext_c) __attribute__((always_inline)) {
-        static_assert(KS == 2 * UPW || RB != 1, "slot plan assumes one tile-load piece per QK slot of block 0");
-        constexpr int RING = decltype(ring_c)::value;
-        constexpr bool EXT = decltype(ext_c)::value;
-        constexpr int kPD = 2;    // K fragments in flight ahead of their MFMA
-        constexpr int kPDV = 2;   // V fragments in flight ahead of their MFMA
-        constexpr int NPV = 2 * NB;  // MFMAs per PV block (2 groups of 16 keys x NB head-dim blocks)
-        const int pn = p0 + kKT;  // first key of the next tile
-        auto fence = [&]() __attribute__((always_inline)) { __builtin_amdgcn_sched_barrier(0); };
-        auto rd_k = [&](int blk, int sl) __attribute__((always_inline)) -> bf16x8 {
-            return *(const __attribute__((address_space(3))) bf16x8*)(lds + k_rd[sl] + (RING * STAGEB + blk * 32 * ROWB));
-        };
-        auto rd_v = [&](int blk, int j) __attribute__((always_inline)) -> bf16x8 {  // j = cs * NB + b
-            const int off = RING * STAGEB + (blk * 32 + (j / NB) * 16) * ROWB;
-            const s16x4 f0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(lds + v_rd[j % NB][0] + off));
-            const s16x4 f1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(lds + v_rd[j % NB][1] + off));
-            return __builtin_bit_cast(bf16x8, __builtin_shufflevector(f0, f1, 0, 1, 2, 3, 4, 5, 6, 7));
-        };
-        // one piece of the next tile's load: block u of this wave, K (which = 0) then V (which = 1);
-        // rows past the end of the key range repeat the last valid one
-        unsigned row_off = 0;  // byte offset of the row from the pool base (from k_ext of the request); low 8 bits clear
-        auto load_piece = [&](int u, int which) __attribute__((always_inline)) {
-            const int blk = wave * UPW + u;
-            const unsigned lds_k = smem_addr + (RING ^ 1) * STAGEB + blk * 1024;
-            if (which == 0) {
-                if constexpr (EXT) {
-                    const int pp = min(pn + blk * RPB + ld_rowl, kv_hi - 1);
-                    row_off = mul24(static_cast<unsigned>(pp - P), x_stride32);
-                    load_to_lds_16(kx_g, row_off | ld_koff(u), lds_k);
-                } else {
-                    const unsigned sl = static_cast<unsigned>(min(max(sl_next[u], 0), num_slots - 1));
-                    const unsigned page = sl >> page_shift;
-                    const unsigned o = sl & static_cast<unsigned>(page_size - 1);
-                    row_off = mul24(page, page_stride) + (o << (D == 128 ? 8 : 7));
-                    load_to_lds_16(pool_g, row_off | ld_koff(u), lds_k);
-                }
-            } else {
-                if constexpr (EXT) load_to_lds_16(vx_g, row_off | ld_voff(u), lds_k + TILEB);
-                else load_to_lds_16(pool_g, (row_off | ld_voff(u)) + v_off32, lds_k + TILEB);
-            }
-        };
-        // exponentials of elements 2 e, 2 e + 1 of a block's scores, and their share of the block maximum
-        auto exp_piece = [&](const f32x16& sc, int e, float neg_m, uint32_t (&pb)[RB][8], float& lsum, float& mx)
-                             __attribute__((always_inline)) {
-            const float x0 = sc[2 * e], x1 = sc[2 * e + 1];
-            const float a = __builtin_amdgcn_exp2f(fmaf(x0, scale_log2e, neg_m));
-            const float b = __builtin_amdgcn_exp2f(fmaf(x1, scale_log2e, neg_m));
-            const uint32_t pk = pack_bf16x2(a, b);
-            pb[0][e] = pk;
-            lsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk), ones, lsum, false);
-            mx = fmaxf(fmaxf(mx, x0), x1);
-        };
-
-        // mx = this lane's maximum over its 16 keys of the block: some lane of a row sees the row maximum, so
-        // "no lane outgrew the running maximum" needs no exchange between the halves of a row
-        auto commit_light = [&](const f32x16 (&sc)[RB], float mx, uint32_t (&pb)[RB][8], float (&lsum)[RB])
-                                __attribute__((always_inline)) {
-            asm volatile("" : "+v"(pb[0][0]), "+v"(pb[0][1]), "+v"(pb[0][2]), "+v"(pb[0][3]), "+v"(pb[0][4]), "+v"(pb[0][5]),
-                         "+v"(pb[0][6]), "+v"(pb[0][7]), "+v"(lsum[0]));
-            if (__any(mx * scale_log2e > m_run[0] + kRescaleThreshold)) {
-                float m_blk[RB];
-                m_blk[0] = row_max(mx) * scale_log2e;
-                block_commit(sc, m_blk, pb, lsum);
-            } else {
-                l_run[0] += lsum[0];
-            }
-        };
-        f32x16 sc0[RB], sc1[RB];
-        uint32_t pb0[RB][8], pb1[RB][8];
-        float ls[RB];
-        bf16x8 ka[KS], kb[KS], va[NPV], vb[NPV];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sc0[0][i] = sc1[0][i] = 0.f;
-
-        // ---- slots 0..KS-1: S0, next tile's loads ----
-#pragma unroll
-        for (int sl = 0; sl < kPD; ++sl) ka[sl] = rd_k(0, sl);
-        fence();
-#pragma unroll
-        for (int sl = 0; sl < KS; ++sl) {
-            sc0[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[sl], qreg[0][sl], sc0[0], 0, 0, 0);
-            if (sl + kPD < KS) ka[sl + kPD] = rd_k(0, sl + kPD);
-            else kb[sl + kPD - KS] = rd_k(1, sl + kPD - KS);
-            load_piece(sl / 2, sl % 2);  // also after the last tile (rows clamp to the last valid one): no branch
-            fence();
-        }
-        // ---- slots KS..2KS-1: S1, exponentials of block 0 ----
-        {
-            const float neg_m = (m_run[0] == -INFINITY) ? 0.f : -m_run[0];
-            float mx = -INFINITY, lsum = 0.f;
-#pragma unroll
-            for (int sl = 0; sl < KS; ++sl) {
-                sc1[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[sl], qreg[0][sl], sc1[0], 0, 0, 0);
-                if (sl + kPD < KS) kb[sl + kPD] = rd_k(1, sl + kPD);
-                else va[sl + kPD - KS] = rd_v(0, sl + kPD - KS);
-#pragma unroll
-                for (int e = sl * 8 / KS; e < (sl + 1) * 8 / KS; ++e) exp_piece(sc0[0], e, neg_m, pb0, lsum, mx);
-                if (!EXT && sl < UPW) {
-                    // slot of this lane's row in the tile after the next one; rows outside the prefix read the
-                    // last prefix slot and never use it (P >= 1 here: the next tile is a prefix tile)
-                    const int pp = min(pn + kKT + (wave * UPW + sl) * RPB + ld_rowl, P - 1);
-                    sl_next[sl] = slots[pp];
-                }
-                fence();
-            }
-            ls[0] = lsum;
-            commit_light(sc0, mx, pb0, ls);
-        }
-        fence();
-        // ---- PV of block 0, exponentials of block 1 ----
-        {
-            const float neg_m = (m_run[0] == -INFINITY) ? 0.f : -m_run[0];
-            float mx = -INFINITY, lsum = 0.f;
-            bf16x8 pop[2];
-#pragma unroll
-            for (int cs = 0; cs < 2; ++cs)
-                pop[cs] = __builtin_bit_cast(bf16x8, make_uint4(pb0[0][cs * 4 + 0], pb0[0][cs * 4 + 1], pb0[0][cs * 4 + 2], pb0[0][cs * 4 + 3]));
-#pragma unroll
-            for (int j = 0; j < NPV; ++j) {
-                oacc[0][j % NB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[j], pop[j / NB], oacc[0][j % NB], 0, 0, 0);
-                if (j + kPDV < NPV) va[j + kPDV] = rd_v(0, j + kPDV);
-                else vb[j + kPDV - NPV] = rd_v(1, j + kPDV - NPV);
-#pragma unroll
-                for (int e = j * 8 / NPV; e < (j + 1) * 8 / NPV; ++e) exp_piece(sc1[0], e, neg_m, pb1, lsum, mx);
-                fence();
-            }
-            ls[0] = lsum;
-            commit_light(sc1, mx, pb1, ls);
-        }
-        fence();
-        // ---- PV of block 1 ----
-        {
-            bf16x8 pop[2];
-#pragma unroll
-            for (int cs = 0; cs < 2; ++cs)
-                pop[cs] = __builtin_bit_cast(bf16x8, make_uint4(pb1[0][cs * 4 + 0], pb1[0][cs * 4 + 1], pb1[0][cs * 4 + 2], pb1[0][cs * 4 + 3]));
-#pragma unroll
-            for (int j = 0; j < NPV; ++j) {
-                oacc[0][j % NB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[j], pop[j / NB], oacc[0][j % NB], 0, 0, 0);
-                if (j + kPDV < NPV) vb[j + kPDV] = rd_v(1, j + kPDV);
-                fence();
-            }
-        }
-    };
-
-    // One tile.  Order of the matrix work: QK(block 0), QK(block 1), PV(block 0), PV(block 1); the exponentials
-    // of block 0 are independent of QK(block 1) and those of block 1 of PV(block 0), so the scheduler can
-    // run them in the shadow of those MFMAs.  The next tile's loads are issued after the first MFMAs so that
-    // their address arithmetic overlaps too.
-    auto tile_step = [&](int p0, auto ring_c) __attribute__((always_inline)) {
-        constexpr int RING = decltype(ring_c)::value;
-        const bool compute = wave_on && p0 <= P + wave_i_last;
-        if constexpr (RB == 1) {
-            bool no_mask = true;
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) no_mask &= p0 + kKT <= blk_vis_min[rb];
-            if (compute && no_mask && fast_ok) {
-                // kind of the next tile (its rows clamp to the last valid key): wholly prefix, wholly extend, or mixed
-                const int first = min(p0 + kKT, kv_hi - 1), last = min(p0 + 2 * kKT - 1, kv_hi - 1);
-                if (last < P) {
-                    tile_fast(p0, ring_c, std::false_type{});
-                    wait_vm_all();
-                    wg_barrier();
-                    return;
-                }
-                if (first >= P) {
-                    tile_fast(p0, ring_c, std::true_type{});
-                    wait_vm_all();
-                    wg_barrier();
-                    return;
-                }
-            }
-        }
-        f32x16 s0[RB], s1[RB];
-        uint32_t pb0[RB][8], pb1[RB][8];
-        float mb0[RB], mb1[RB], ls0[RB], ls1[RB];
-        if (compute) qk_block(ring_c, std::integral_constant<int, 0>{}, s0);
-        if (p0 + kKT < kv_hi) {
-            issue(p0 + kKT, RING ^ 1);  // the next tile flies during this tile's arithmetic
+    // One tile, general: any mix of prefix and extend rows, masks, ragged ends, any page size.  from = 1: the first
+    // key block is already accumulated; issue_next = false: the next tile's loads are already in flight.
+    auto tile_general = [&](int p0, int ring, int from, bool issue_next) __attribute__((always_inline)) {
+        if (issue_next && p0 + kKT < kv_hi) {
+            issue(p0 + kKT, ring ^ 1);  // the next tile flies during this tile's arithmetic
             load_slots(p0 + 2 * kKT);
         }
-        if (compute) {
+        if (wave_on && p0 <= P + wave_i_last) {
             bool need_mask = false;
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) need_mask |= p0 + kKT > blk_vis_min[rb];
-            if (need_mask) mask_block(p0, s0);
-            qk_block(ring_c, std::integral_constant<int, 1>{}, s1);
-            block_max(s0, mb0);
-            block_exp(s0, pb0, ls0);
-            block_commit(s0, mb0, pb0, ls0);
-            if (need_mask) mask_block(p0 + 32, s1);
-            pv_block(ring_c, std::integral_constant<int, 0>{}, pb0);
-            block_max(s1, mb1);
-            block_exp(s1, pb1, ls1);
-            block_commit(s1, mb1, pb1, ls1);
-            pv_block(ring_c, std::integral_constant<int, 1>{}, pb1);
+#pragma unroll 1
+            for (int mb = from; mb < 2; ++mb) general_block(p0, mb, need_mask);
         }
-        wait_vm_all();  // this wave's part of the next tile has landed ...
-        wg_barrier();   // ... and so has everyone else's; nobody still reads the tile just finished
+    };
+    // 0: the tile at p0 takes the general code; 1 / 2: the hand-scheduled one, the next tile lying wholly in the
+    // prefix / wholly in the extend tokens (its rows clamp to the last valid key).  Uniform over the wave.
+    auto tile_kind = [&](int p0) __attribute__((always_inline)) -> int {
+        if (!(fast_ok && D == 128 && RB == 1 && NW == 4 && (smem_addr & 255u) == 0)) return 0;
+        bool no_mask = true;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) no_mask &= p0 + kKT <= blk_vis_min[rb];
+        if (!(wave_on && p0 <= P + wave_i_last && no_mask)) return 0;
+        const int first = min(p0 + kKT, kv_hi - 1), last = min(p0 + 2 * kKT - 1, kv_hi - 1);
+        return last < P ? 1 : first >= P ? 2 : 0;
     };
 
     // ---- prologue: first tile into ring slot 0 ----
@@ -736,10 +498,87 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     wait_vm_all();
     wg_barrier();
 
-    for (int p0 = kv_lo; p0 < kv_hi; p0 += 2 * kKT) {
-        tile_step(p0, std::integral_constant<int, 0>{});
-        if (p0 + kKT >= kv_hi) break;
-        tile_step(p0 + kKT, std::integral_constant<int, 1>{});
+    int p0 = kv_lo, ring = 0;  // the tile at p0 sits in ring slot `ring`
+    // the LDS read addresses follow the ring: from slot `from_ring` to the other one
+    auto move_read_addresses = [&](int from_ring) __attribute__((always_inline)) {
+        const int d = from_ring ? -STAGEB : STAGEB;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) k_rd[s] += d;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            v_rd[b][0] += d;
+            v_rd[b][1] += d;
+        }
+    };
+    // this wave's part of the next tile has landed, and so has everyone else's; nobody still reads the tile just
+    // finished; then on to the next tile
+    auto next_tile = [&]() __attribute__((always_inline)) {
+        wait_vm_all();
+        wg_barrier();
+        move_read_addresses(ring);
+        ring ^= 1;
+        p0 += kKT;
+    };
+    bool fast_allowed = true;
+    while (p0 < kv_hi) {
+        p0 = __builtin_amdgcn_readfirstlane(p0);  // wave-uniform, said so to the compiler
+        ring = __builtin_amdgcn_readfirstlane(ring);
+        int from = 0;
+        bool issue_next = true;
+        const int kind = fast_allowed ? tile_kind(p0) : 0;
+        bool have_m = true;  // every row has a finite running maximum
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) have_m &= m_run[rb] != -INFINITY;
+        if (kind != 0 && __all(have_m)) {
+            if constexpr (D == 128 && RB == 1 && NW == 4) {
+                // A run of steady-state tiles against the running maximum as it stands: scores never move it in there
+                // (a row's probabilities may reach 2^40 instead), the output accumulators are touched by MFMAs only.
+                int p_end = p0;
+                do p_end += kKT;
+                while (tile_kind(p_end) == kind);
+                const int p_start = p0, ring_start = ring;
+                int st = 0;
+                const bf16x16 q01 = __builtin_shufflevector(qreg[0][0], qreg[0][1], 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+                const bf16x16 q23 = __builtin_shufflevector(qreg[0][2], qreg[0][3], 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+                const bf16x16 q45 = __builtin_shufflevector(qreg[0][4], qreg[0][5], 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+                const bf16x16 q67 = __builtin_shufflevector(qreg[0][6], qreg[0][7], 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+                const bf16x32 q_lo = __builtin_shufflevector(q01, q23, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18,
+                                                             19, 20, 21, 22, 23, 24, 25, 26, 27, 28, 29, 30, 31);
+                const bf16x32 q_hi = __builtin_shufflevector(q45, q67, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18,
+                                                             19, 20, 21, 22, 23, 24, 25, 26, 27, 28, 29, 30, 31);
+                // wave-uniform values, said so to the compiler (they go to scalar registers)
+                auto uni = [](int x) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane(x); };
+                auto uni_ptr = [&](const void* q) __attribute__((always_inline)) {
+                    const uint64_t a = reinterpret_cast<uint64_t>(q);
+                    const uint64_t lo = static_cast<uint32_t>(uni(static_cast<int>(a))), hi = static_cast<uint32_t>(uni(static_cast<int>(a >> 32)));
+                    return reinterpret_cast<const void*>(lo | (hi << 32));
+                };
+                const i32x8 c = {uni(page_shift), uni(page_size - 1), uni(static_cast<int>(page_stride)), uni(num_slots - 1),
+                                 uni(P - 1), uni(static_cast<int>(x_stride)), uni(kv_hi - 1 - P),
+                                 uni(static_cast<int>(smem_addr) + wave * (UPW * 1024))};
+                const i32x4 c2 = {uni(128), uni(192), uni(P), uni(__float_as_int(scale_log2e))};
+                p0 = uni(p0);
+                ring = uni(ring);
+                p_end = uni(p_end);
+                const int row_in_tile = wave * (UPW * RPB) + ld_rowl;
+                if (kind == 1)
+                    fast_run_pool_d128(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
+                                       k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
+                                       uni_ptr(pool_g), uni_ptr(pool_g + v_off32), c, c2);
+                else
+                    fast_run_ext_d128(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
+                                      k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
+                                      uni_ptr(kx_g), uni_ptr(vx_g), c, c2);
+                if (((p0 - p_start) / kKT) & 1) move_read_addresses(ring_start);
+                if (st == 0) continue;
+                // the tile outgrew the maximum: the general code does what is left of it, and stays (rare enough)
+                from = st - 1;
+                issue_next = false;
+                fast_allowed = false;
+            }
+        }
+        tile_general(p0, ring, from, issue_next);
+        next_tile();
     }
 
     // ---- epilogue: lane holds, for block b and register i, head-dim element 32 b + 8 (i / 4) + 4 hh + i % 4 ----
