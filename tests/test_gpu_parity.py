@@ -327,6 +327,46 @@ def test_extend_running_maximum_rescale(pa, gpu_device, direction):
     assert np.isfinite(out_to_f64(out)).all() and err <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("jump_at", [0.3, 0.6, 0.9])
+def test_extend_score_jump_leaves_the_steady_state_run(pa, gpu_device, jump_at):
+    """Keys whose scores jump by far more than 2^40 (in probability) part of the way through the prefix or the
+    extend tokens: the runs of steady-state tiles, which never move the running maximum, have to hand the tile
+    that outgrows it to the general code (in its first or its second key block) and the result must still meet the
+    same bar.  Requests are long enough for such runs to exist."""
+    import oracle
+    rng = np.random.default_rng(int(jump_at * 100))
+    Hq, Hkv, D, page, nslots, B = 8, 2, 128, 16, 16384, 4
+    c = _random_case(rng, B, Hq, Hkv, D, 3000, 400, "bf16", page, nslots)
+    pk = W.bf16_bits_to_f32(c["pk"]).copy()
+    k = W.bf16_bits_to_f32(c["k"]).copy()
+    cur = 0
+    for r in range(B):
+        P, E = int(c["P"][r]), int(c["E"][r])
+        f = np.ones(P + E, np.float32)
+        j = int((P + E) * jump_at) + r  # not tile-aligned, differs per request
+        f[j:] = 48.0                    # scores x 48: tens of log2 units above anything before
+        pk[cur:cur + P] *= f[:P, None, None]
+        k[c["eo"][r]:c["eo"][r] + E] *= f[P:, None, None]
+        cur += P
+    c["pk"], c["k"] = W.f32_to_bf16_bits(pk), W.f32_to_bf16_bits(k)
+    dev = gpu_device
+    pool = torch.zeros(pa.kv_pool_bytes(nslots, Hkv, D, torch.bfloat16, page), dtype=torch.uint8, device=dev)
+    kw = dict(page_size=page, num_slots=nslots)
+    pa.append_kv(pool, torch.from_numpy(c["backed"]).to(dev), to_torch(c["pk"], "bf16", dev), to_torch(c["pv"], "bf16", dev), **kw)
+    tt = lambda a: torch.from_numpy(a).to(dev)
+    scale = 1.0 / np.sqrt(D)
+    out = pa.extend_attention(to_torch(c["q"], "bf16", dev), to_torch(c["k"], "bf16", dev), to_torch(c["v"], "bf16", dev), pool,
+                              tt(c["si"]), tt(c["off"]), tt(c["P"]), tt(c["E"]), tt(c["eo"]), scale,
+                              max_kv_len=int((c["P"] + c["E"]).max()), **kw)
+    torch.cuda.synchronize()
+    opk, opv = oracle.new_pool(nslots, Hkv, D, "bf16")
+    oracle.append_kv(opk, opv, c["backed"], c["pk"], c["pv"], "bf16")
+    ref = oracle.extend_attention(c["q"], c["k"], c["v"], opk, opv, c["si"], c["off"], c["P"], c["E"], c["eo"], scale, "bf16")
+    err = np.abs(out_to_f64(out) - ref).max()
+    say(f"  jump at {jump_at}: max abs err {err:.3e}")
+    assert np.isfinite(out_to_f64(out)).all() and err <= TOL["bf16"]
+
+
 def test_extend_slot_permutation_invariance(pa, gpu_device):
     """Moving the cached rows to other slots (and renaming slot_idx accordingly) must not change a single bit."""
     wl = W.small_variant("tool_use", 3)
