@@ -29,8 +29,8 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3
 # HBM bytes per launch of the extend-attention kernel, measured with rocprofv3 --pmc: FETCH_SIZE x 1.984 +
 # WRITE_SIZE x 1.000 (KiB), the factors being what the same counters read for append_kv, a plain copy of
 # known size; the runs are summarised in profiles/extend_attention_<workload>.md.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"tool_use": 305_799_373, "agent_tree": 3_044_875_322, "long_doc_qa": 937_986_029,
-                          "video_qa": 398_054_344}
+MEASURED_TRAFFIC_BYTES = {"tool_use": 284_058_423, "agent_tree": 3_156_072_806, "long_doc_qa": 1_474_727_155,
+                          "video_qa": 403_564_874}
 
 
 def algorithmic_work(wl, prefix_len):
