@@ -24,6 +24,11 @@
 // exchange between lane l and l ^ 32, and the probabilities are already laid out as the
 // B operand of the second product O^T = V^T * P^T.  The V^T fragments are read from the
 // row-major V tile with the transposing LDS read of gfx950.
+//
+// Two kinds of tile.  The general tile (general_block below) takes any mix of pool and extend rows, masks and
+// ragged ends, and moves the running maximum; it runs for the first tile of a workgroup, where prefix and extend
+// tokens meet, and on the causal diagonal.  Runs of consecutive tiles that need no mask (D = 128) execute as one
+// assembly statement each (fast_run_d128.inc, written by gen_fast_run.py) with the running maximum frozen.
 #include <hip/hip_bf16.h>
 
 #include <type_traits>
