@@ -462,3 +462,75 @@ def test_full_config_append_then_reuse(pa, gpu_device, full_cache):
     err = np.abs(out_to_f64(out2) - ref[rows_q]).max()
     say(f"  reuse max abs err {err:.3e}")
     assert err <= TOL[wl.dtype]
+
+
+def test_chunked_prefill_through_the_cache_loop(pa, gpu_device):
+    """Chunked prefill (Sec. 3.3: long non-shared prompts are chunked): the extend part of every request is
+    prefilled 48 tokens at a time, and between chunks the new KV is appended to the pool and the tokens are inserted
+    into the tree, so that chunk k finds cached prefix + chunks < k as its prefix.  Every round goes through
+    match -> extend -> append -> insert/upload; matches are bit-exact, and the stitched output meets the same bar
+    against the oracle's one-shot result (prefix reuse is lossless, Sec. 5)."""
+    wl = W.small_variant("tool_use", 5)
+    g, o = GpuSide(wl, gpu_device), OracleSide(wl)
+    ref = o.extend(*o.match())  # [T, Hq, D] one shot
+    dev, C = gpu_device, 48
+    tt = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    out_all = torch.zeros_like(g.q)
+    Pd, E, off, eo = wl.designed_prefix_len.astype(int), wl.ext_len.astype(int), wl.offsets.astype(int), wl.ext_offsets.astype(int)
+    for k in range(int((E.max() + C - 1) // C)):
+        live = [r for r in range(wl.B) if k * C < E[r]]
+        done = [min(E[r], k * C) for r in live]          # extend tokens already cached
+        upto = [min(E[r], (k + 1) * C) for r in live]    # ... after this round
+        prompts = [wl.tokens[off[r]:off[r] + Pd[r] + u] for r, u in zip(live, upto)]
+        toks = np.concatenate(prompts).astype(np.int32)
+        offs = np.zeros(len(live) + 1, np.int32)
+        offs[1:] = np.cumsum([len(p) for p in prompts])
+        pl, si = pa.match_prefixes(g.tree, tt(toks), tt(offs))
+        want_pl = np.array([Pd[r] + d for r, d in zip(live, done)], np.int32)
+        np.testing.assert_array_equal(pl.cpu().numpy(), want_pl)
+        sin = si.cpu().numpy()
+        for j, (r, d) in enumerate(zip(live, done)):
+            want = np.concatenate([wl.designed_slots[off[r]:off[r] + Pd[r]], wl.new_slots[eo[r]:eo[r] + d]])
+            np.testing.assert_array_equal(sin[offs[j]:offs[j] + want_pl[j]], want)
+        rows = np.concatenate([np.arange(eo[r] + d, eo[r] + u) for r, d, u in zip(live, done, upto)])
+        idx = tt(rows).long()
+        el = np.array([u - d for d, u in zip(done, upto)], np.int32)
+        eo_k = np.zeros(len(live) + 1, np.int32)
+        eo_k[1:] = np.cumsum(el)
+        qk, kk, vk = g.q[idx].contiguous(), g.k[idx].contiguous(), g.v[idx].contiguous()
+        out = pa.extend_attention(qk, kk, vk, g.pool, si, tt(offs), pl, tt(el), tt(eo_k), wl.scale,
+                                  max_kv_len=int((offs[1:] - offs[:-1]).max()), **g.kw)
+        out_all[idx] = out
+        pa.append_kv(g.pool, tt(wl.new_slots[rows]), kk, vk, **g.kw)
+        for r, u in zip(live, upto):
+            g.tree.insert(wl.tokens[off[r]:off[r] + Pd[r] + u],
+                          np.concatenate([wl.designed_slots[off[r]:off[r] + Pd[r]], wl.new_slots[eo[r]:eo[r] + u]]).astype(np.int32))
+        g.tree.upload()
+    torch.cuda.synchronize()
+    err = np.abs(out_to_f64(out_all) - ref).max()
+    say(f"  chunked prefill max abs err {err:.3e}")
+    assert err <= TOL[wl.dtype]
+
+
+def test_decode_shape_one_new_token(pa, gpu_device):
+    """A fully cached prompt plus one new token per request (the decoding-phase unit of Sec. 3.2): E = 1 rows only."""
+    import oracle
+    rng = np.random.default_rng(77)
+    Hq, Hkv, D, page, nslots, B = 32, 8, 128, 16, 131072, 33
+    c = _random_case(rng, B, Hq, Hkv, D, 2500, 1, "bf16", page, nslots)
+    dev = gpu_device
+    pool = torch.zeros(pa.kv_pool_bytes(nslots, Hkv, D, torch.bfloat16, page), dtype=torch.uint8, device=dev)
+    kw = dict(page_size=page, num_slots=nslots)
+    pa.append_kv(pool, torch.from_numpy(c["backed"]).to(dev), to_torch(c["pk"], "bf16", dev), to_torch(c["pv"], "bf16", dev), **kw)
+    tt = lambda a: torch.from_numpy(a).to(dev)
+    scale = 1.0 / np.sqrt(D)
+    out = pa.extend_attention(to_torch(c["q"], "bf16", dev), to_torch(c["k"], "bf16", dev), to_torch(c["v"], "bf16", dev), pool,
+                              tt(c["si"]), tt(c["off"]), tt(c["P"]), tt(c["E"]), tt(c["eo"]), scale,
+                              max_kv_len=int((c["P"] + c["E"]).max()), **kw)
+    torch.cuda.synchronize()
+    opk, opv = oracle.new_pool(nslots, Hkv, D, "bf16")
+    oracle.append_kv(opk, opv, c["backed"], c["pk"], c["pv"], "bf16")
+    ref = oracle.extend_attention(c["q"], c["k"], c["v"], opk, opv, c["si"], c["off"], c["P"], c["E"], c["eo"], scale, "bf16")
+    err = np.abs(out_to_f64(out) - ref).max() if c["T"] else 0.0
+    say(f"  decode shape: T = {c['T']}, max abs err {err:.3e}")
+    assert c["T"] >= 8 and err <= TOL["bf16"]
