@@ -80,6 +80,45 @@ int pa_tree_stats(const pa_tree* tree, int64_t* n_nodes, int64_t* n_tokens);
 int pa_tree_destroy(pa_tree* tree);
 
 /* ---------------------------------------------------------------------------------
+ * Cache bookkeeping on the host, the steps either side of the hot path (not timed with it).
+ *
+ * Sec. 3.3: the local scheduler keeps a prefix tree and the number of active requests sharing each
+ * node; a new request is matched to the tree and the tree is updated; when memory is short a node,
+ * or part of a node if a part is enough, is evicted by the access time of the requests (LRU).  The
+ * paper says nothing of pages: as for the workloads, the new part of a prompt receives whole pages
+ * and token t of it sits in slot page[t / page_size] * page_size + t % page_size.  All pointers are
+ * host pointers.  Every call that changes the tree marks the device mirror stale (pa_tree_upload).
+ * --------------------------------------------------------------------------------- */
+
+/* Give the (still empty) tree a pool of num_slots slots in pages of page_size: from then on slots
+ * come from pa_tree_admit (pa_tree_insert returns PA_ESTATE).  Page 0 is handed out first, freed
+ * pages are reused last-freed-first. */
+int pa_tree_attach_pool(pa_tree* tree, int64_t num_slots, int page_size);
+
+/* Slots in pages that hold no cached token. */
+int pa_tree_free_slots(const pa_tree* tree, int64_t* free_slots);
+
+/* Admit a request: match tokens[0..n) (n >= 1) to the tree, store the part that is not cached in
+ * freshly allocated pages, pin every node on the prompt's path (one more active request) and make
+ * the path the most recently used (time `now`, which must grow from one admission to the next).
+ * *n_cached (may be NULL) receives the number of cached leading tokens, new_slots[n_cached .. n)
+ * the slots of the new tokens (what pa_append_kv needs; entries below n_cached are not written),
+ * *handle what pa_tree_release takes.  PA_ENOMEM if the free pages do not suffice: nothing is
+ * stored or pinned then (evict and call again). */
+int pa_tree_admit(pa_tree* tree, const int32_t* tokens, int32_t n, int64_t now, int32_t* new_slots,
+                  int32_t* n_cached, int64_t* handle);
+
+/* The request of this handle has finished: its path is no longer pinned by it. */
+int pa_tree_release(pa_tree* tree, int64_t handle);
+
+/* Evict until at least need_slots slots are in free pages, or nothing evictable is left: the
+ * least recently used leaf that no admitted request runs through goes first, from its tail,
+ * token by token, and only as far as needed; a parent whose children are all gone is a leaf in
+ * turn.  *freed_slots (may be NULL) receives the slots of the pages that became free,
+ * *evicted_tokens (may be NULL) the number of tokens dropped from the tree. */
+int pa_tree_evict(pa_tree* tree, int64_t need_slots, int64_t* freed_slots, int64_t* evicted_tokens);
+
+/* ---------------------------------------------------------------------------------
  * KV pool.  num_slots rows, each holding K and V of one token for all Hkv heads.  The
  * byte layout is private to the library: only pa_append_kv writes it and only
  * pa_extend_attention / pa_gather_kv read it.  The caller allocates

@@ -34,6 +34,11 @@ _SIGS = {
     "pa_tree_upload": (_i, [_vp, _vp]),
     "pa_tree_stats": (_i, [_vp, C.POINTER(_i64), C.POINTER(_i64)]),
     "pa_tree_destroy": (_i, [_vp]),
+    "pa_tree_attach_pool": (_i, [_vp, _i64, _i]),
+    "pa_tree_free_slots": (_i, [_vp, C.POINTER(_i64)]),
+    "pa_tree_admit": (_i, [_vp, _vp, C.c_int32, _i64, _vp, C.POINTER(C.c_int32), C.POINTER(_i64)]),
+    "pa_tree_release": (_i, [_vp, _i64]),
+    "pa_tree_evict": (_i, [_vp, _i64, C.POINTER(_i64), C.POINTER(_i64)]),
     "pa_kv_pool_bytes": (_sz, [_i64, _i, _i, _i, _i]),
     "pa_extend_workspace_bytes": (_sz, [_i, _i64, _i64, _i, _i, _i, _i]),
     "pa_match_prefixes": (_i, [_vp, _vp, _vp, _i, _vp, _vp, _vp]),
@@ -98,13 +103,41 @@ class Tree:
     def upload(self, stream=None):
         _check(_lib.pa_tree_upload(self._h, _stream(stream)), "pa_tree_upload")
 
+    # ---- cache bookkeeping on the host (pa_tree_attach_pool / admit / release / evict) ----
+    def attach_pool(self, num_slots: int, page_size: int) -> None:
+        _check(_lib.pa_tree_attach_pool(self._h, num_slots, page_size), "pa_tree_attach_pool")
+
+    def free_slots(self) -> int:
+        n = _i64(0)
+        _check(_lib.pa_tree_free_slots(self._h, C.byref(n)), "pa_tree_free_slots")
+        return int(n.value)
+
+    def admit(self, tokens, now: int):
+        """-> (n_cached, new_slots int32 tensor of the tokens that were not cached, handle)."""
+        t = torch.as_tensor(tokens, dtype=torch.int32).contiguous()
+        if t.is_cuda or t.dim() != 1:
+            raise TypeError("tokens must be a host int32 vector")
+        slots = torch.full_like(t, -1)
+        cached, handle = C.c_int32(0), _i64(0)
+        _check(_lib.pa_tree_admit(self._h, _ptr(t), t.numel(), now, _ptr(slots), C.byref(cached), C.byref(handle)), "pa_tree_admit")
+        return int(cached.value), slots[int(cached.value):].clone(), int(handle.value)
+
+    def release(self, handle: int) -> None:
+        _check(_lib.pa_tree_release(self._h, handle), "pa_tree_release")
+
+    def evict(self, need_slots: int):
+        """-> (slots in pages that became free, tokens dropped)."""
+        freed, gone = _i64(0), _i64(0)
+        _check(_lib.pa_tree_evict(self._h, need_slots, C.byref(freed), C.byref(gone)), "pa_tree_evict")
+        return int(freed.value), int(gone.value)
+
     def stats(self) -> Tuple[int, int]:
         a, b = _i64(0), _i64(0)
         _check(_lib.pa_tree_stats(self._h, C.byref(a), C.byref(b)), "pa_tree_stats")
         return int(a.value), int(b.value)
 
     def close(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and _lib is not None:  # (module globals may be gone at interpreter exit)
             _lib.pa_tree_destroy(self._h)
             self._h = None
 

@@ -32,13 +32,23 @@ struct Node {
     std::vector<int32_t> tok;   // edge tokens leading into this node
     std::vector<int32_t> slot;  // KV slot of each edge token
     std::unordered_map<int32_t, int32_t> child;  // first token of child's edge -> node id
+    int32_t parent = -1;        // -1: the root, or a node that was evicted whole (its id waits for reuse)
+    int32_t ref = 0;            // requests admitted and not yet released whose prompt runs through this node
+    int64_t last = 0;           // time of the last admission that ran through this node
 };
 
 }  // namespace pa
 
 struct pa_tree {
     std::vector<pa::Node> nodes;
+    std::vector<int32_t> free_nodes;  // ids of evicted nodes
     int64_t n_tokens = 0;
+    // cache bookkeeping, once a pool is attached
+    int64_t num_slots = 0;
+    int32_t page_size = 0;
+    std::vector<int32_t> free_pages;  // stack: the back is handed out next
+    std::vector<int32_t> page_live;   // cached tokens per page
+    int64_t clock = INT64_MIN;        // time of the last admission
     // device mirror
     bool uploaded = false;
     int device = -1;
@@ -58,11 +68,50 @@ extern "C" int pa_tree_create(pa_tree** out) {
     return PA_OK;
 }
 
+namespace pa {
+
+static int32_t new_node(pa_tree* t) {
+    if (!t->free_nodes.empty()) {
+        const int32_t id = t->free_nodes.back();
+        t->free_nodes.pop_back();
+        t->nodes[id] = Node();
+        return id;
+    }
+    t->nodes.emplace_back();
+    return static_cast<int32_t>(t->nodes.size() - 1);
+}
+
+// Splits node c after its first k edge tokens (0 < k < length).  The TAIL keeps the id c - whoever holds c as the
+// deepest node of a path still does - and a new node takes the head, between c and its old parent; both halves
+// carry the pins and the access time.  Returns the head.
+static int32_t split_node(pa_tree* t, int32_t c, int32_t k) {
+    const int32_t h = new_node(t);  // may move the vector: no references across this call
+    auto& nodes = t->nodes;
+    Node& tail = nodes[c];
+    Node& head = nodes[h];
+    head.tok.assign(tail.tok.begin(), tail.tok.begin() + k);
+    head.slot.assign(tail.slot.begin(), tail.slot.begin() + k);
+    head.parent = tail.parent;
+    head.ref = tail.ref;
+    head.last = tail.last;
+    tail.tok.erase(tail.tok.begin(), tail.tok.begin() + k);
+    tail.slot.erase(tail.slot.begin(), tail.slot.begin() + k);
+    tail.parent = h;
+    head.child.emplace(tail.tok[0], c);
+    nodes[head.parent].child[head.tok[0]] = h;
+    t->uploaded = false;
+    return h;
+}
+
+}  // namespace pa
+
 extern "C" int pa_tree_insert(pa_tree* tree, const int32_t* tokens, const int32_t* slots, int32_t n,
                               int32_t* n_already_cached) {
     PA_REQUIRE(tree != nullptr, "pa_tree_insert: tree is NULL");
     PA_REQUIRE(n >= 0 && (n == 0 || (tokens && slots)), "pa_tree_insert: bad sequence (n=%d)", n);
     std::lock_guard<std::mutex> lk(tree->mu);
+    if (tree->page_size > 0)
+        return pa::fail(PA_ESTATE, "pa_tree_insert: a pool is attached, slots come from pa_tree_admit");
     auto& nodes = tree->nodes;
     int32_t cur = 0, pos = 0;
     try {
@@ -76,32 +125,19 @@ extern "C" int pa_tree_insert(pa_tree* tree, const int32_t* tokens, const int32_
             while (k < lim && nodes[c].tok[k] == tokens[pos + k]) ++k;
             if (k < elen) {
                 if (pos + k == n) { pos = n; break; }  // the sequence ends inside this edge: nothing new to store
-                // split c at k: c keeps [0,k), a new node takes [k,elen) together with c's children
-                pa::Node rest;
-                rest.tok.assign(nodes[c].tok.begin() + k, nodes[c].tok.end());
-                rest.slot.assign(nodes[c].slot.begin() + k, nodes[c].slot.end());
-                rest.child.swap(nodes[c].child);
-                const int32_t rid = static_cast<int32_t>(nodes.size());
-                const int32_t first = rest.tok[0];
-                nodes.push_back(std::move(rest));
-                nodes[c].tok.resize(k);
-                nodes[c].slot.resize(k);
-                nodes[c].child.clear();
-                nodes[c].child.emplace(first, rid);
+                cur = pa::split_node(tree, c, k);
                 pos += k;
-                cur = c;
-                break;  // tokens[pos] differs from `first`, so the walk ends here
+                break;  // tokens[pos] differs from the tail's first token, so the walk ends here
             }
             pos += elen;
             cur = c;
         }
         if (n_already_cached) *n_already_cached = pos;
         if (pos < n) {
-            pa::Node leaf;
-            leaf.tok.assign(tokens + pos, tokens + n);
-            leaf.slot.assign(slots + pos, slots + n);
-            const int32_t lid = static_cast<int32_t>(nodes.size());
-            nodes.push_back(std::move(leaf));
+            const int32_t lid = pa::new_node(tree);
+            nodes[lid].tok.assign(tokens + pos, tokens + n);
+            nodes[lid].slot.assign(slots + pos, slots + n);
+            nodes[lid].parent = cur;
             nodes[cur].child.emplace(tokens[pos], lid);
             tree->n_tokens += n - pos;
             tree->uploaded = false;
@@ -112,9 +148,165 @@ extern "C" int pa_tree_insert(pa_tree* tree, const int32_t* tokens, const int32_
     return PA_OK;
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Cache bookkeeping around the hot path (Sec. 3.3: the local scheduler keeps, next to the prefix tree, the number
+// of active requests sharing each node, and when memory is short evicts a node, or part of one if a part is
+// enough, by the access time of the nodes' requests).  Pages follow the reading used for the workloads: the new
+// part of a prompt receives whole pages, token t of it sits in slot page[t / p] * p + t % p.
+// ---------------------------------------------------------------------------------------------------------
+extern "C" int pa_tree_attach_pool(pa_tree* tree, int64_t num_slots, int page_size) {
+    PA_REQUIRE(tree != nullptr, "pa_tree_attach_pool: tree is NULL");
+    PA_REQUIRE(page_size >= 1 && num_slots >= page_size && num_slots % page_size == 0 && num_slots / page_size <= INT32_MAX &&
+                   num_slots <= INT32_MAX,
+               "pa_tree_attach_pool: num_slots %lld, page_size %d", static_cast<long long>(num_slots), page_size);
+    std::lock_guard<std::mutex> lk(tree->mu);
+    if (tree->n_tokens != 0 || tree->page_size != 0)
+        return pa::fail(PA_ESTATE, "pa_tree_attach_pool: the tree must be empty and have no pool yet");
+    try {
+        const int32_t pages = static_cast<int32_t>(num_slots / page_size);
+        tree->free_pages.resize(pages);
+        for (int32_t i = 0; i < pages; ++i) tree->free_pages[i] = pages - 1 - i;  // page 0 is handed out first
+        tree->page_live.assign(pages, 0);
+    } catch (const std::bad_alloc&) {
+        return pa::fail(PA_ENOMEM, "pa_tree_attach_pool: out of host memory");
+    }
+    tree->num_slots = num_slots;
+    tree->page_size = page_size;
+    return PA_OK;
+}
+
+extern "C" int pa_tree_free_slots(const pa_tree* tree, int64_t* free_slots) {
+    PA_REQUIRE(tree != nullptr && free_slots != nullptr, "pa_tree_free_slots: NULL argument");
+    *free_slots = static_cast<int64_t>(tree->free_pages.size()) * tree->page_size;
+    return PA_OK;
+}
+
+extern "C" int pa_tree_admit(pa_tree* tree, const int32_t* tokens, int32_t n, int64_t now, int32_t* new_slots,
+                             int32_t* n_cached, int64_t* handle) {
+    PA_REQUIRE(tree != nullptr && handle != nullptr, "pa_tree_admit: NULL argument");
+    PA_REQUIRE(n >= 1 && tokens && new_slots, "pa_tree_admit: bad prompt (n=%d)", n);
+    std::lock_guard<std::mutex> lk(tree->mu);
+    if (tree->page_size == 0) return pa::fail(PA_ESTATE, "pa_tree_admit: no pool attached");
+    if (now <= tree->clock) return pa::fail(PA_EINVAL, "pa_tree_admit: time must increase from one admission to the next");
+    auto& nodes = tree->nodes;
+    const int32_t p = tree->page_size;
+    try {
+        // the cached part of the prompt; a prompt that ends inside an edge splits it there, so that pins are exact
+        int32_t cur = 0, pos = 0;
+        while (pos < n) {
+            auto it = nodes[cur].child.find(tokens[pos]);
+            if (it == nodes[cur].child.end()) break;
+            const int32_t c = it->second;
+            const int32_t elen = static_cast<int32_t>(nodes[c].tok.size());
+            const int32_t lim = std::min(elen, n - pos);
+            int32_t k = 1;
+            while (k < lim && nodes[c].tok[k] == tokens[pos + k]) ++k;
+            if (k < elen) {
+                cur = pa::split_node(tree, c, k);
+                pos += k;
+                break;
+            }
+            pos += elen;
+            cur = c;
+        }
+        const int32_t rem = n - pos;
+        const int64_t need = (static_cast<int64_t>(rem) + p - 1) / p;
+        if (need > static_cast<int64_t>(tree->free_pages.size()))
+            return pa::fail(PA_ENOMEM, "pa_tree_admit: %lld pages needed, %zu free (evict and try again)",
+                            static_cast<long long>(need), tree->free_pages.size());
+        if (rem > 0) {
+            const int32_t lid = pa::new_node(tree);
+            pa::Node& leaf = nodes[lid];
+            leaf.tok.assign(tokens + pos, tokens + n);
+            leaf.slot.resize(rem);
+            int32_t page = -1;
+            for (int32_t i = 0; i < rem; ++i) {
+                if (i % p == 0) {
+                    page = tree->free_pages.back();
+                    tree->free_pages.pop_back();
+                }
+                leaf.slot[i] = page * p + i % p;
+                ++tree->page_live[page];
+                new_slots[pos + i] = leaf.slot[i];
+            }
+            leaf.parent = cur;
+            nodes[cur].child.emplace(tokens[pos], lid);
+            tree->n_tokens += rem;
+            cur = lid;
+        }
+        for (int32_t x = cur; x > 0; x = nodes[x].parent) {  // pin the path, and it is the most recently used now
+            ++nodes[x].ref;
+            nodes[x].last = now;
+        }
+        tree->clock = now;
+        tree->uploaded = false;
+        if (n_cached) *n_cached = pos;
+        *handle = cur;
+    } catch (const std::bad_alloc&) {
+        return pa::fail(PA_ENOMEM, "pa_tree_admit: out of host memory");
+    }
+    return PA_OK;
+}
+
+extern "C" int pa_tree_release(pa_tree* tree, int64_t handle) {
+    PA_REQUIRE(tree != nullptr, "pa_tree_release: tree is NULL");
+    std::lock_guard<std::mutex> lk(tree->mu);
+    auto& nodes = tree->nodes;
+    PA_REQUIRE(handle > 0 && handle < static_cast<int64_t>(nodes.size()) && nodes[handle].ref > 0 && !nodes[handle].tok.empty(),
+               "pa_tree_release: %lld is not the handle of an admitted request", static_cast<long long>(handle));
+    for (int32_t x = static_cast<int32_t>(handle); x > 0; x = nodes[x].parent) {
+        if (nodes[x].ref <= 0) return pa::fail(PA_ESTATE, "pa_tree_release: pin counts are inconsistent at node %d", x);
+        --nodes[x].ref;
+    }
+    return PA_OK;
+}
+
+extern "C" int pa_tree_evict(pa_tree* tree, int64_t need_slots, int64_t* freed_slots, int64_t* evicted_tokens) {
+    PA_REQUIRE(tree != nullptr, "pa_tree_evict: tree is NULL");
+    std::lock_guard<std::mutex> lk(tree->mu);
+    if (tree->page_size == 0) return pa::fail(PA_ESTATE, "pa_tree_evict: no pool attached");
+    auto& nodes = tree->nodes;
+    const int32_t p = tree->page_size;
+    int64_t freed = 0, gone = 0;
+    while (freed < need_slots) {
+        // least recently used leaf that no admitted request runs through (admission times are distinct, and an
+        // admission touches one path, so no two leaves share a time)
+        int32_t victim = -1;
+        for (int32_t i = 1; i < static_cast<int32_t>(nodes.size()); ++i) {
+            const pa::Node& nd = nodes[i];
+            if (nd.tok.empty() || !nd.child.empty() || nd.ref != 0) continue;
+            if (victim < 0 || nd.last < nodes[victim].last) victim = i;
+        }
+        if (victim < 0) break;
+        pa::Node& nd = nodes[victim];
+        const int32_t first_tok = nd.tok.front();
+        // from the tail, token by token, until enough whole pages are free: part of a node if a part is enough
+        while (!nd.tok.empty() && freed < need_slots) {
+            const int32_t page = nd.slot.back() / p;
+            nd.tok.pop_back();
+            nd.slot.pop_back();
+            ++gone;
+            if (--tree->page_live[page] == 0) {
+                tree->free_pages.push_back(page);
+                freed += p;
+            }
+        }
+        if (nd.tok.empty()) {
+            nodes[nd.parent].child.erase(first_tok);
+            nd.parent = -1;
+            tree->free_nodes.push_back(victim);
+        }
+    }
+    tree->n_tokens -= gone;
+    if (gone) tree->uploaded = false;
+    if (freed_slots) *freed_slots = freed;
+    if (evicted_tokens) *evicted_tokens = gone;
+    return PA_OK;
+}
+
 extern "C" int pa_tree_stats(const pa_tree* tree, int64_t* n_nodes, int64_t* n_tokens) {
     PA_REQUIRE(tree != nullptr, "pa_tree_stats: tree is NULL");
-    if (n_nodes) *n_nodes = static_cast<int64_t>(tree->nodes.size());
+    if (n_nodes) *n_nodes = static_cast<int64_t>(tree->nodes.size() - tree->free_nodes.size());
     if (n_tokens) *n_tokens = tree->n_tokens;
     return PA_OK;
 }

@@ -534,3 +534,84 @@ def test_decode_shape_one_new_token(pa, gpu_device):
     err = np.abs(out_to_f64(out) - ref).max() if c["T"] else 0.0
     say(f"  decode shape: T = {c['T']}, max abs err {err:.3e}")
     assert c["T"] >= 8 and err <= TOL["bf16"]
+
+
+def test_cache_loop_with_eviction(pa, gpu_device):
+    """Rounds of upload -> match (GPU) -> admit (host: pages for the new tokens, pins) -> extend -> append, with
+    releases and LRU evictions in between, so that pages are reused and pool rows overwritten.  Every round the
+    GPU match has to agree with what the admission finds cached and with the per-token cache oracle, and the
+    attention output with the fp64 oracle on the oracle's own copy of the pool."""
+    import oracle
+    from oracle.cache_oracle import CacheOracle
+    rng = np.random.default_rng(404)
+    Hq, Hkv, D, page, nslots = 8, 2, 128, 16, 2048
+    dev, tdt = gpu_device, torch.bfloat16
+    tree, co = pa.Tree(), CacheOracle(nslots, page)
+    tree.attach_pool(nslots, page)
+    pool = torch.zeros(pa.kv_pool_bytes(nslots, Hkv, D, tdt, page), dtype=torch.uint8, device=dev)
+    opk, opv = oracle.new_pool(nslots, Hkv, D, "bf16")
+    kw = dict(page_size=page, num_slots=nslots)
+    tt = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    history, live, now, worst, evictions = [], [], 0, 0.0, 0
+    for rnd in range(14):
+        # prompts: continuations of earlier prompts (cut anywhere) or fresh ones; new parts are random, so distinct
+        prompts = []
+        for _ in range(int(rng.integers(1, 4))):
+            if history and rng.random() < 0.7:
+                base = history[int(rng.integers(len(history)))]
+                head = base[:int(rng.integers(1, len(base) + 1))]
+            else:
+                head = np.zeros(0, np.int32)
+            prompts.append(np.concatenate([head, rng.integers(0, 50000, int(rng.integers(20, 300)))]).astype(np.int32))
+        need = sum((len(p) + page - 1) // page * page for p in prompts)
+        if tree.free_slots() < need:
+            for _ in range(len(live) // 2 + 1):  # finish some requests, then make room by LRU
+                if live:
+                    hl, ho = live.pop(0)
+                    tree.release(hl)
+                    co.release(ho)
+            assert tree.evict(need) == co.evict(need)
+            evictions += 1
+        # two requests of one batch must not share tokens that are not cached (any more): the second would find them
+        # in the tree, put there by the first's admission, before their KV exists.  Such a request is dropped here.
+        lcp = lambda a, b: int((np.cumprod(a[:min(len(a), len(b))] == b[:min(len(a), len(b))])).sum())
+        kept = []
+        for cand in prompts:
+            if all(lcp(cand, q) <= co.match(cand)[0] for q in kept):
+                kept.append(cand)
+        prompts = kept
+        tree.upload()
+        toks = np.concatenate(prompts)
+        off = np.zeros(len(prompts) + 1, np.int32)
+        off[1:] = np.cumsum([len(p) for p in prompts])
+        pl, si = pa.match_prefixes(tree, tt(toks), tt(off))
+        pln, sin = pl.cpu().numpy(), si.cpu().numpy()
+        el, new_slots = [], []
+        want = [co.match(p) for p in prompts]  # before any of the batch is admitted
+        for j, p in enumerate(prompts):
+            want_n, want_slots = want[j]
+            assert pln[j] == want_n and list(sin[off[j]:off[j] + want_n]) == want_slots
+            now += 1
+            got, ref = tree.admit(p, now), co.admit(list(p), now)
+            assert ref is not None and got[0] == want_n == ref[0] and got[1].tolist() == ref[1]
+            live.append((got[2], ref[2]))
+            history.append(p)
+            el.append(len(p) - want_n)
+            new_slots.append(np.asarray(ref[1], np.int32))
+        el = np.asarray(el, np.int32)
+        eo = np.zeros(len(prompts) + 1, np.int32)
+        eo[1:] = np.cumsum(el)
+        T = int(eo[-1])
+        ss = np.random.SeedSequence(rnd).spawn(3)
+        mk = lambda s_, h: W._normal(s_, T * h * D, "bf16").reshape(T, h, D)
+        q, k, v = mk(ss[0], Hq), mk(ss[1], Hkv), mk(ss[2], Hkv)
+        scale = 1.0 / np.sqrt(D)
+        out = pa.extend_attention(to_torch(q, "bf16", dev), to_torch(k, "bf16", dev), to_torch(v, "bf16", dev), pool, si, tt(off),
+                                  pl, tt(el), tt(eo), scale, max_kv_len=int((off[1:] - off[:-1]).max()), **kw)
+        ref_out = oracle.extend_attention(q, k, v, opk, opv, sin, off, pln, el, eo, scale, "bf16")
+        worst = max(worst, float(np.abs(out_to_f64(out) - ref_out).max()))
+        ns = np.concatenate(new_slots)
+        pa.append_kv(pool, tt(ns), to_torch(k, "bf16", dev), to_torch(v, "bf16", dev), **kw)
+        oracle.append_kv(opk, opv, ns, k, v, "bf16")
+    say(f"  cache loop: {evictions} evictions, worst max abs err over the rounds {worst:.3e}")
+    assert evictions >= 2 and worst <= TOL["bf16"]
