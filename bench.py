@@ -88,6 +88,58 @@ def cpu_baseline(wl, budget_s=15.0):
                       f"(whole batch {t_match:.3f}s, {wl.B / t_match:.0f} req/s), fp64 attention {t_att:.2f}s, append {t_app:.4f}s"}
 
 
+def extras(pa, g, wl, prefix_len, slot_idx, out, ws, main_k, nbytes):
+    """Two measurements beside the step: the extend-attention kernel with cold caches (1 GiB streamed through the
+    chip between launches: the L2s and the memory-side cache hold none of the K/V when it starts), and the matcher
+    on a batch large enough to show its bandwidth (4,096 requests resampled from the workload's)."""
+    import numpy as np
+    import torch
+    dev = g.tokens.device
+    ex = {}
+    # ---- cold caches ----
+    flush = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    pa.profile_enable(True)
+    n_cold = 10
+    for i in range(n_cold):
+        flush.fill_(i)
+        pa.extend_attention(g.q, g.k, g.v, g.pool, slot_idx, g.offsets, prefix_len, g.ext_len, g.ext_offsets, wl.scale,
+                            max_kv_len=g.max_kv_len, out=out, workspace=ws, **g.kw)
+    torch.cuda.synchronize()
+    pa.profile_enable(False)
+    ms, n = pa.profile_read(main_k)
+    if n:
+        t = ms / n * 1e-3
+        ex["extend_cold_cache"] = {"avg_kernel_us": t * 1e6, "launches": n, "GBps_algorithmic": nbytes / t / 1e9,
+                                   "hbm_frac": nbytes / t / 1e9 / HBM_PEAK_GBS, "flushed_bytes_between_launches": 1 << 30}
+    del flush
+    # ---- matcher at a batch that fills the chip ----
+    rng = np.random.default_rng(0)
+    Bbig = 4096
+    pick = rng.integers(0, wl.B, Bbig)
+    lens = (wl.offsets[1:] - wl.offsets[:-1])[pick].astype(np.int64)
+    off = np.zeros(Bbig + 1, np.int64)
+    off[1:] = np.cumsum(lens)
+    if off[-1] < 2 ** 31 - 64:
+        toks = np.concatenate([wl.tokens[wl.offsets[r]:wl.offsets[r + 1]] for r in pick]).astype(np.int32)
+        t_d, o_d = torch.from_numpy(toks).to(dev), torch.from_numpy(off.astype(np.int32)).to(dev)
+        pl = torch.empty(Bbig, dtype=torch.int32, device=dev)
+        si = torch.empty_like(t_d)
+        for _ in range(2):
+            pa.match_prefixes(g.tree, t_d, o_d, pl, si)
+        pa.profile_enable(True)
+        for _ in range(5):
+            pa.match_prefixes(g.tree, t_d, o_d, pl, si)
+        torch.cuda.synchronize()
+        pa.profile_enable(False)
+        ms, n = pa.profile_read("match_prefixes")
+        assert (pl.cpu().numpy() == wl.designed_prefix_len[pick]).all()
+        t = ms / n * 1e-3
+        matched = int(wl.designed_prefix_len[pick].astype(np.int64).sum())
+        ex["match_scaled"] = {"requests": Bbig, "avg_kernel_us": t * 1e6, "reqs_per_s": Bbig / t, "matched_tokens_per_s": matched / t,
+                              "GBps": 16.0 * matched / t / 1e9, "bytes_per_matched_token": 16}
+    return ex
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -95,6 +147,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="tool_use", choices=["tiny_fp32", "tool_use", "long_doc_qa", "agent_tree", "video_qa"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the cold-cache and the scaled-matcher measurements")
     ap.add_argument("--only", default="", help="time only one call of the path: match | extend | append (for profiling)")
     ap.add_argument("--graph", action="store_true", help="replay one captured HIP graph per step instead of launching its calls "
                     "from the host (measured: no faster, the gaps between the dependent kernels are not host-bound)")
@@ -216,6 +269,12 @@ def main():
     }
     if "match_prefixes" in kern:
         res["match_reqs_per_s"] = wl.B / (kern["match_prefixes"]["avg_us"] * 1e-6)
+    if "append_kv" in kern:
+        el = 4 if wl.dtype == "f32" else 2
+        app_bytes = 2 * (2 * wl.T * wl.Hkv * wl.D * el) + 4 * wl.T   # K and V rows read and written, slot ids read
+        res["append_GBps"] = app_bytes / (kern["append_kv"]["avg_us"] * 1e-6) / 1e9
+    if not args.no_extras and not args.only:
+        res["extras"] = extras(pa, g, wl, prefix_len, slot_idx, out, ws, main_k, nbytes)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(res))
