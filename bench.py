@@ -236,6 +236,16 @@ def main():
         ms, n = pa.profile_read(name)
         if n:
             kern[name] = {"avg_us": ms / n * 1e3, "launches_per_step": n / args.steps}
+    shader_mhz = 0.0
+    if wl.dtype == "bf16":
+        # a few more steps with the clock probe in the kernel, kept out of the times above
+        pa.profile_clock(ws, reset=True)
+        pa.profile_enable(True, clock_probe=True)
+        for _ in range(min(args.steps, 20)):
+            step()
+        torch.cuda.synchronize()
+        pa.profile_enable(False)
+        shader_mhz = pa.profile_clock(ws)
 
     pl = prefix_len.cpu().numpy()
     assert (pl == wl.designed_prefix_len).all(), "matcher disagrees with the designed prefix lengths"
@@ -255,6 +265,11 @@ def main():
         roofline.update({"traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "kernel": main_k,
                          "avg_kernel_us": kern[main_k]["avg_us"], "algorithmic_bytes": nbytes, "algorithmic_flops": flops,
                          "hbm_frac": gbs / HBM_PEAK_GBS, "compute_frac": tfs / peak_f})
+        if shader_mhz > 0 and wl.dtype == "bf16":
+            # the clock the kernel ran at (shader cycles against the 100 MHz constant counter, across the key loop of a
+            # few workgroups), and the matrix peak at that clock: 2.5 PFLOP/s is quoted at 2,400 MHz
+            roofline["shader_mhz"] = shader_mhz
+            roofline["compute_frac_at_measured_clock"] = tfs / (peak_f * shader_mhz / 2400.0)
 
     res = {
         "metric": "extend_prefill_tokens_per_s", "value": wl.T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,

@@ -205,6 +205,14 @@ int pa_gather_kv(const void* kv_pool, const int32_t* slots, int64_t n, int Hkv, 
 int pa_profile_enable(int on);
 int pa_profile_read(const char* kernel, double* total_ms, int64_t* launches);
 
+/* Clock probe, for benchmarks: after pa_profile_enable(2) (timing plus the probe; the probed kernel reads
+ * two clocks more per workgroup, so time it with pa_profile_enable(1)), a few workgroups of every bf16
+ * extend-attention launch add the shader cycles and the ticks of the constant 100 MHz counter that pass across their key
+ * loop to two counters in the workspace (device pointer, the one given to pa_extend_attention).
+ * reset != 0 zeroes the counters; reset == 0 reads them: *shader_mhz = 100 * cycles / ticks, the clock
+ * the kernel actually ran at (0 if nothing was recorded).  Synchronises the device. */
+int pa_profile_clock(void* workspace, int reset, double* shader_mhz);
+
 #ifdef __cplusplus
 }
 #endif

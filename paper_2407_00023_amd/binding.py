@@ -47,6 +47,7 @@ _SIGS = {
     "pa_gather_kv": (_i, [_vp, _vp, _i64, _i, _i, _i, _i64, _i, _vp, _vp, _vp]),
     "pa_profile_enable": (_i, [_i]),
     "pa_profile_read": (_i, [C.c_char_p, C.POINTER(C.c_double), C.POINTER(_i64)]),
+    "pa_profile_clock": (_i, [_vp, _i, C.POINTER(C.c_double)]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _fn = getattr(_lib, _name)
@@ -238,8 +239,15 @@ def gather_kv(kv_pool: torch.Tensor, slots: torch.Tensor, *, Hkv: int, D: int, d
     return k, v
 
 
-def profile_enable(on: bool) -> None:
-    _check(_lib.pa_profile_enable(1 if on else 0), "pa_profile_enable")
+def profile_enable(on: bool, clock_probe: bool = False) -> None:
+    _check(_lib.pa_profile_enable((2 if clock_probe else 1) if on else 0), "pa_profile_enable")
+
+
+def profile_clock(workspace: torch.Tensor, reset: bool = False) -> float:
+    """Shader clock in MHz seen by the bf16 extend-attention launches that used `workspace` while the clock probe was on."""
+    mhz = C.c_double(0.0)
+    _check(_lib.pa_profile_clock(_ptr(workspace), 1 if reset else 0, C.byref(mhz)), "pa_profile_clock")
+    return float(mhz.value)
 
 
 def profile_read(kernel: str) -> Tuple[float, int]:

@@ -98,6 +98,11 @@ __host__ __device__ inline int64_t pool_row(int64_t slot, int which, int g, int 
 
 // Per-kernel event timing (profile.cpp).  A ProfScope around a launch records a start/stop event
 // pair on the stream while profiling is switched on, and does nothing otherwise.
+// Byte offset, in the workspace of pa_extend_attention, of the two 64-bit counters of the clock probe (the header
+// of the workspace is 256 bytes; the first 12 hold the work-list counts).
+constexpr size_t kClockProbeOffset = 128;
+bool prof_clock_enabled();
+
 enum ProfKernel { kProfMatch = 0, kProfTiles, kProfExtend, kProfMerge, kProfExtendF32, kProfAppend, kProfGather, kProfKernels };
 bool prof_begin(int kernel, hipStream_t stream, size_t* slot);
 void prof_end(size_t slot, hipStream_t stream);

@@ -235,7 +235,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     const int32_t* __restrict__ ext_offsets, int Hq, int Hkv, int page_size, int page_shift, int num_slots,
     int fast_ok, float scale_log2e, __hip_bfloat16* __restrict__ out, const int32_t* __restrict__ n_tiles,
     const int32_t* __restrict__ tile_req, const int32_t* __restrict__ tile_row0, int nsplit, int chunk,
-    float* __restrict__ part_o, float* __restrict__ part_ml) {
+    float* __restrict__ part_o, float* __restrict__ part_ml, unsigned long long* __restrict__ clk) {
     constexpr int WR = 32 * RB;              // packed query rows per wave (RB blocks of 32)
     constexpr int MT = WR * NW;              // packed query rows per workgroup
     constexpr int NB = D / 32;               // MFMA row blocks of the head dimension in O^T
@@ -503,6 +503,12 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     wait_vm_all();
     wg_barrier();
 
+    // clock probe (benchmarks only): shader cycles and ticks of the constant 100 MHz counter across the key loop
+    long long clk_c0 = 0, clk_w0 = 0;
+    if (clk) {
+        clk_c0 = clock64();
+        clk_w0 = wall_clock64();
+    }
     int p0 = kv_lo, ring = 0;  // the tile at p0 sits in ring slot `ring`
     // the LDS read addresses follow the ring: from slot `from_ring` to the other one
     auto move_read_addresses = [&](int from_ring) __attribute__((always_inline)) {
@@ -586,6 +592,10 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
         next_tile();
     }
 
+    if (clk && blockIdx.x % 997 == 7 && tid == 0) {
+        atomicAdd(clk, static_cast<unsigned long long>(clock64() - clk_c0));
+        atomicAdd(clk + 1, static_cast<unsigned long long>(wall_clock64() - clk_w0));
+    }
     // ---- epilogue: lane holds, for block b and register i, head-dim element 32 b + 8 (i / 4) + 4 hh + i % 4 ----
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -676,7 +686,7 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
                          const void* kv_pool, const int32_t* slot_idx, const int32_t* slot_offsets,
                          const int32_t* prefix_len, const int32_t* ext_len, const int32_t* ext_offsets, int Hq, int Hkv,
                          int page_size, int64_t num_slots, int64_t T_total, float scale_log2e, void* out, int32_t* n_tiles,
-                         int32_t* tile_req, int32_t* tile_row0, float* part_o, float* part_ml, hipStream_t stream) {
+                         int32_t* tile_req, int32_t* tile_row0, float* part_o, float* part_ml, unsigned long long* clk, hipStream_t stream) {
     constexpr size_t lds_bytes = static_cast<size_t>(kStages) * 2 * kKT * D * 2;
     int page_shift = -1;
     if ((page_size & (page_size - 1)) == 0) {
@@ -698,7 +708,7 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
                            static_cast<const __hip_bfloat16*>(v_ext), static_cast<const __hip_bfloat16*>(kv_pool), slot_idx,
                            slot_offsets, prefix_len, ext_len, ext_offsets, Hq, Hkv, page_size, page_shift,
                            static_cast<int>(num_slots), fast_ok, scale_log2e, static_cast<__hip_bfloat16*>(out), n_tiles, tile_req,
-                           tile_row0, p.nsplit, p.chunk, part_o, part_ml);
+                           tile_row0, p.nsplit, p.chunk, part_o, part_ml, clk);
     }
     if (p.nsplit > 1) {
         ProfScope prof(kProfMerge, stream);
@@ -735,6 +745,8 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
     int32_t* tile_row0 = reinterpret_cast<int32_t*>(ws + p.off_row0);
     float* part_o = reinterpret_cast<float*>(ws + p.off_part_o);
     float* part_ml = reinterpret_cast<float*>(ws + p.off_part_ml);
+    // with the clock probe on, a few workgroups also add their cycle counts to two counters in the header
+    unsigned long long* clk = prof_clock_enabled() ? reinterpret_cast<unsigned long long*>(ws + kClockProbeOffset) : nullptr;
     const int G = Hq / Hkv;
     const float scale_log2e = scale * 1.4426950408889634f;
     {
@@ -744,10 +756,10 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
     }
     if (D == 64)
         launch_extend<64, 4, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, Hq,
-                             Hkv, page_size, num_slots, T, scale_log2e, out, n_tiles, tile_req, tile_row0, part_o, part_ml, stream);
+                             Hkv, page_size, num_slots, T, scale_log2e, out, n_tiles, tile_req, tile_row0, part_o, part_ml, clk, stream);
     else
         launch_extend<128, 4, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, Hq,
-                              Hkv, page_size, num_slots, T, scale_log2e, out, n_tiles, tile_req, tile_row0, part_o, part_ml, stream);
+                              Hkv, page_size, num_slots, T, scale_log2e, out, n_tiles, tile_req, tile_row0, part_o, part_ml, clk, stream);
     PA_HIP(hipGetLastError());
     return PA_OK;
 }

@@ -20,9 +20,15 @@ struct ProfRecord {
 
 static std::mutex g_prof_mu;
 static bool g_prof_on = false;
+static bool g_prof_clock = false;
 static std::vector<ProfRecord> g_prof_records;  // events are reused across enable() calls
 static size_t g_prof_used = 0;
 constexpr size_t kProfMaxRecords = 1 << 16;
+
+bool prof_clock_enabled() {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    return g_prof_on && g_prof_clock;
+}
 
 bool prof_begin(int kernel, hipStream_t stream, size_t* slot) {
     std::lock_guard<std::mutex> lk(g_prof_mu);
@@ -50,6 +56,7 @@ extern "C" int pa_profile_enable(int on) {
     std::lock_guard<std::mutex> lk(pa::g_prof_mu);
     if (on) pa::g_prof_used = 0;
     pa::g_prof_on = on != 0;
+    pa::g_prof_clock = on == 2;
     return PA_OK;
 }
 
@@ -73,5 +80,20 @@ extern "C" int pa_profile_read(const char* kernel, double* total_ms, int64_t* la
     }
     if (total_ms) *total_ms = ms;
     if (launches) *launches = n;
+    return PA_OK;
+}
+
+extern "C" int pa_profile_clock(void* workspace, int reset, double* shader_mhz) {
+    PA_REQUIRE(workspace != nullptr, "pa_profile_clock: workspace is NULL");
+    unsigned char* at = static_cast<unsigned char*>(workspace) + pa::kClockProbeOffset;
+    unsigned long long c[2] = {0, 0};
+    PA_HIP(hipDeviceSynchronize());
+    if (reset) {
+        PA_HIP(hipMemcpy(at, c, sizeof c, hipMemcpyHostToDevice));
+        if (shader_mhz) *shader_mhz = 0.0;
+        return PA_OK;
+    }
+    PA_HIP(hipMemcpy(c, at, sizeof c, hipMemcpyDeviceToHost));
+    if (shader_mhz) *shader_mhz = c[1] ? 100.0 * static_cast<double>(c[0]) / static_cast<double>(c[1]) : 0.0;
     return PA_OK;
 }
