@@ -118,6 +118,96 @@ int pa_tree_release(pa_tree* tree, int64_t handle);
  * *evicted_tokens (may be NULL) the number of tokens dropped from the tree. */
 int pa_tree_evict(pa_tree* tree, int64_t need_slots, int64_t* freed_slots, int64_t* evicted_tokens);
 
+/* Make room for a prompt about to be admitted: as pa_tree_evict with need_slots = the whole pages
+ * its part that is not cached needs, less the free ones, and never dropping a token of its cached
+ * part (a request must not evict the prefix it is about to reuse). */
+int pa_tree_evict_for(pa_tree* tree, const int32_t* tokens, int32_t n, int64_t* freed_slots,
+                      int64_t* evicted_tokens);
+
+/* Admission times older than `window` before the latest admission are forgotten from then on
+ * (0, the default: none is).  They are what pa_tree_evict_plan counts sharers from. */
+int pa_tree_set_hit_window(pa_tree* tree, int64_t window);
+
+/* What pa_tree_evict(tree, need_slots, ...) would drop, without dropping it (Sec. 3.2, second cost:
+ * "the tree nodes that would be evicted to run the request").  node_tokens[k] receives the number
+ * of tokens the k-th victim would lose (all of a node, or its tail), node_sharers[k] the number of
+ * admissions later than time `since` whose prompt ran through that node (a node that goes whole
+ * and is followed at once by its parent with the same count forms one entry with it: where a path
+ * used by the same requests happens to be cut does not show); at most `cap` entries
+ * are written, *n_nodes receives the number there are (PA_ENOMEM if it exceeds cap), and
+ * *n_requests (may be NULL) the number of admissions later than `since` in the whole tree. */
+int pa_tree_evict_plan(const pa_tree* tree, int64_t need_slots, int64_t since, int64_t cap, int32_t* node_tokens,
+                       int32_t* node_sharers, int64_t* n_nodes, int64_t* n_requests);
+
+/* The same for pa_tree_evict_for(tree, tokens, n, ...): the E of Algorithm 2 for this prompt. */
+int pa_tree_evict_plan_for(const pa_tree* tree, const int32_t* tokens, int32_t n, int64_t since, int64_t cap,
+                           int32_t* node_tokens, int32_t* node_sharers, int64_t* n_nodes, int64_t* n_requests);
+
+/* ---------------------------------------------------------------------------------
+ * Scheduling decisions on the host: plain functions over numbers the caller holds (all host
+ * pointers; nothing here touches the GPU).  The matcher's prefix lengths are their input.
+ * --------------------------------------------------------------------------------- */
+
+/* Sec. 3.3, "waiting queue request ordering": with P priority groups a request belongs to the
+ * group given by the cached share of its prompt, in whole P-ths (63 of 100 tokens cached, P = 10:
+ * group 6).  Groups run from 0 to P; only a fully cached prompt is in group P. */
+int pa_priority_group(int32_t cached_len, int32_t prompt_len, int32_t P, int32_t* group);
+
+/* Sec. 3.3 and Algorithm 3: choose the next batch of at most n_pick requests from a waiting queue
+ * given in arrival order (cached_len[i], prompt_len[i] of waiting request i).  Group p takes a share
+ * of the picks in proportion to p (55 picks from full groups: 10 from group 10, 9 from group 9, ...,
+ * 1 from group 1), by largest remainder, ties to the higher group; what a group cannot use is shared
+ * out again the same way among the groups that still have requests; group 0 has weight 0 and fills
+ * what the others leave.  Inside a group requests leave in arrival order.  picked[0 .. *n_picked)
+ * (room for min(n_pick, n_waiting) entries) receives queue indices, higher groups first. */
+int pa_priority_select(const int32_t* cached_len, const int32_t* prompt_len, int64_t n_waiting, int32_t P,
+                       int64_t n_pick, int32_t* picked, int64_t* n_picked);
+
+/* The two regression functions of Sec. 3.2 (time against token count, from profiling; the paper
+ * prints no coefficients): PrefillTime(n) = prefill_per_token * n + prefill_base for n > 0, 0 for
+ * n = 0, DecodeTime likewise.  default_output_len stands in for the average output length of a
+ * GPU on which no request has finished inside the window. */
+typedef struct pa_cost_model {
+    double prefill_per_token, prefill_base, decode_per_token, decode_base, default_output_len;
+} pa_cost_model;
+
+/* Algorithm 2, load cost of one GPU for one new request: *L = sum over the n_hist requests of the
+ * window of PrefillTime(hist_missed_len[r]) + DecodeTime(avg_output_len); *M = sum over the n_evict
+ * nodes that would be evicted of PrefillTime(evict_tokens[j]) * evict_sharers[j] / n_requests
+ * (0 if n_requests is 0); *P = PrefillTime(missed_len_k).  The cost is their sum. */
+int pa_e2_load_cost(const pa_cost_model* model, const int32_t* hist_missed_len, int64_t n_hist,
+                    double avg_output_len, const int32_t* evict_tokens, const int32_t* evict_sharers,
+                    int64_t n_evict, int64_t n_requests, int32_t missed_len_k, double* L, double* M, double* P);
+
+#define PA_EXPLOIT 0        /* sent to a GPU that caches the longest node of the matched path */
+#define PA_EXPLORE_DECODE 1 /* sent to the GPU most loaded with decoding */
+#define PA_EXPLORE_COST 2   /* sent to the GPU of lowest load cost */
+
+/* Algorithm 1 for one request over n_gpus GPUs.  If the missed part (prompt_len - cached_len) is
+ * shorter than the cached part, and on_longest_node[i] != 0 for some GPU (GPU i caches the longest
+ * node of the matched path), the request goes to the flagged GPU of lowest cost[i].  Otherwise, if
+ * the highest decode_ratio[i] exceeds imbal_r it goes there, else to the GPU of lowest cost[i].
+ * Ties go to the lowest index. */
+int pa_e2_schedule(int32_t prompt_len, int32_t cached_len, const uint8_t* on_longest_node, const double* cost,
+                   const double* decode_ratio, double imbal_r, int32_t n_gpus, int32_t* gpu, int32_t* mode);
+
+/* Per-GPU request history over the window H of Sec. 3.2 (first cost): what L and the decode ratio
+ * are computed from.  Times are the caller's integers (any unit; the window is in the same unit);
+ * a request counts at time `now` if now - window < its time <= now. */
+typedef struct pa_history pa_history;
+int pa_history_create(int32_t n_gpus, int64_t window, const pa_cost_model* model, pa_history** out);
+int pa_history_destroy(pa_history* h);
+/* A request with missed_len tokens to prefill was assigned to `gpu` at time `now`. */
+int pa_history_assign(pa_history* h, int32_t gpu, int64_t now, int32_t missed_len);
+/* A request on `gpu` finished at time `now` after output_len generated tokens. */
+int pa_history_complete(pa_history* h, int32_t gpu, int64_t now, int32_t output_len);
+/* *L as in pa_e2_load_cost over the window; *decode_ratio = decode time / (prefill + decode time)
+ * of the window (0 if it is empty): the share of "decoding-phase" work on that GPU;
+ * *n_requests the assignments in the window; *avg_output_len the average the decode time used.
+ * Any of the four may be NULL.  Entries older than the window are dropped. */
+int pa_history_gpu_load(pa_history* h, int32_t gpu, int64_t now, double* L, double* decode_ratio,
+                        int64_t* n_requests, double* avg_output_len);
+
 /* ---------------------------------------------------------------------------------
  * KV pool.  num_slots rows, each holding K and V of one token for all Hkv heads.  The
  * byte layout is private to the library: only pa_append_kv writes it and only

@@ -10,6 +10,10 @@ handed out first, freed pages reused last-freed-first; admission times strictly 
 Eviction, per token: while fewer than `need` slots have become free, drop the token that (a) has no child, (b) lies on
 no admitted request's path, (c) has the smallest access time among those.  (Admission times are distinct and one
 admission touches one root-to-leaf path, so (c) never ties between two leaves.)
+
+For the eviction term of the load cost (Sec. 3.2, second cost: the nodes that would be evicted to run a request, each
+weighted by the share of the recent requests that used it) every token also keeps the times of the admissions that
+ran through it, and `evict_plan` says which tokens an eviction would drop, without dropping them.
 """
 from __future__ import annotations
 
@@ -17,13 +21,14 @@ from typing import Dict, List, Optional, Tuple
 
 
 class _Tok:
-    __slots__ = ("token", "slot", "parent", "child", "ref", "last")
+    __slots__ = ("token", "slot", "parent", "child", "ref", "last", "hits")
 
     def __init__(self, token: int, slot: int, parent: Optional["_Tok"]):
         self.token, self.slot, self.parent = token, slot, parent
         self.child: Dict[int, _Tok] = {}
         self.ref = 0
         self.last = 0
+        self.hits: List[int] = []
 
 
 class CacheOracle:
@@ -35,6 +40,7 @@ class CacheOracle:
         self.page_live = [0] * self.n_pages
         self.root = _Tok(-1, -1, None)
         self.clock: Optional[int] = None
+        self.admissions: List[int] = []  # times of all admissions
 
     # -- queries -------------------------------------------------------------------------------------------------
     def free_slots(self) -> int:
@@ -84,8 +90,10 @@ class CacheOracle:
         while x is not self.root:
             x.ref += 1
             x.last = now
+            x.hits.append(now)
             x = x.parent
         self.clock = now
+        self.admissions.append(now)
         return n_cached, new_slots, node
 
     def release(self, handle: _Tok) -> None:
@@ -95,7 +103,43 @@ class CacheOracle:
             x.ref -= 1
             x = x.parent
 
-    def evict(self, need_slots: int) -> Tuple[int, int]:
+    def need_for(self, tokens) -> int:
+        """Slots that admitting this prompt still lacks: the whole pages of its part that is not cached, less the
+        free pages."""
+        rem = len(tokens) - self.match(tokens)[0]
+        return max(0, ((rem + self.p - 1) // self.p) * self.p - self.free_slots())
+
+    def _cached_part(self, tokens) -> set:
+        node, keep = self.root, set()
+        for t in tokens:
+            node = node.child.get(int(t))
+            if node is None:
+                break
+            keep.add(id(node))
+        return keep
+
+    def evict_for(self, tokens) -> Tuple[int, int]:
+        """Make room for a prompt about to be admitted, never dropping a token of its cached part."""
+        return self.evict(self.need_for(tokens), keep=self._cached_part(tokens))
+
+    def evict_plan_for(self, tokens, since: int):
+        return self.evict_plan(self.need_for(tokens), since, keep=self._cached_part(tokens))
+
+    def evict_plan(self, need_slots: int, since: int, keep: Optional[set] = None):
+        """What evict(need_slots) would drop: -> (per dropped token, in order: the number of admissions after time
+        `since` that ran through it; per dropped token: whether it is the parent of the token dropped just before;
+        the number of admissions after `since` in all).  Nothing changes."""
+        pages_before, live_before = list(self.free_pages), list(self.page_live)
+        victims: List[_Tok] = []
+        self.evict(need_slots, victims, keep)
+        for v in reversed(victims):
+            v.parent.child[v.token] = v
+        self.free_pages, self.page_live = pages_before, live_before
+        sharers = [sum(1 for t in v.hits if t > since) for v in victims]
+        linked = [k > 0 and victims[k - 1].parent is v for k, v in enumerate(victims)]
+        return sharers, linked, sum(1 for t in self.admissions if t > since)
+
+    def evict(self, need_slots: int, victims_out: Optional[List[_Tok]] = None, keep: Optional[set] = None) -> Tuple[int, int]:
         """-> (slots of the pages that became free, tokens dropped)."""
         freed = gone = 0
         while freed < need_slots:
@@ -104,11 +148,14 @@ class CacheOracle:
                 x = stack.pop()
                 if x.child:
                     stack.extend(x.child.values())
-                elif x is not self.root and x.ref == 0 and (victim is None or x.last < victim.last):
+                elif x is not self.root and x.ref == 0 and (keep is None or id(x) not in keep) and \
+                        (victim is None or x.last < victim.last):
                     victim = x
             if victim is None:
                 break
             del victim.parent.child[victim.token]
+            if victims_out is not None:
+                victims_out.append(victim)
             gone += 1
             page = victim.slot // self.p
             self.page_live[page] -= 1

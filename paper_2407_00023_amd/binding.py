@@ -39,6 +39,19 @@ _SIGS = {
     "pa_tree_admit": (_i, [_vp, _vp, C.c_int32, _i64, _vp, C.POINTER(C.c_int32), C.POINTER(_i64)]),
     "pa_tree_release": (_i, [_vp, _i64]),
     "pa_tree_evict": (_i, [_vp, _i64, C.POINTER(_i64), C.POINTER(_i64)]),
+    "pa_tree_set_hit_window": (_i, [_vp, _i64]),
+    "pa_tree_evict_plan": (_i, [_vp, _i64, _i64, _i64, _vp, _vp, C.POINTER(_i64), C.POINTER(_i64)]),
+    "pa_tree_evict_for": (_i, [_vp, _vp, C.c_int32, C.POINTER(_i64), C.POINTER(_i64)]),
+    "pa_tree_evict_plan_for": (_i, [_vp, _vp, C.c_int32, _i64, _i64, _vp, _vp, C.POINTER(_i64), C.POINTER(_i64)]),
+    "pa_priority_group": (_i, [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
+    "pa_priority_select": (_i, [_vp, _vp, _i64, C.c_int32, _i64, _vp, C.POINTER(_i64)]),
+    "pa_e2_load_cost": (_i, [_vp, _vp, _i64, C.c_double, _vp, _vp, _i64, _i64, C.c_int32] + [C.POINTER(C.c_double)] * 3),
+    "pa_e2_schedule": (_i, [C.c_int32, C.c_int32, _vp, _vp, _vp, C.c_double, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "pa_history_create": (_i, [C.c_int32, _i64, _vp, C.POINTER(_vp)]),
+    "pa_history_destroy": (_i, [_vp]),
+    "pa_history_assign": (_i, [_vp, C.c_int32, _i64, C.c_int32]),
+    "pa_history_complete": (_i, [_vp, C.c_int32, _i64, C.c_int32]),
+    "pa_history_gpu_load": (_i, [_vp, C.c_int32, _i64, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(_i64), C.POINTER(C.c_double)]),
     "pa_kv_pool_bytes": (_sz, [_i64, _i, _i, _i, _i]),
     "pa_extend_workspace_bytes": (_sz, [_i, _i64, _i64, _i, _i, _i, _i]),
     "pa_match_prefixes": (_i, [_vp, _vp, _vp, _i, _vp, _vp, _vp]),
@@ -132,6 +145,37 @@ class Tree:
         _check(_lib.pa_tree_evict(self._h, need_slots, C.byref(freed), C.byref(gone)), "pa_tree_evict")
         return int(freed.value), int(gone.value)
 
+    def set_hit_window(self, window: int) -> None:
+        _check(_lib.pa_tree_set_hit_window(self._h, window), "pa_tree_set_hit_window")
+
+    def evict_plan(self, need_slots: int, since: int, cap: int = 4096):
+        """-> (tokens each victim node would lose, admissions after `since` through each, admissions after `since`)."""
+        toks = torch.zeros(cap, dtype=torch.int32)
+        shr = torch.zeros(cap, dtype=torch.int32)
+        n, nreq = _i64(0), _i64(0)
+        _check(_lib.pa_tree_evict_plan(self._h, need_slots, since, cap, _ptr(toks), _ptr(shr), C.byref(n), C.byref(nreq)),
+               "pa_tree_evict_plan")
+        k = int(n.value)
+        return toks[:k].clone(), shr[:k].clone(), int(nreq.value)
+
+    def evict_for(self, tokens):
+        """Make room for this prompt without touching its cached part -> (slots freed, tokens dropped)."""
+        t = _host_i32(tokens)
+        freed, gone = _i64(0), _i64(0)
+        _check(_lib.pa_tree_evict_for(self._h, _ptr(t), t.numel(), C.byref(freed), C.byref(gone)), "pa_tree_evict_for")
+        return int(freed.value), int(gone.value)
+
+    def evict_plan_for(self, tokens, since: int, cap: int = 4096):
+        """What evict_for(tokens) would drop -> (tokens per node, sharers per node, admissions after `since`)."""
+        t = _host_i32(tokens)
+        toks = torch.zeros(cap, dtype=torch.int32)
+        shr = torch.zeros(cap, dtype=torch.int32)
+        n, nreq = _i64(0), _i64(0)
+        _check(_lib.pa_tree_evict_plan_for(self._h, _ptr(t), t.numel(), since, cap, _ptr(toks), _ptr(shr), C.byref(n),
+                                           C.byref(nreq)), "pa_tree_evict_plan_for")
+        k = int(n.value)
+        return toks[:k].clone(), shr[:k].clone(), int(nreq.value)
+
     def stats(self) -> Tuple[int, int]:
         a, b = _i64(0), _i64(0)
         _check(_lib.pa_tree_stats(self._h, C.byref(a), C.byref(b)), "pa_tree_stats")
@@ -140,6 +184,92 @@ class Tree:
     def close(self):
         if getattr(self, "_h", None) and _lib is not None:  # (module globals may be gone at interpreter exit)
             _lib.pa_tree_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+
+EXPLOIT, EXPLORE_DECODE, EXPLORE_COST = 0, 1, 2
+
+
+class CostModel(C.Structure):
+    """pa_cost_model: PrefillTime(n) = prefill_per_token * n + prefill_base (n > 0), DecodeTime likewise."""
+    _fields_ = [("prefill_per_token", C.c_double), ("prefill_base", C.c_double), ("decode_per_token", C.c_double),
+                ("decode_base", C.c_double), ("default_output_len", C.c_double)]
+
+
+def _host_i32(x) -> torch.Tensor:
+    t = torch.as_tensor(x, dtype=torch.int32).contiguous()
+    if t.is_cuda or t.dim() != 1:
+        raise TypeError("expected a host int32 vector")
+    return t
+
+
+def priority_group(cached_len: int, prompt_len: int, P: int) -> int:
+    g = C.c_int32(0)
+    _check(_lib.pa_priority_group(cached_len, prompt_len, P, C.byref(g)), "pa_priority_group")
+    return int(g.value)
+
+
+def priority_select(cached_len, prompt_len, P: int, n_pick: int) -> torch.Tensor:
+    """-> queue indices of the next batch (int32 host tensor), higher groups first."""
+    c, n = _host_i32(cached_len), _host_i32(prompt_len)
+    if c.numel() != n.numel():
+        raise ValueError("cached_len and prompt_len differ in length")
+    picked = torch.zeros(max(0, min(n_pick, c.numel())), dtype=torch.int32)
+    k = _i64(0)
+    _check(_lib.pa_priority_select(_ptr(c), _ptr(n), c.numel(), P, n_pick, _ptr(picked), C.byref(k)), "pa_priority_select")
+    return picked[:int(k.value)]
+
+
+def e2_load_cost(model: CostModel, hist_missed_len, avg_output_len: float, evict_tokens, evict_sharers,
+                 n_requests: int, missed_len_k: int) -> Tuple[float, float, float]:
+    """-> (L, M, P) of Algorithm 2."""
+    h, et, es = _host_i32(hist_missed_len), _host_i32(evict_tokens), _host_i32(evict_sharers)
+    if et.numel() != es.numel():
+        raise ValueError("evict_tokens and evict_sharers differ in length")
+    L, M, P = C.c_double(0), C.c_double(0), C.c_double(0)
+    _check(_lib.pa_e2_load_cost(C.byref(model), _ptr(h), h.numel(), avg_output_len, _ptr(et), _ptr(es), et.numel(),
+                                n_requests, missed_len_k, C.byref(L), C.byref(M), C.byref(P)), "pa_e2_load_cost")
+    return float(L.value), float(M.value), float(P.value)
+
+
+def e2_schedule(prompt_len: int, cached_len: int, on_longest_node, cost, decode_ratio, imbal_r: float) -> Tuple[int, int]:
+    """-> (gpu, mode) of Algorithm 1."""
+    f = torch.as_tensor(on_longest_node).to(torch.uint8).contiguous()
+    c = torch.as_tensor(cost, dtype=torch.float64).contiguous()
+    r = torch.as_tensor(decode_ratio, dtype=torch.float64).contiguous()
+    if not (f.numel() == c.numel() == r.numel()):
+        raise ValueError("per-GPU arrays differ in length")
+    gpu, mode = C.c_int32(-1), C.c_int32(-1)
+    _check(_lib.pa_e2_schedule(prompt_len, cached_len, _ptr(f), _ptr(c), _ptr(r), imbal_r, c.numel(), C.byref(gpu),
+                               C.byref(mode)), "pa_e2_schedule")
+    return int(gpu.value), int(mode.value)
+
+
+class History:
+    """Owner of a pa_history handle (per-GPU request history over the window H)."""
+
+    def __init__(self, n_gpus: int, window: int, model: CostModel):
+        h = C.c_void_p()
+        _check(_lib.pa_history_create(n_gpus, window, C.byref(model), C.byref(h)), "pa_history_create")
+        self._h = h
+
+    def assign(self, gpu: int, now: int, missed_len: int) -> None:
+        _check(_lib.pa_history_assign(self._h, gpu, now, missed_len), "pa_history_assign")
+
+    def complete(self, gpu: int, now: int, output_len: int) -> None:
+        _check(_lib.pa_history_complete(self._h, gpu, now, output_len), "pa_history_complete")
+
+    def gpu_load(self, gpu: int, now: int) -> Tuple[float, float, int, float]:
+        """-> (L, decode ratio, requests in the window, average output length)."""
+        L, r, n, a = C.c_double(0), C.c_double(0), _i64(0), C.c_double(0)
+        _check(_lib.pa_history_gpu_load(self._h, gpu, now, C.byref(L), C.byref(r), C.byref(n), C.byref(a)), "pa_history_gpu_load")
+        return float(L.value), float(r.value), int(n.value), float(a.value)
+
+    def close(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.pa_history_destroy(self._h)
             self._h = None
 
     __del__ = close

@@ -7,6 +7,7 @@
 // sequence that matches nothing becomes a new tree (here a child of an empty root).
 #include <algorithm>
 #include <cstring>
+#include <deque>
 #include <mutex>
 #include <string>
 #include <unordered_map>
@@ -35,6 +36,7 @@ struct Node {
     int32_t parent = -1;        // -1: the root, or a node that was evicted whole (its id waits for reuse)
     int32_t ref = 0;            // requests admitted and not yet released whose prompt runs through this node
     int64_t last = 0;           // time of the last admission that ran through this node
+    std::vector<int64_t> hits;  // times of the admissions that ran through this node, increasing
 };
 
 }  // namespace pa
@@ -49,6 +51,8 @@ struct pa_tree {
     std::vector<int32_t> free_pages;  // stack: the back is handed out next
     std::vector<int32_t> page_live;   // cached tokens per page
     int64_t clock = INT64_MIN;        // time of the last admission
+    int64_t hit_window = 0;           // admission times older than clock - hit_window are forgotten (0: none is)
+    std::deque<int64_t> admissions;   // times of the admissions, increasing
     // device mirror
     bool uploaded = false;
     int device = -1;
@@ -94,6 +98,7 @@ static int32_t split_node(pa_tree* t, int32_t c, int32_t k) {
     head.parent = tail.parent;
     head.ref = tail.ref;
     head.last = tail.last;
+    head.hits = tail.hits;
     tail.tok.erase(tail.tok.begin(), tail.tok.begin() + k);
     tail.slot.erase(tail.slot.begin(), tail.slot.begin() + k);
     tail.parent = h;
@@ -234,10 +239,18 @@ extern "C" int pa_tree_admit(pa_tree* tree, const int32_t* tokens, int32_t n, in
             tree->n_tokens += rem;
             cur = lid;
         }
+        const bool forget = tree->hit_window > 0 && now > INT64_MIN + tree->hit_window;
+        const int64_t horizon = forget ? now - tree->hit_window : INT64_MIN;  // times <= horizon are forgotten
         for (int32_t x = cur; x > 0; x = nodes[x].parent) {  // pin the path, and it is the most recently used now
             ++nodes[x].ref;
             nodes[x].last = now;
+            auto& hits = nodes[x].hits;
+            if (forget && !hits.empty() && hits.front() <= horizon)
+                hits.erase(hits.begin(), std::upper_bound(hits.begin(), hits.end(), horizon));
+            hits.push_back(now);
         }
+        while (forget && !tree->admissions.empty() && tree->admissions.front() <= horizon) tree->admissions.pop_front();
+        tree->admissions.push_back(now);
         tree->clock = now;
         tree->uploaded = false;
         if (n_cached) *n_cached = pos;
@@ -261,27 +274,106 @@ extern "C" int pa_tree_release(pa_tree* tree, int64_t handle) {
     return PA_OK;
 }
 
-extern "C" int pa_tree_evict(pa_tree* tree, int64_t need_slots, int64_t* freed_slots, int64_t* evicted_tokens) {
-    PA_REQUIRE(tree != nullptr, "pa_tree_evict: tree is NULL");
-    std::lock_guard<std::mutex> lk(tree->mu);
-    if (tree->page_size == 0) return pa::fail(PA_ESTATE, "pa_tree_evict: no pool attached");
-    auto& nodes = tree->nodes;
+namespace pa {
+
+struct EvictStep {
+    int32_t node;    // a leaf that no admitted request runs through
+    int32_t tokens;  // how many tokens it loses from its tail (all of them: the node goes)
+};
+
+// The eviction order: the least recently used leaf that no admitted request runs through goes first, from its
+// tail, token by token, until enough whole pages are free: part of a node if a part is enough.  A parent whose
+// children are all gone is a leaf in turn.  (Admission times are distinct, and an admission touches one path, so
+// no two leaves share a time.)  Reads the tree only; pa_tree_evict applies the steps, pa_tree_evict_plan reports them.
+// keep (may be NULL): node -> number of leading tokens that must stay (the cached part of a prompt about to be admitted).
+static void plan_eviction(const pa_tree* tree, int64_t need_slots, const std::unordered_map<int32_t, int32_t>* keep,
+                          std::vector<EvictStep>& steps, int64_t& freed) {
+    const auto& nodes = tree->nodes;
     const int32_t p = tree->page_size;
-    int64_t freed = 0, gone = 0;
+    const int32_t nn = static_cast<int32_t>(nodes.size());
+    std::vector<int32_t> kids(nn, 0);
+    std::vector<char> gone(nn, 0);
+    for (int32_t i = 0; i < nn; ++i) kids[i] = static_cast<int32_t>(nodes[i].child.size());
+    std::unordered_map<int32_t, int32_t> live;  // page -> cached tokens left, for the pages touched so far
+    int32_t done_partly = -1;                   // the one node of `keep` whose tail has been taken already
+    freed = 0;
     while (freed < need_slots) {
-        // least recently used leaf that no admitted request runs through (admission times are distinct, and an
-        // admission touches one path, so no two leaves share a time)
         int32_t victim = -1;
-        for (int32_t i = 1; i < static_cast<int32_t>(nodes.size()); ++i) {
-            const pa::Node& nd = nodes[i];
-            if (nd.tok.empty() || !nd.child.empty() || nd.ref != 0) continue;
+        for (int32_t i = 1; i < nn; ++i) {
+            const Node& nd = nodes[i];
+            if (nd.tok.empty() || gone[i] || kids[i] != 0 || nd.ref != 0) continue;
+            if (keep) {
+                auto kp = keep->find(i);
+                if (kp != keep->end() && (kp->second >= static_cast<int32_t>(nd.tok.size()) || done_partly == i)) continue;
+            }
             if (victim < 0 || nd.last < nodes[victim].last) victim = i;
         }
         if (victim < 0) break;
-        pa::Node& nd = nodes[victim];
+        const Node& nd = nodes[victim];
+        int32_t k = 0;
+        int32_t len = static_cast<int32_t>(nd.tok.size());
+        const int32_t full = len;
+        if (keep) {
+            auto kp = keep->find(victim);
+            if (kp != keep->end()) len -= kp->second;  // only the tail past the part to keep
+        }
+        while (k < len && freed < need_slots) {
+            const int32_t page = nd.slot[full - 1 - k] / p;
+            auto it = live.find(page);
+            if (it == live.end()) it = live.emplace(page, tree->page_live[page]).first;
+            ++k;
+            if (--it->second == 0) freed += p;
+        }
+        steps.push_back({victim, k});
+        if (k == full) {
+            gone[victim] = 1;
+            --kids[nd.parent];
+        } else if (k == len) {
+            done_partly = victim;  // its head is to be kept: it stays a leaf, and has nothing more to give
+        } else {
+            break;  // a node that keeps its head: enough is free
+        }
+    }
+}
+
+}  // namespace pa
+
+namespace pa {
+
+// The cached part of a prompt as "tokens to keep" per node, and the slots its admission still needs.
+static void keep_for_prompt(const pa_tree* tree, const int32_t* tokens, int32_t n,
+                            std::unordered_map<int32_t, int32_t>& keep, int64_t& need_slots) {
+    const auto& nodes = tree->nodes;
+    int32_t cur = 0, pos = 0;
+    while (pos < n) {
+        auto it = nodes[cur].child.find(tokens[pos]);
+        if (it == nodes[cur].child.end()) break;
+        const int32_t c = it->second;
+        const int32_t elen = static_cast<int32_t>(nodes[c].tok.size());
+        const int32_t lim = std::min(elen, n - pos);
+        int32_t k = 1;
+        while (k < lim && nodes[c].tok[k] == tokens[pos + k]) ++k;
+        keep.emplace(c, k);
+        pos += k;
+        if (k < elen) break;
+        cur = c;
+    }
+    const int64_t p = tree->page_size;
+    const int64_t pages = (static_cast<int64_t>(n - pos) + p - 1) / p;
+    need_slots = std::max<int64_t>(0, pages * p - static_cast<int64_t>(tree->free_pages.size()) * p);
+}
+
+static int evict_locked(pa_tree* tree, int64_t need_slots, const std::unordered_map<int32_t, int32_t>* keep,
+                        int64_t* freed_slots, int64_t* evicted_tokens) {
+    auto& nodes = tree->nodes;
+    const int32_t p = tree->page_size;
+    int64_t freed = 0, planned = 0, gone = 0;
+    std::vector<EvictStep> steps;
+    plan_eviction(tree, need_slots, keep, steps, planned);
+    for (const EvictStep& st : steps) {
+        Node& nd = nodes[st.node];
         const int32_t first_tok = nd.tok.front();
-        // from the tail, token by token, until enough whole pages are free: part of a node if a part is enough
-        while (!nd.tok.empty() && freed < need_slots) {
+        for (int32_t k = 0; k < st.tokens; ++k) {
             const int32_t page = nd.slot.back() / p;
             nd.tok.pop_back();
             nd.slot.pop_back();
@@ -294,13 +386,108 @@ extern "C" int pa_tree_evict(pa_tree* tree, int64_t need_slots, int64_t* freed_s
         if (nd.tok.empty()) {
             nodes[nd.parent].child.erase(first_tok);
             nd.parent = -1;
-            tree->free_nodes.push_back(victim);
+            nd.hits.clear();
+            tree->free_nodes.push_back(st.node);
         }
     }
     tree->n_tokens -= gone;
     if (gone) tree->uploaded = false;
     if (freed_slots) *freed_slots = freed;
     if (evicted_tokens) *evicted_tokens = gone;
+    return PA_OK;
+}
+
+static int plan_locked(const pa_tree* tree, int64_t need_slots, const std::unordered_map<int32_t, int32_t>* keep,
+                       int64_t since, int64_t cap, int32_t* node_tokens, int32_t* node_sharers, int64_t* n_nodes,
+                       int64_t* n_requests) {
+    std::vector<EvictStep> steps;
+    int64_t freed = 0;
+    plan_eviction(tree, need_slots, keep, steps, freed);
+    // A node that goes whole, followed at once by its parent with the same count of sharers, is one entry: where
+    // the tree happens to be cut along a path that the same requests used does not show in the result.
+    std::vector<std::pair<int32_t, int32_t>> runs;  // (tokens, sharers)
+    for (size_t k = 0; k < steps.size(); ++k) {
+        const auto& hits = tree->nodes[steps[k].node].hits;
+        const int32_t sharers = static_cast<int32_t>(hits.end() - std::upper_bound(hits.begin(), hits.end(), since));
+        if (k > 0 && tree->nodes[steps[k - 1].node].parent == steps[k].node && runs.back().second == sharers)
+            runs.back().first += steps[k].tokens;
+        else
+            runs.emplace_back(steps[k].tokens, sharers);
+    }
+    *n_nodes = static_cast<int64_t>(runs.size());
+    if (n_requests)
+        *n_requests = tree->admissions.end() - std::upper_bound(tree->admissions.begin(), tree->admissions.end(), since);
+    if (static_cast<int64_t>(runs.size()) > cap)
+        return fail(PA_ENOMEM, "pa_tree_evict_plan: %zu nodes, room for %lld", runs.size(), static_cast<long long>(cap));
+    for (size_t k = 0; k < runs.size(); ++k) {
+        node_tokens[k] = runs[k].first;
+        node_sharers[k] = runs[k].second;
+    }
+    return PA_OK;
+}
+
+}  // namespace pa
+
+extern "C" int pa_tree_evict(pa_tree* tree, int64_t need_slots, int64_t* freed_slots, int64_t* evicted_tokens) {
+    PA_REQUIRE(tree != nullptr, "pa_tree_evict: tree is NULL");
+    std::lock_guard<std::mutex> lk(tree->mu);
+    if (tree->page_size == 0) return pa::fail(PA_ESTATE, "pa_tree_evict: no pool attached");
+    try {
+        return pa::evict_locked(tree, need_slots, nullptr, freed_slots, evicted_tokens);
+    } catch (const std::bad_alloc&) {
+        return pa::fail(PA_ENOMEM, "pa_tree_evict: out of host memory");
+    }
+}
+
+extern "C" int pa_tree_evict_for(pa_tree* tree, const int32_t* tokens, int32_t n, int64_t* freed_slots,
+                                 int64_t* evicted_tokens) {
+    PA_REQUIRE(tree != nullptr && tokens != nullptr && n >= 1, "pa_tree_evict_for: bad argument");
+    std::lock_guard<std::mutex> lk(tree->mu);
+    if (tree->page_size == 0) return pa::fail(PA_ESTATE, "pa_tree_evict_for: no pool attached");
+    try {
+        std::unordered_map<int32_t, int32_t> keep;
+        int64_t need = 0;
+        pa::keep_for_prompt(tree, tokens, n, keep, need);
+        return pa::evict_locked(tree, need, &keep, freed_slots, evicted_tokens);
+    } catch (const std::bad_alloc&) {
+        return pa::fail(PA_ENOMEM, "pa_tree_evict_for: out of host memory");
+    }
+}
+
+extern "C" int pa_tree_evict_plan(const pa_tree* tree, int64_t need_slots, int64_t since, int64_t cap,
+                                  int32_t* node_tokens, int32_t* node_sharers, int64_t* n_nodes, int64_t* n_requests) {
+    PA_REQUIRE(tree != nullptr && n_nodes != nullptr, "pa_tree_evict_plan: NULL argument");
+    PA_REQUIRE(cap >= 0 && (cap == 0 || (node_tokens && node_sharers)), "pa_tree_evict_plan: bad output arrays");
+    std::lock_guard<std::mutex> lk(const_cast<pa_tree*>(tree)->mu);
+    if (tree->page_size == 0) return pa::fail(PA_ESTATE, "pa_tree_evict_plan: no pool attached");
+    try {
+        return pa::plan_locked(tree, need_slots, nullptr, since, cap, node_tokens, node_sharers, n_nodes, n_requests);
+    } catch (const std::bad_alloc&) {
+        return pa::fail(PA_ENOMEM, "pa_tree_evict_plan: out of host memory");
+    }
+}
+
+extern "C" int pa_tree_evict_plan_for(const pa_tree* tree, const int32_t* tokens, int32_t n, int64_t since, int64_t cap,
+                                      int32_t* node_tokens, int32_t* node_sharers, int64_t* n_nodes,
+                                      int64_t* n_requests) {
+    PA_REQUIRE(tree != nullptr && n_nodes != nullptr && tokens != nullptr && n >= 1, "pa_tree_evict_plan_for: bad argument");
+    PA_REQUIRE(cap >= 0 && (cap == 0 || (node_tokens && node_sharers)), "pa_tree_evict_plan_for: bad output arrays");
+    std::lock_guard<std::mutex> lk(const_cast<pa_tree*>(tree)->mu);
+    if (tree->page_size == 0) return pa::fail(PA_ESTATE, "pa_tree_evict_plan_for: no pool attached");
+    try {
+        std::unordered_map<int32_t, int32_t> keep;
+        int64_t need = 0;
+        pa::keep_for_prompt(tree, tokens, n, keep, need);
+        return pa::plan_locked(tree, need, &keep, since, cap, node_tokens, node_sharers, n_nodes, n_requests);
+    } catch (const std::bad_alloc&) {
+        return pa::fail(PA_ENOMEM, "pa_tree_evict_plan_for: out of host memory");
+    }
+}
+
+extern "C" int pa_tree_set_hit_window(pa_tree* tree, int64_t window) {
+    PA_REQUIRE(tree != nullptr && window >= 0, "pa_tree_set_hit_window: bad argument");
+    std::lock_guard<std::mutex> lk(tree->mu);
+    tree->hit_window = window;
     return PA_OK;
 }
 
