@@ -29,8 +29,8 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3
 # HBM bytes per launch of the extend-attention kernel, measured with rocprofv3 --pmc: FETCH_SIZE x 1.984 +
 # WRITE_SIZE x 1.000 (KiB), the factors being what the same counters read for append_kv, a plain copy of
 # known size; the runs are summarised in profiles/extend_attention_<workload>.md.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"tool_use": 284_058_423, "agent_tree": 3_156_072_806, "long_doc_qa": 1_474_727_155,
-                          "video_qa": 403_564_874}
+MEASURED_TRAFFIC_BYTES = {"tool_use": 248_639_878, "agent_tree": 2_871_238_233, "long_doc_qa": 1_311_929_340,
+                          "video_qa": 538_494_213, "programming": 289_392_562}
 
 
 def algorithmic_work(wl, prefix_len):
@@ -145,7 +145,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="tool_use", choices=["tiny_fp32", "tool_use", "long_doc_qa", "agent_tree", "video_qa"])
+    ap.add_argument("--workload", default="tool_use", choices=["tiny_fp32", "tool_use", "long_doc_qa", "agent_tree", "video_qa", "programming"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the cold-cache and the scaled-matcher measurements")
     ap.add_argument("--only", default="", help="time only one call of the path: match | extend | append (for profiling)")
@@ -232,7 +232,7 @@ def main():
     torch.cuda.synchronize()
     pa.profile_enable(False)
     kern = {}
-    for name in ("match_prefixes", "extend_tiles", "extend_attention", "extend_merge", "extend_attention_f32", "append_kv"):
+    for name in ("match_prefixes", "extend_plan", "extend_attention", "extend_merge", "extend_attention_f32", "append_kv"):
         ms, n = pa.profile_read(name)
         if n:
             kern[name] = {"avg_us": ms / n * 1e3, "launches_per_step": n / args.steps}

@@ -219,6 +219,9 @@ size_t pa_kv_pool_bytes(int64_t num_slots, int Hkv, int D, int dtype, int page_s
 
 /* Bytes of device workspace pa_extend_attention needs for any batch with at most B
  * requests, T extend tokens in total and prefix_len[r] + ext_len[r] <= max_kv_len.
+ * It holds the work list of the launch and the partial results of row tiles whose key range is
+ * split over several workgroups; with bf16 at serving sizes the bound on the latter dominates
+ * (about 200 MB for 8 KV heads of 128: 2 x 3 parts per workgroup slot, each 128 rows of fp32).
  * Returns 0 for invalid arguments. */
 size_t pa_extend_workspace_bytes(int B, int64_t T, int64_t max_kv_len, int Hq, int Hkv, int D, int dtype);
 
@@ -289,7 +292,7 @@ int pa_gather_kv(const void* kv_pool, const int32_t* slots, int64_t n, int Hkv, 
  * first use, so do not enable it under stream capture).  pa_profile_enable(1) clears the
  * records and starts recording, pa_profile_enable(0) stops.  pa_profile_read waits for the
  * recorded events and returns the summed device time (ms) and the number of launches of one
- * kernel, named "match_prefixes", "extend_tiles", "extend_attention", "extend_merge",
+ * kernel, named "match_prefixes", "extend_plan", "extend_attention", "extend_merge",
  * "extend_attention_f32", "append_kv" or "gather_kv".  At most 65536 launches are recorded.
  * --------------------------------------------------------------------------------- */
 int pa_profile_enable(int on);

@@ -9,8 +9,9 @@
 // rows into one row axis rho = i * G + (h mod G), so a K/V tile is read once per KV head.
 // A workgroup of NW waves owns 32 * NW packed rows of one (request, KV head) and walks the
 // key axis in tiles of kKT = 64 tokens: prefix positions first, then the extend tokens
-// (the same loop; only the row address differs).  Optionally the key axis is cut into
-// `nsplit` chunks handled by different workgroups, merged by a second kernel.
+// (the same loop; only the row address differs).  A planning kernel (extend_plan_kernel, one
+// workgroup) builds the list of work items per launch - row tile x part of its key range - from
+// the lengths on the device; the parts of a split tile are merged by a third kernel.
 //
 // Data movement.  K and V tiles go from global memory straight into LDS (16 bytes per
 // lane, no register staging), one tile ahead of the arithmetic, into a ring of LDS
@@ -54,8 +55,13 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kKT = 64;                  // key tokens per tile
 constexpr int kStages = 2;               // LDS ring: one tile being read, one being filled
-constexpr int kTargetWorkgroups = 1024;  // split the key axis until about this many workgroups exist
-constexpr int kMinChunk = 512;           // never split below this many keys per chunk
+constexpr int kWgSlots = 512;            // workgroups resident at once: two on each of the 256 compute units
+constexpr int kRounds = 3;               // the plan aims at about this many work items per workgroup slot
+constexpr int kMinChunkTiles = 8;        // never split below this many key tiles (512 keys) per part
+constexpr int kItemOverhead = 4;         // fixed cost of a work item, in key tiles (its prologue and epilogue)
+constexpr int kMaxParts = 64;            // parts of one row tile at most
+constexpr int kSortMax = 1024;           // up to this many requests are ordered (and their lengths staged in LDS)
+constexpr int kTileLds = 3072;           // up to this many row tiles the planner keeps in LDS between its passes
 constexpr float kRescaleThreshold = 8.f; // log2 units: the running maximum may lag the true one by this much
 // The steady-state tiles (fast_run_*.inc) never move the running maximum: a run is left, for the general tile, when
 // the probabilities of one lane and key block sum to more than 2^40.  The exponent range of fp32 and bf16 leaves that
@@ -65,13 +71,22 @@ struct ExtendPlan {
     int nw;          // waves per workgroup
     int rb;          // blocks of 32 packed rows per wave; a row tile has 32 * rb * nw packed rows
     int tiles_cap;   // upper bound on the number of (request, row tile) pairs
-    int nsplit;      // chunks of the key axis
-    int chunk;       // keys per chunk (multiple of kKT)
-    size_t off_req, off_row0, off_part_o, off_part_ml, total;
+    int items_cap;   // upper bound on the number of work items (row tile x part of its key range)
+    int parts_cap;   // upper bound on the number of items that belong to split tiles (they write partial results)
+    int slots;       // workgroup slots per KV head
+    size_t off_order, off_tile, off_item, off_split, off_part_o, off_part_ml, total;
 };
 
 static inline size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
 
+// Work list of one launch.  A row tile = up to 128 packed query rows (row = (extend token, query head of the group))
+// of one request; a work item = a row tile x a contiguous part of its key range; one workgroup per (item, KV head).
+// Workgroups cost about the same per key tile whatever the number of their rows, and the hardware starts them in
+// index order as slots fall free, so the list is built for an even finish: requests with the same prefix together,
+// the longest first, every tile cut into parts of about 1 / kRounds of a slot's share of the whole work.  (Cutting
+// the end of the list finer still evens the finish further and was measured to gain nothing: while every slot is
+// busy the chip is at its power limit, and the extra parts cost a merge.)  The bounds below follow from that rule
+// (see extend_plan_kernel).
 static ExtendPlan make_plan(int B, int64_t T, int64_t max_kv_len, int Hq, int Hkv, int D) {
     ExtendPlan p{};
     const int G = Hq / Hkv;
@@ -80,65 +95,275 @@ static ExtendPlan make_plan(int B, int64_t T, int64_t max_kv_len, int Hq, int Hk
     const int mt = 32 * p.rb * p.nw;
     const int64_t est = (T * G + mt - 1) / mt;
     p.tiles_cap = static_cast<int>(est + B);
-    int64_t want = (kTargetWorkgroups + est * Hkv - 1) / (est * Hkv > 0 ? est * Hkv : 1);
-    int64_t max_split = (max_kv_len + kMinChunk - 1) / kMinChunk;
-    if (max_split < 1) max_split = 1;
-    if (want > max_split) want = max_split;
-    if (want < 1) want = 1;
-    if (want > 64) want = 64;
-    p.nsplit = static_cast<int>(want);
-    int64_t chunk = (max_kv_len + p.nsplit - 1) / p.nsplit;
-    chunk = (chunk + kKT - 1) / kKT * kKT;
-    if (chunk < kKT) chunk = kKT;
-    p.chunk = static_cast<int>(chunk);
-    p.off_req = 256;
-    p.off_row0 = p.off_req + up256(sizeof(int32_t) * p.tiles_cap);
-    p.off_part_o = p.off_row0 + up256(sizeof(int32_t) * p.tiles_cap);
-    const size_t units = p.nsplit > 1 ? static_cast<size_t>(p.tiles_cap) * p.nsplit * Hkv : 0;
+    p.slots = kWgSlots / Hkv > 0 ? kWgSlots / Hkv : 1;
+    const int64_t by_rule = static_cast<int64_t>(p.slots) * kRounds + 1;                  // sum of (parts - 1) over the tiles
+    const int64_t per_tile = (max_kv_len / kKT) / kMinChunkTiles > 1 ? (max_kv_len / kKT) / kMinChunkTiles : 1;
+    const int64_t by_size = static_cast<int64_t>(p.tiles_cap) * (per_tile < kMaxParts ? per_tile : kMaxParts);
+    p.items_cap = static_cast<int>(p.tiles_cap + (by_rule < by_size ? by_rule : by_size));
+    p.parts_cap = static_cast<int>(2 * by_rule < by_size ? 2 * by_rule : by_size);
+    p.off_order = 256;
+    p.off_tile = p.off_order + up256(sizeof(int32_t) * (B > 0 ? B : 1));
+    p.off_item = p.off_tile + up256(sizeof(int4) * p.tiles_cap);
+    p.off_split = p.off_item + up256(sizeof(int4) * 3 * p.items_cap);
+    p.off_part_o = p.off_split + up256(sizeof(int32_t) * ((p.parts_cap + 1) / 2 + 1));
+    const size_t units = static_cast<size_t>(p.parts_cap) * Hkv;
     p.off_part_ml = p.off_part_o + up256(units * mt * D * sizeof(float));
     p.total = p.off_part_ml + up256(units * mt * 2 * sizeof(float));
     return p;
 }
 
+constexpr int kPlanThreads = 1024;
+
+// Exclusive prefix sums of up to three ints per thread over the workgroup of the planner (kPlanThreads threads):
+// a shuffle scan inside each wave, then the 16 wave totals.  total[] receives the sums.
+template <int N>
+__device__ __forceinline__ void block_scan(int (&v)[N], int (&total)[N], int (*s_w)[kPlanThreads / 64 + 1]) {
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    int x[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        x[i] = v[i];
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int y = __shfl_up(x[i], off);
+            if (lane >= off) x[i] += y;
+        }
+    }
+    __syncthreads();  // s_w may still be read from the call before
+    if (lane == 63)
+#pragma unroll
+        for (int i = 0; i < N; ++i) s_w[i][w] = x[i];
+    __syncthreads();
+    if (tid < N) {
+        int run = 0;
+        for (int k = 0; k < kPlanThreads / 64; ++k) {
+            const int c = s_w[tid][k];
+            s_w[tid][k] = run;
+            run += c;
+        }
+        s_w[tid][kPlanThreads / 64] = run;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        v[i] = x[i] - v[i] + s_w[i][w];
+        total[i] = s_w[i][kPlanThreads / 64];
+    }
+}
+
 // ---------------------------------------------------------------------------------------
-// Row-tile table: tile t -> (request, first packed row).  One workgroup; block-wide scan.
+// The work list.  One workgroup.  hdr[0] = row tiles, hdr[1] = work items, hdr[2] = split tiles (listed in
+// split_tiles, at most parts_cap / 2 of them).
+//   tile_tab[t] = (parts, index of its first partial result or -1, request, first packed row)
+//   item_tab[3 i ..] = (request, first packed row, first key, end key), (partial index or -1: writes the output,
+//                      prefix length, extend length, first extend token), (first slot-list entry, tile, 0, 0)
+// Everything a workgroup of the attention kernel needs sits in its item record: one dependent load, not four.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void extend_tiles_kernel(const int32_t* __restrict__ ext_len, int B, int G, int mt,
-                                                          int tiles_cap, int32_t* __restrict__ n_tiles,
-                                                          int32_t* __restrict__ tile_req,
-                                                          int32_t* __restrict__ tile_row0) {
-    __shared__ int s_scan[256];
+__global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
+    const int32_t* __restrict__ prefix_len, const int32_t* __restrict__ ext_len, const int32_t* __restrict__ ext_offsets,
+    const int32_t* __restrict__ slot_offsets, const int32_t* __restrict__ slot_idx, int B, int G, int mt, int tiles_cap,
+    int items_cap, int parts_cap, int slots, int32_t* __restrict__ hdr, int32_t* __restrict__ order,
+    int4* __restrict__ tile_tab, int4* __restrict__ item_tab, int32_t* __restrict__ split_tiles) {
+    __shared__ int s_w[3][kPlanThreads / 64 + 1];
+    __shared__ int s_P[kSortMax], s_E[kSortMax];  // prefix and extend length of the request (staged when B <= kSortMax)
+    __shared__ int s_key[kSortMax];               // keys of the request, prefix + extend length (-1: nothing to do)
+    __shared__ int s_grp[kSortMax];               // slot of its last prefix token: equal for requests with the same prefix
+    __shared__ int s_gkey[kSortMax];              // the most keys of any request of its group
+    __shared__ int s_order[kSortMax];             // position in the list -> request
+    __shared__ int s_e0[kSortMax], s_so[kSortMax]; // first extend token and first slot-list entry of the request
+    __shared__ int s_trow[kTileLds], s_tkv[kTileLds];  // (request << 16 | row tile of the request), end of the key range
     __shared__ int s_carry;
     const int tid = threadIdx.x;
+    const bool staged = B <= kSortMax;
+    auto P_of = [&](int r) { return staged ? s_P[r] : prefix_len[r]; };
+    auto E_of = [&](int r) { return staged ? s_E[r] : ext_len[r]; };
+    // Requests that share their whole prefix become neighbours (their workgroups then run at the same time and the
+    // shared keys are served from L2); groups with the most keys first, inside a group the request with the most
+    // keys first.  Beyond kSortMax requests the order stays as given.
+    if (staged) {
+        for (int r = tid; r < B; r += kPlanThreads) {
+            const int P = prefix_len[r], so = slot_offsets[r];
+            const int E = ext_len[r];
+            s_P[r] = P;
+            s_E[r] = E;
+            s_key[r] = E > 0 ? P + E : -1;
+            s_e0[r] = ext_offsets[r];
+            s_so[r] = so;
+            s_grp[r] = P > 0 ? slot_idx[so + P - 1] : -1 - r;
+        }
+        __syncthreads();
+        // tpr threads per request r, each over its share of the other requests q
+        const int tpr = max(1, kPlanThreads / B);
+        const int r = tid / tpr, q_first = tid % tpr;
+        const bool on = r < B;
+        const int k = on ? s_key[r] : 0, grp = on ? s_grp[r] : 0;
+        if (on && q_first == 0) {
+            s_gkey[r] = k;
+            s_order[r] = 0;  // (the rank of r is summed up here first)
+        }
+        __syncthreads();
+        if (on) {
+            int gk = -1;
+            for (int q = q_first; q < B; q += tpr) {
+                const int kq = s_key[q], gq = s_grp[q];
+                gk = max(gk, gq == grp ? kq : -1);
+            }
+            atomicMax(&s_gkey[r], gk);
+        }
+        __syncthreads();
+        int rank = 0;
+        if (on) {
+            const int gk = s_gkey[r];
+            for (int q = q_first; q < B; q += tpr) {
+                const int kq = s_key[q], gq = s_grp[q], gkq = s_gkey[q];
+                // (group keys, group, keys, index) of q sorts before that of r: more keys first, lower ids first
+                rank += (gkq > gk) | ((gkq == gk) & ((gq < grp) | ((gq == grp) & ((kq > k) | ((kq == k) & (q < r))))));
+            }
+            atomicAdd(&s_order[r], rank);
+        }
+        __syncthreads();
+        if (on && q_first == 0) rank = s_order[r];
+        __syncthreads();
+        if (on && q_first == 0) s_order[rank] = r;
+    } else {
+        for (int r = tid; r < B; r += kPlanThreads) order[r] = r;
+    }
     if (tid == 0) s_carry = 0;
     __syncthreads();
-    for (int base = 0; base < B; base += 256) {
-        const int r = base + tid;
+    // With few requests and few row tiles (row tiles of a request < 65536, staged lengths) the passes below work on
+    // LDS copies; otherwise on the table in global memory.
+    const bool in_lds = staged && tiles_cap <= kTileLds;
+    // row tiles: a request's tiles are neighbours (they read the same keys), its last rows - the most keys - first
+    if (in_lds) {
+        // B <= kPlanThreads here: the first tile of every list position, then one thread per tile
         int cnt = 0;
-        if (r < B) {
-            const int e = ext_len[r];
+        if (tid < B) {
+            const int e = s_E[s_order[tid]];
             cnt = e > 0 ? (e * G + mt - 1) / mt : 0;
         }
-        s_scan[tid] = cnt;
+        int v[1] = {cnt}, total[1];
+        block_scan<1>(v, total, s_w);
+        if (tid < B) s_gkey[tid] = v[0];  // (s_gkey is free again)
         __syncthreads();
-        for (int off = 1; off < 256; off <<= 1) {
-            const int v = tid >= off ? s_scan[tid - off] : 0;
-            __syncthreads();
-            s_scan[tid] += v;
-            __syncthreads();
-        }
-        const int start = s_carry + s_scan[tid] - cnt;
-        for (int k = 0; k < cnt; ++k) {
-            if (start + k < tiles_cap) {
-                tile_req[start + k] = r;
-                tile_row0[start + k] = k * mt;
+        const int nt = min(total[0], tiles_cap);
+        for (int t = tid; t < nt; t += kPlanThreads) {
+            int lo = 0, hi = B;  // the last position whose first tile is <= t
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (s_gkey[mid] <= t) lo = mid; else hi = mid;
             }
+            const int r = s_order[lo];
+            const int c = (s_E[r] * G + mt - 1) / mt;
+            s_trow[t] = (r << 16) | (c - 1 - (t - s_gkey[lo]));
         }
+        if (tid == 0) s_carry = total[0];
         __syncthreads();
-        if (tid == 255) s_carry += s_scan[255];
-        __syncthreads();
+    } else {
+        for (int base = 0; base < B; base += kPlanThreads) {
+            const int k = base + tid;
+            int cnt = 0, r = 0;
+            if (k < B) {
+                r = staged ? s_order[k] : order[k];
+                const int e = E_of(r);
+                cnt = e > 0 ? (e * G + mt - 1) / mt : 0;
+            }
+            int v[1] = {cnt}, total[1];
+            block_scan<1>(v, total, s_w);
+            const int start = s_carry + v[0];
+            for (int j = 0; j < cnt; ++j)
+                if (start + j < tiles_cap) tile_tab[start + j] = make_int4(1, -1, r, (cnt - 1 - j) * mt);
+            __syncthreads();
+            if (tid == 0) s_carry += total[0];
+            __syncthreads();
+        }
     }
-    if (tid == 0) *n_tiles = min(s_carry, tiles_cap);
+    const int n_tiles = min(s_carry, tiles_cap);
+    // cost of a tile = its key tiles + a fixed overhead; thread i owns tiles [i * per, (i + 1) * per)
+    const int per = (n_tiles + kPlanThreads - 1) / kPlanThreads;
+    const int t_lo = min(n_tiles, tid * per), t_hi = min(n_tiles, t_lo + per);
+    int my_cost = 0;
+    for (int t = t_lo; t < t_hi; ++t) {  // the end of the tile's key range is kept for the passes below
+        int r, row0;
+        if (in_lds) {
+            r = s_trow[t] >> 16;
+            row0 = (s_trow[t] & 0xFFFF) * mt;
+        } else {
+            const int4 tt = tile_tab[t];
+            r = tt.z;
+            row0 = tt.w;
+        }
+        const int rows_here = min(mt, E_of(r) * G - row0);
+        const int kv_end = P_of(r) + (row0 + rows_here - 1) / G + 1;
+        if (in_lds)
+            s_tkv[t] = kv_end;
+        else
+            tile_tab[t] = make_int4(1, kv_end, r, row0);
+        my_cost += (kv_end + kKT - 1) / kKT + kItemOverhead;
+    }
+    auto kv_end_of = [&](int t) { return in_lds ? s_tkv[t] : tile_tab[t].y; };
+    int W;
+    {
+        int v[1] = {my_cost}, total[1];
+        block_scan<1>(v, total, s_w);
+        W = total[0];
+    }
+    // parts of a tile: its cost over the target cost of an item, rounded; never below kMinChunkTiles key tiles per
+    // part.  Summed over the tiles, parts - 1 stays below W / target = slots * kRounds (a tile of cost c adds at most
+    // c / target - 1/2), which is what the capacities are sized for.
+    const float target = fmaxf(static_cast<float>(W) / static_cast<float>(slots * kRounds), 1.f);
+    auto parts_of = [&](int K) {
+        int n = static_cast<int>(static_cast<float>(K + kItemOverhead) / target + 0.5f);
+        n = min(min(n, K / kMinChunkTiles), kMaxParts);
+        return max(n, 1);
+    };
+    int my_items = 0, my_parts = 0, my_split = 0;
+    for (int t = t_lo; t < t_hi; ++t) {
+        const int n = parts_of((kv_end_of(t) + kKT - 1) / kKT);
+        my_items += n;
+        my_parts += n > 1 ? n : 0;
+        my_split += n > 1;
+    }
+    int base3[3] = {my_items, my_parts, my_split}, total3[3];
+    block_scan<3>(base3, total3, s_w);
+    int item0 = base3[0], part0 = base3[1], split0 = base3[2];
+    int n_items = total3[0], n_split = total3[2];
+    const bool whole = n_items > items_cap || total3[1] > parts_cap;  // cannot happen by the bound; then nothing is split
+    if (whole) {
+        item0 = t_lo;
+        n_items = n_tiles;
+        n_split = 0;
+    }
+    {
+        for (int t = t_lo; t < t_hi; ++t) {
+            int4 tt;
+            if (in_lds)
+                tt = make_int4(0, s_tkv[t], s_trow[t] >> 16, (s_trow[t] & 0xFFFF) * mt);
+            else
+                tt = tile_tab[t];
+            const int kv_end = tt.y, r = tt.z;
+            const int K = (kv_end + kKT - 1) / kKT;
+            const int n = whole ? 1 : parts_of(K);
+            tile_tab[t] = make_int4(n, n > 1 ? part0 : -1, r, tt.w);
+            if (n > 1) split_tiles[split0++] = t;
+            const int4 rec1 = make_int4(0, P_of(r), E_of(r), staged ? s_e0[r] : ext_offsets[r]);
+            const int slot_off = staged ? s_so[r] : slot_offsets[r];
+            for (int j = 0; j < n; ++j) {
+                const int lo = static_cast<int>(static_cast<int64_t>(K) * j / n) * kKT;
+                const int hi = min(kv_end, static_cast<int>(static_cast<int64_t>(K) * (j + 1) / n) * kKT);
+                int4* rec = item_tab + 3 * static_cast<size_t>(item0 + j);
+                rec[0] = make_int4(r, tt.w, lo, hi);
+                rec[1] = make_int4(n > 1 ? part0 + j : -1, rec1.y, rec1.z, rec1.w);
+                rec[2] = make_int4(slot_off, t, 0, 0);
+            }
+            item0 += n;
+            part0 += n > 1 ? n : 0;
+        }
+    }
+    if (tid == 0) {
+        hdr[0] = n_tiles;
+        hdr[1] = n_items;
+        hdr[2] = n_split;
+    }
 }
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
@@ -147,13 +372,6 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
     f32x2 v = {a, b};
     bf16x2_t r = __builtin_convertvector(v, bf16x2_t);
     return __builtin_bit_cast(uint32_t, r);
-}
-
-// Key range handled by split s of a tile whose visible keys are [0, kv_end).
-__device__ __forceinline__ void split_range(int kv_end, int chunk, int nsplit, int s, int& n_act, int& lo, int& hi) {
-    n_act = min(nsplit, (kv_end + chunk - 1) / chunk);
-    lo = s * chunk;
-    hi = (s == n_act - 1) ? kv_end : min(kv_end, (s + 1) * chunk);
 }
 
 // XOR swizzles of the 16-byte chunks of a K/V row in LDS, chosen so that the two read patterns of the
@@ -230,12 +448,10 @@ template <int D, int NW, int RB>
 __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     const __hip_bfloat16* __restrict__ q_ext, const __hip_bfloat16* __restrict__ k_ext,
     const __hip_bfloat16* __restrict__ v_ext, const __hip_bfloat16* __restrict__ pool,
-    const int32_t* __restrict__ slot_idx, const int32_t* __restrict__ slot_offsets,
-    const int32_t* __restrict__ prefix_len, const int32_t* __restrict__ ext_len,
-    const int32_t* __restrict__ ext_offsets, int Hq, int Hkv, int page_size, int page_shift, int num_slots,
-    int fast_ok, float scale_log2e, __hip_bfloat16* __restrict__ out, const int32_t* __restrict__ n_tiles,
-    const int32_t* __restrict__ tile_req, const int32_t* __restrict__ tile_row0, int nsplit, int chunk,
-    float* __restrict__ part_o, float* __restrict__ part_ml, unsigned long long* __restrict__ clk) {
+    const int32_t* __restrict__ slot_idx, int Hq, int Hkv, int page_size, int page_shift, int num_slots,
+    int fast_ok, float scale_log2e, __hip_bfloat16* __restrict__ out, const int32_t* __restrict__ hdr,
+    const int4* __restrict__ item_tab, float* __restrict__ part_o, float* __restrict__ part_ml,
+    unsigned long long* __restrict__ clk) {
     constexpr int WR = 32 * RB;              // packed query rows per wave (RB blocks of 32)
     constexpr int MT = WR * NW;              // packed query rows per workgroup
     constexpr int NB = D / 32;               // MFMA row blocks of the head dimension in O^T
@@ -249,32 +465,26 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     static_assert(UPW >= 1, "tile too small for this many waves");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [kStages][K tile | V tile]
 
-    // block -> (row tile, key split, kv head); the kv head varies fastest so that with 8 kv heads every
-    // XCD (blocks are dealt round-robin to the 8 XCDs) serves one head and keeps its shared prefixes in L2
+    // block -> (work item, kv head); the kv head varies fastest so that with 8 kv heads every XCD (blocks are
+    // dealt round-robin to the 8 XCDs) serves one head and keeps its shared prefixes in L2
     const int g = blockIdx.x % Hkv;
-    const int ts = blockIdx.x / Hkv;
-    const int t = ts / nsplit;
-    const int sp = ts - t * nsplit;
-    if (t >= *n_tiles) return;
-    const int r = tile_req[t];
-    const int row0 = tile_row0[t];
+    const int item = blockIdx.x / Hkv;
+    if (item >= hdr[1]) return;
+    const int4 rec0 = item_tab[3 * static_cast<size_t>(item)], rec1 = item_tab[3 * static_cast<size_t>(item) + 1];
+    const int slot_off = item_tab[3 * static_cast<size_t>(item) + 2].x;
+    const int row0 = rec0.y, kv_lo = rec0.z, kv_hi = rec0.w;
+    const int part = rec1.x;  // index of this item's partial result; -1: the item covers all keys and writes the output
+    const int P = rec1.y, E = rec1.z;
     const int G = Hq / Hkv;
-    const int P = prefix_len[r];
-    const int E = ext_len[r];
     const int rows_total = E * G;
     const int rows_here = min(MT, rows_total - row0);
-    const int i_last = (row0 + rows_here - 1) / G;
-    const int kv_end = P + i_last + 1;
-    int n_act, kv_lo, kv_hi;
-    split_range(kv_end, chunk, nsplit, sp, n_act, kv_lo, kv_hi);
-    if (sp >= n_act) return;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, hh = lane >> 5;
-    const int64_t e0 = ext_offsets[r];
-    const int32_t* __restrict__ slots = slot_idx + slot_offsets[r];
+    const int64_t e0 = rec1.w;
+    const int32_t* __restrict__ slots = slot_idx + slot_off;
 
     // this lane's query rows: one per row block
     const bool wave_on = wave * WR < rows_here;
@@ -601,7 +811,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     for (int rb = 0; rb < RB; ++rb) {
         const float l_row = row_sum(l_run[rb]);
         if (!row_ok[rb]) continue;
-        if (n_act == 1) {
+        if (part < 0) {
             const float inv = 1.f / l_row;
             __hip_bfloat16* orow = out + ((e0 + qi[rb]) * Hq + qh[rb]) * static_cast<int64_t>(D);
 #pragma unroll
@@ -614,7 +824,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
                     *reinterpret_cast<uint2*>(orow + 32 * b + 8 * q4 + 4 * hh) = v;
                 }
         } else {
-            const size_t unit = (static_cast<size_t>(t) * nsplit + sp) * Hkv + g;
+            const size_t unit = static_cast<size_t>(part) * Hkv + g;
             const int lrow = wave * WR + rb * 32 + n;
             float* prow = part_o + (unit * MT + lrow) * D;
 #pragma unroll
@@ -631,27 +841,24 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     }
 }
 
-// Merge of the key-axis splits: out = sum_s 2^(m_s - m) O_s / sum_s 2^(m_s - m) l_s.
+// Merge of the parts of a split tile: out = sum_s 2^(m_s - m) O_s / sum_s 2^(m_s - m) l_s.
 template <int D>
-__global__ __launch_bounds__(256) void extend_merge_kernel(const int32_t* __restrict__ prefix_len,
-                                                          const int32_t* __restrict__ ext_len,
+__global__ __launch_bounds__(256) void extend_merge_kernel(const int32_t* __restrict__ ext_len,
                                                           const int32_t* __restrict__ ext_offsets, int Hq, int Hkv,
                                                           __hip_bfloat16* __restrict__ out,
-                                                          const int32_t* __restrict__ n_tiles,
-                                                          const int32_t* __restrict__ tile_req,
-                                                          const int32_t* __restrict__ tile_row0, int mt, int nsplit,
-                                                          int chunk, const float* __restrict__ part_o,
+                                                          const int32_t* __restrict__ hdr,
+                                                          const int4* __restrict__ tile_tab,
+                                                          const int32_t* __restrict__ split_tiles, int mt,
+                                                          const float* __restrict__ part_o,
                                                           const float* __restrict__ part_ml) {
-    const int t = blockIdx.x, g = blockIdx.y;
-    if (t >= *n_tiles) return;
-    const int r = tile_req[t], row0 = tile_row0[t];
-    const int G = Hq / Hkv;
-    const int P = prefix_len[r], E = ext_len[r];
-    const int rows_here = min(mt, E * G - row0);
-    const int kv_end = P + (row0 + rows_here - 1) / G + 1;
-    int n_act, lo, hi;
-    split_range(kv_end, chunk, nsplit, 0, n_act, lo, hi);
+    const int g = blockIdx.y;
+    if (static_cast<int>(blockIdx.x) >= hdr[2]) return;
+    const int t = split_tiles[blockIdx.x];
+    const int4 tt = tile_tab[t];
+    const int n_act = tt.x, part0 = tt.y, r = tt.z, row0 = tt.w;
     if (n_act <= 1) return;
+    const int G = Hq / Hkv;
+    const int rows_here = min(mt, ext_len[r] * G - row0);
     const int64_t e0 = ext_offsets[r];
     constexpr int V4 = D / 4;           // 16-byte pieces per partial row
     constexpr int RPBK = 256 / V4;      // rows per block: one thread per (row, piece)
@@ -659,13 +866,13 @@ __global__ __launch_bounds__(256) void extend_merge_kernel(const int32_t* __rest
     if (lrow >= rows_here) return;
     float m = -INFINITY;
     for (int s = 0; s < n_act; ++s) {
-        const size_t unit = (static_cast<size_t>(t) * nsplit + s) * Hkv + g;
+        const size_t unit = static_cast<size_t>(part0 + s) * Hkv + g;
         m = fmaxf(m, part_ml[(unit * mt + lrow) * 2]);
     }
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float l = 0.f;
     for (int s = 0; s < n_act; ++s) {
-        const size_t unit = (static_cast<size_t>(t) * nsplit + s) * Hkv + g;
+        const size_t unit = static_cast<size_t>(part0 + s) * Hkv + g;
         const float2 ml = reinterpret_cast<const float2*>(part_ml)[unit * mt + lrow];
         const float w = (ml.x == -INFINITY) ? 0.f : exp2f(ml.x - m);
         l += w * ml.y;
@@ -683,17 +890,17 @@ __global__ __launch_bounds__(256) void extend_merge_kernel(const int32_t* __rest
 
 template <int D, int NW, int RB>
 static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_ext, const void* v_ext,
-                         const void* kv_pool, const int32_t* slot_idx, const int32_t* slot_offsets,
-                         const int32_t* prefix_len, const int32_t* ext_len, const int32_t* ext_offsets, int Hq, int Hkv,
-                         int page_size, int64_t num_slots, int64_t T_total, float scale_log2e, void* out, int32_t* n_tiles,
-                         int32_t* tile_req, int32_t* tile_row0, float* part_o, float* part_ml, unsigned long long* clk, hipStream_t stream) {
+                         const void* kv_pool, const int32_t* slot_idx, const int32_t* ext_len, const int32_t* ext_offsets,
+                         int Hq, int Hkv, int page_size, int64_t num_slots, int64_t T_total, float scale_log2e, void* out,
+                         const int32_t* hdr, const int4* tile_tab, const int4* item_tab, const int32_t* split_tiles, float* part_o,
+                         float* part_ml, unsigned long long* clk, hipStream_t stream) {
     constexpr size_t lds_bytes = static_cast<size_t>(kStages) * 2 * kKT * D * 2;
     int page_shift = -1;
     if ((page_size & (page_size - 1)) == 0) {
         page_shift = 0;
         while ((1 << page_shift) < page_size) ++page_shift;
     }
-    const dim3 grid(static_cast<unsigned>(p.tiles_cap) * p.nsplit * Hkv);
+    const dim3 grid(static_cast<unsigned>(p.items_cap) * Hkv);
     // The hand-scheduled tile addresses K/V rows with 32-bit byte offsets and 24-bit multiplies: it needs a
     // power-of-two page size, a pool below 4 GB, and extend tensors below 4 GB.
     const int64_t rowb = static_cast<int64_t>(D) * 2;
@@ -706,15 +913,14 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
         hipLaunchKernelGGL((extend_bf16_kernel<D, NW, RB>), grid, dim3(NW * 64), lds_bytes, stream,
                            static_cast<const __hip_bfloat16*>(q_ext), static_cast<const __hip_bfloat16*>(k_ext),
                            static_cast<const __hip_bfloat16*>(v_ext), static_cast<const __hip_bfloat16*>(kv_pool), slot_idx,
-                           slot_offsets, prefix_len, ext_len, ext_offsets, Hq, Hkv, page_size, page_shift,
-                           static_cast<int>(num_slots), fast_ok, scale_log2e, static_cast<__hip_bfloat16*>(out), n_tiles, tile_req,
-                           tile_row0, p.nsplit, p.chunk, part_o, part_ml, clk);
+                           Hq, Hkv, page_size, page_shift, static_cast<int>(num_slots), fast_ok, scale_log2e,
+                           static_cast<__hip_bfloat16*>(out), hdr, item_tab, part_o, part_ml, clk);
     }
-    if (p.nsplit > 1) {
+    if (p.parts_cap > 0) {  // whether any tile was split is known on the device only: unsplit tiles leave at once
         ProfScope prof(kProfMerge, stream);
-        hipLaunchKernelGGL((extend_merge_kernel<D>), dim3(p.tiles_cap, Hkv, (32 * RB * NW) / (256 / (D / 4))), dim3(256), 0, stream, prefix_len, ext_len,
-                           ext_offsets, Hq, Hkv, static_cast<__hip_bfloat16*>(out), n_tiles, tile_req, tile_row0, 32 * RB * NW,
-                           p.nsplit, p.chunk, part_o, part_ml);
+        hipLaunchKernelGGL((extend_merge_kernel<D>), dim3((p.parts_cap + 1) / 2, Hkv, (32 * RB * NW) / (256 / (D / 4))), dim3(256), 0,
+                           stream, ext_len, ext_offsets, Hq, Hkv, static_cast<__hip_bfloat16*>(out), hdr, tile_tab, split_tiles,
+                           32 * RB * NW, part_o, part_ml);
     }
     return PA_OK;
 }
@@ -740,9 +946,11 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
         return fail(PA_ENOMEM, "pa_extend_attention: workspace of %zu bytes given, %zu needed", workspace_bytes, p.total);
     PA_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255u) == 0, "pa_extend_attention: workspace must be 256-byte aligned");
     unsigned char* ws = static_cast<unsigned char*>(workspace);
-    int32_t* n_tiles = reinterpret_cast<int32_t*>(ws);
-    int32_t* tile_req = reinterpret_cast<int32_t*>(ws + p.off_req);
-    int32_t* tile_row0 = reinterpret_cast<int32_t*>(ws + p.off_row0);
+    int32_t* hdr = reinterpret_cast<int32_t*>(ws);
+    int32_t* order = reinterpret_cast<int32_t*>(ws + p.off_order);
+    int4* tile_tab = reinterpret_cast<int4*>(ws + p.off_tile);
+    int4* item_tab = reinterpret_cast<int4*>(ws + p.off_item);
+    int32_t* split_tiles = reinterpret_cast<int32_t*>(ws + p.off_split);
     float* part_o = reinterpret_cast<float*>(ws + p.off_part_o);
     float* part_ml = reinterpret_cast<float*>(ws + p.off_part_ml);
     // with the clock probe on, a few workgroups also add their cycle counts to two counters in the header
@@ -750,16 +958,17 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
     const int G = Hq / Hkv;
     const float scale_log2e = scale * 1.4426950408889634f;
     {
-        ProfScope prof(kProfTiles, stream);
-        hipLaunchKernelGGL(extend_tiles_kernel, dim3(1), dim3(256), 0, stream, ext_len, B, G, 32 * p.rb * p.nw, p.tiles_cap,
-                           n_tiles, tile_req, tile_row0);
+        ProfScope prof(kProfPlan, stream);
+        hipLaunchKernelGGL(extend_plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, prefix_len, ext_len, ext_offsets, slot_offsets, slot_idx, B,
+                           G, 32 * p.rb * p.nw, p.tiles_cap, p.items_cap, p.parts_cap, p.slots, hdr, order, tile_tab, item_tab,
+                           split_tiles);
     }
     if (D == 64)
-        launch_extend<64, 4, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, Hq,
-                             Hkv, page_size, num_slots, T, scale_log2e, out, n_tiles, tile_req, tile_row0, part_o, part_ml, clk, stream);
+        launch_extend<64, 4, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots, T,
+                             scale_log2e, out, hdr, tile_tab, item_tab, split_tiles, part_o, part_ml, clk, stream);
     else
-        launch_extend<128, 4, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, Hq,
-                              Hkv, page_size, num_slots, T, scale_log2e, out, n_tiles, tile_req, tile_row0, part_o, part_ml, clk, stream);
+        launch_extend<128, 4, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots, T,
+                              scale_log2e, out, hdr, tile_tab, item_tab, split_tiles, part_o, part_ml, clk, stream);
     PA_HIP(hipGetLastError());
     return PA_OK;
 }

@@ -9,7 +9,7 @@
 
 namespace pa {
 
-static const char* const kKernelNames[kProfKernels] = {"match_prefixes", "extend_tiles",        "extend_attention",
+static const char* const kKernelNames[kProfKernels] = {"match_prefixes", "extend_plan",        "extend_attention",
                                                        "extend_merge",   "extend_attention_f32", "append_kv",
                                                        "gather_kv"};
 

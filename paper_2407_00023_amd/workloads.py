@@ -378,12 +378,59 @@ def video_qa(seed=0, B=32, vis_len=8192, n_templates=8, tmpl_len=256, ext_lo=32,
                    pages, backed, notes={"template_of_request": which})
 
 
+# --------------------------------------------------------------------------------------
+# config 6: program-generation shaped
+# --------------------------------------------------------------------------------------
+def programming(seed=0, B=64, sys_len=1500, n_problems=6, n_new=3, prob_mean=2371, prob_sd=1656, prob_lo=200,
+                prob_hi=7000, gen_lo=1, gen_hi=8, Hq=32, Hkv=8, D=128, num_slots=262144, page_size=16,
+                vocab=128256, dtype="bf16") -> Workload:
+    """Every prompt = one system prompt of code demonstrations + a problem description.  n_problems
+    problems are cached with it; most requests are further generations for a cached problem (everything
+    but their last gen_lo..gen_hi tokens is cached), n_new requests bring a problem that is not cached yet
+    and prefill all of it behind the cached system prompt.  Stand-in for the programming workload
+    (Table 1, third row: prompts of 3,871 +- 1,656 tokens, 97 % shared)."""
+    rng = np.random.default_rng(seed)
+    pages = _Pages(rng, num_slots, page_size)
+    stok = rng.integers(0, vocab, size=sys_len).astype(np.int32)
+    sslot = pages.take(sys_len)
+
+    def problem_len():
+        return int(np.clip(rng.normal(prob_mean, prob_sd), prob_lo, prob_hi))
+
+    cached, firsts = [], set()
+    for _ in range(n_problems):
+        n = problem_len()
+        t = rng.integers(0, vocab, size=n).astype(np.int32)
+        while int(t[0]) in firsts:
+            t[0] = rng.integers(0, vocab)
+        firsts.add(int(t[0]))
+        cached.append((np.concatenate([stok, t]), np.concatenate([sslot, pages.take(n)])))
+    is_new = np.zeros(B, dtype=bool)
+    is_new[rng.choice(B, size=min(n_new, B), replace=False)] = True
+    which = rng.integers(0, n_problems, size=B)
+    req_prefix, ext, forbidden = [], [], []
+    for r in range(B):
+        if is_new[r]:
+            req_prefix.append((stok, sslot))
+            ext.append(problem_len())
+            forbidden.append(firsts)
+        else:
+            req_prefix.append(cached[int(which[r])])
+            ext.append(int(rng.integers(gen_lo, gen_hi + 1)))
+            forbidden.append(set())
+    backed = _unique_slots([c[1] for c in cached])
+    return _finish("programming", dtype, Hq, Hkv, D, page_size, num_slots, vocab, rng, seed,
+                   cached, req_prefix, ext, forbidden, pages, backed,
+                   notes={"new_problem": is_new, "problem_of_request": which})
+
+
 CONFIGS = {
     "tiny_fp32": tiny_fp32,
     "tool_use": tool_use,
     "long_doc_qa": long_doc_qa,
     "agent_tree": agent_tree,
     "video_qa": video_qa,
+    "programming": programming,
 }
 
 
@@ -402,6 +449,9 @@ def small_variant(name: str, seed: int = 0) -> Workload:
     if name == "video_qa":
         return video_qa(seed, B=4, vis_len=700, n_templates=2, tmpl_len=50, ext_lo=8, ext_hi=33,
                         n_cached=40, len_lo=100, len_hi=900, Hq=16, Hkv=2, num_slots=4096)
+    if name == "programming":
+        return programming(seed, B=7, sys_len=300, n_problems=2, n_new=2, prob_mean=400, prob_sd=250, prob_lo=60,
+                           prob_hi=900, gen_lo=1, gen_hi=5, Hq=8, Hkv=2, num_slots=8192)
     if name == "tiny_fp32":
         return tiny_fp32(seed)
     raise KeyError(name)

@@ -18,8 +18,8 @@ pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "radix_hand_example.txt")
-SMALL = ["tiny_fp32", "tool_use", "long_doc_qa", "agent_tree", "video_qa"]
-FULL = ["tool_use", "long_doc_qa", "agent_tree", "video_qa"]
+SMALL = ["tiny_fp32", "tool_use", "long_doc_qa", "agent_tree", "video_qa", "programming"]
+FULL = ["tool_use", "long_doc_qa", "agent_tree", "video_qa", "programming"]
 
 
 def say(*a):
@@ -432,6 +432,35 @@ def test_full_config_extend_sampled_rows(pa, gpu_device, full_cache, name):
     # softmax weights are a convex combination: |out| can never exceed the largest |V| in the inputs
     vmax = max(float(np.abs(W.bf16_bits_to_f32(wl.pool_v)).max()), float(np.abs(W.bf16_bits_to_f32(wl.v_ext)).max()))
     assert float(out.float().abs().max()) <= vmax * (1 + 2 ** -7)
+
+
+@pytest.mark.parametrize("case", ["many_requests", "many_tiles"])
+def test_extend_work_list_beyond_the_small_table_sizes(pa, gpu_device, case):
+    """The kernel that plans a launch keeps its tables in LDS for up to 1,024 requests and 3,072 row tiles and in
+    global memory beyond (more than 1,024 requests also keep their given order): both larger shapes against the
+    oracle."""
+    say(f"[case] work list {case}")
+    if case == "many_requests":
+        wl = W.tiny_fp32(seed=11, B=1100, prefix=96, ext_lo=1, ext_hi=5, n_distract=2, Hq=8, Hkv=2, D=64,
+                         num_slots=32768, page_size=16, dtype="bf16")
+    else:
+        wl = W.tiny_fp32(seed=12, B=8, prefix=200, ext_lo=12800, ext_hi=13100, n_distract=0, Hq=8, Hkv=2, D=128,
+                         num_slots=131072, page_size=16, dtype="bf16")
+        assert wl.T * (wl.Hq // wl.Hkv) // 128 > 3072
+    g, o = GpuSide(wl, gpu_device), OracleSide(wl)
+    pl, si = g.match()
+    out = g.extend(pl, si)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    pl_ref, si_ref = o.match()
+    assert_match_equal(wl, pl, si, pl_ref, si_ref)
+    rows = sample_rows(wl, 256, seed=3)
+    ref = o.extend(pl_ref, si_ref, rows=rows)
+    outn = out_to_f64(out)
+    got = np.stack([outn[wl.ext_offsets[r] + i, h] for r, i, h in rows])
+    err = np.abs(got - ref).max()
+    say(f"  max abs err over {len(rows)} rows: {err:.3e}")
+    assert err <= TOL[wl.dtype]
 
 
 def test_full_config_append_then_reuse(pa, gpu_device, full_cache):
