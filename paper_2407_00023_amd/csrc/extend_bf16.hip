@@ -62,6 +62,9 @@ constexpr int kItemOverhead = 4;         // fixed cost of a work item, in key ti
 constexpr int kMaxParts = 64;            // parts of one row tile at most
 constexpr int kSortMax = 1024;           // up to this many requests are ordered (and their lengths staged in LDS)
 constexpr int kTileLds = 3072;           // up to this many row tiles the planner keeps in LDS between its passes
+constexpr int kPackMax = 256;            // batches of up to this many requests pack the left-over rows of requests
+                                         // that share their prefix into common row tiles
+constexpr int kPackMinPrefix = 512;      // ... if the shared prefix has at least this many keys
 constexpr float kRescaleThreshold = 8.f; // log2 units: the running maximum may lag the true one by this much
 // The steady-state tiles (fast_run_*.inc) never move the running maximum: a run is left, for the general tile, when
 // the probabilities of one lane and key block sum to more than 2^40.  The exponent range of fp32 and bf16 leaves that
@@ -74,7 +77,9 @@ struct ExtendPlan {
     int items_cap;   // upper bound on the number of work items (row tile x part of its key range)
     int parts_cap;   // upper bound on the number of items that belong to split tiles (they write partial results)
     int slots;       // workgroup slots per KV head
-    size_t off_order, off_tile, off_item, off_split, off_part_o, off_part_ml, total;
+    int merge_cap;   // upper bound on the number of row tiles whose output rows are merged from partial results
+    int pack;        // 1: left-over rows of requests with a common prefix may be packed (B <= kPackMax)
+    size_t off_order, off_tile, off_aux, off_member, off_item, off_split, off_part_o, off_part_ml, total;
 };
 
 static inline size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -94,18 +99,23 @@ static ExtendPlan make_plan(int B, int64_t T, int64_t max_kv_len, int Hq, int Hk
     p.rb = 1;
     const int mt = 32 * p.rb * p.nw;
     const int64_t est = (T * G + mt - 1) / mt;
-    p.tiles_cap = static_cast<int>(est + B);
+    p.pack = B <= kPackMax;
+    p.tiles_cap = static_cast<int>(est + B);  // (packing only lowers the number of tiles)
     p.slots = kWgSlots / Hkv > 0 ? kWgSlots / Hkv : 1;
     const int64_t by_rule = static_cast<int64_t>(p.slots) * kRounds + 1;                  // sum of (parts - 1) over the tiles
     const int64_t per_tile = (max_kv_len / kKT) / kMinChunkTiles > 1 ? (max_kv_len / kKT) / kMinChunkTiles : 1;
     const int64_t by_size = static_cast<int64_t>(p.tiles_cap) * (per_tile < kMaxParts ? per_tile : kMaxParts);
     p.items_cap = static_cast<int>(p.tiles_cap + (by_rule < by_size ? by_rule : by_size));
-    p.parts_cap = static_cast<int>(2 * by_rule < by_size ? 2 * by_rule : by_size);
+    const int64_t split_parts = 2 * by_rule < by_size ? 2 * by_rule : by_size;
+    p.parts_cap = static_cast<int>(split_parts);
+    p.merge_cap = static_cast<int>(split_parts / 2 + 1);
     p.off_order = 256;
     p.off_tile = p.off_order + up256(sizeof(int32_t) * (B > 0 ? B : 1));
-    p.off_item = p.off_tile + up256(sizeof(int4) * p.tiles_cap);
+    p.off_aux = p.off_tile + up256(sizeof(int4) * p.tiles_cap);
+    p.off_member = p.off_aux + up256(sizeof(int4) * p.tiles_cap);
+    p.off_item = p.off_member + up256(sizeof(int4) * (B > 0 ? B : 1));
     p.off_split = p.off_item + up256(sizeof(int4) * 3 * p.items_cap);
-    p.off_part_o = p.off_split + up256(sizeof(int32_t) * ((p.parts_cap + 1) / 2 + 1));
+    p.off_part_o = p.off_split + up256(sizeof(int32_t) * (p.merge_cap + 1));
     const size_t units = static_cast<size_t>(p.parts_cap) * Hkv;
     p.off_part_ml = p.off_part_o + up256(units * mt * D * sizeof(float));
     p.total = p.off_part_ml + up256(units * mt * 2 * sizeof(float));
@@ -152,26 +162,55 @@ __device__ __forceinline__ void block_scan(int (&v)[N], int (&total)[N], int (*s
 }
 
 // ---------------------------------------------------------------------------------------
-// The work list.  One workgroup.  hdr[0] = row tiles, hdr[1] = work items, hdr[2] = split tiles (listed in
-// split_tiles, at most parts_cap / 2 of them).
+// The work list.  One workgroup.  hdr[0] = row tiles, hdr[1] = work items, hdr[2] = tiles to merge (listed in
+// merge_tiles).
 //   tile_tab[t] = (parts, index of its first partial result or -1, request, first packed row)
-//   item_tab[3 i ..] = (request, first packed row, first key, end key), (partial index or -1: writes the output,
-//                      prefix length, extend length, first extend token), (first slot-list entry, tile, 0, 0)
+//   tile_aux[t] = (kind, first member, members, rows of the group)               (shared tiles; zeros otherwise)
+//   item_tab[3 i ..] = (request, first packed row, first key, end key),
+//                      (partial index or -1: writes the output, prefix length, extend length or rows of the
+//                       group, first extend token), (first slot-list entry, tile, first member, members or 0)
+//   member_tab[m]   = (first row among the group's left-over rows, first extend token, first left-over row of the
+//                      request, extend length)
 // Everything a workgroup of the attention kernel needs sits in its item record: one dependent load, not four.
+//
+// Kinds of row tile.  Whole: rows of one request over all its keys.  With packing (B <= kPackMax, tables in LDS): the
+// left-over rows of a request - those past its last full tile, fewer than a tile - cost a workgroup as much per
+// key tile as a full tile, so where two or more requests share their whole prefix (at least kPackMinPrefix keys)
+// their left-over rows are laid end to end and cut into shared tiles.  A shared tile walks the common prefix, every
+// key of it visible to every row, and then the extend tokens of each request that has rows in the tile, one
+// request's after the other's, visible to that request's rows only (and causally).  Its members are the
+// consecutive entries of member_tab whose rows meet the tile.
 // ---------------------------------------------------------------------------------------
+constexpr int kTileWhole = 0, kTileShared = 1;
+
+struct TileDesc {
+    int kind, r, row0, kv_lo, kv_end, rows_total;  // rows_total: rows of the request, or of the group (shared)
+    int member0, n_members;                        // shared tiles: the entries of member_tab whose rows meet the tile
+};
+
 __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
     const int32_t* __restrict__ prefix_len, const int32_t* __restrict__ ext_len, const int32_t* __restrict__ ext_offsets,
     const int32_t* __restrict__ slot_offsets, const int32_t* __restrict__ slot_idx, int B, int G, int mt, int tiles_cap,
-    int items_cap, int parts_cap, int slots, int32_t* __restrict__ hdr, int32_t* __restrict__ order,
-    int4* __restrict__ tile_tab, int4* __restrict__ item_tab, int32_t* __restrict__ split_tiles) {
+    int items_cap, int parts_cap, int merge_cap, int slots, int pack, int32_t* __restrict__ hdr,
+    int32_t* __restrict__ order, int4* __restrict__ tile_tab, int4* __restrict__ tile_aux, int4* __restrict__ member_tab,
+    int4* __restrict__ item_tab, int32_t* __restrict__ merge_tiles) {
     __shared__ int s_w[3][kPlanThreads / 64 + 1];
     __shared__ int s_P[kSortMax], s_E[kSortMax];  // prefix and extend length of the request (staged when B <= kSortMax)
     __shared__ int s_key[kSortMax];               // keys of the request, prefix + extend length (-1: nothing to do)
     __shared__ int s_grp[kSortMax];               // slot of its last prefix token: equal for requests with the same prefix
-    __shared__ int s_gkey[kSortMax];              // the most keys of any request of its group
+    __shared__ int s_gkey[kSortMax];              // the most keys of any request of its group; later: first tile of a position
     __shared__ int s_order[kSortMax];             // position in the list -> request
     __shared__ int s_e0[kSortMax], s_so[kSortMax]; // first extend token and first slot-list entry of the request
-    __shared__ int s_trow[kTileLds], s_tkv[kTileLds];  // (request << 16 | row tile of the request), end of the key range
+    __shared__ int s_tpos[kTileLds];  // tile -> (list position << 12 | tile of the position)
+    // packing (B <= kPackMax): per list position ...
+    __shared__ int s_gid[kPackMax];     // its group (run of positions with the same prefix)
+    __shared__ int s_R[kPackMax];       // first row of its left-over rows among the group's, -1: not packed
+    __shared__ int s_nshared[kPackMax]; // shared tiles placed in front of its own tiles (the first position of a group)
+    // ... and per group
+    __shared__ int s_gn[kPackMax], s_gL[kPackMax];        // members, left-over rows
+    __shared__ int s_gbase[kPackMax], s_gm0[kPackMax];    // rows / members of earlier groups
+    // ... and per member (packed request)
+    __shared__ int s_mR[kPackMax], s_mE[kPackMax];        // first row among the group's left-over rows, extend length
     __shared__ int s_carry;
     const int tid = threadIdx.x;
     const bool staged = B <= kSortMax;
@@ -230,33 +269,65 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
     }
     if (tid == 0) s_carry = 0;
     __syncthreads();
-    // With few requests and few row tiles (row tiles of a request < 65536, staged lengths) the passes below work on
-    // LDS copies; otherwise on the table in global memory.
+    // With few requests and few row tiles the passes below work on LDS copies; otherwise on the table in global
+    // memory.
     const bool in_lds = staged && tiles_cap <= kTileLds;
-    // row tiles: a request's tiles are neighbours (they read the same keys), its last rows - the most keys - first
+    const bool packing = in_lds && pack && B <= kPackMax;
+    int n_tiles;
     if (in_lds) {
-        // B <= kPlanThreads here: the first tile of every list position, then one thread per tile
-        int cnt = 0;
-        if (tid < B) {
-            const int e = s_E[s_order[tid]];
-            cnt = e > 0 ? (e * G + mt - 1) / mt : 0;
+        // one thread per list position (B <= kPlanThreads here)
+        const bool on = tid < B;
+        const int r = on ? s_order[tid] : 0;
+        const int P = on ? s_P[r] : 0, E = on ? s_E[r] : 0;
+        const int rows = max(E, 0) * G, full = rows / mt, left = rows - full * mt;
+        int nshared = 0;
+        bool packed_me = false;  // this request's left-over rows go into shared tiles
+        if (packing) {
+            // groups: runs of positions with the same prefix
+            const bool head = on && (tid == 0 || s_grp[s_order[tid - 1]] != s_grp[r]);
+            if (tid < kPackMax) {
+                s_gn[tid] = 0;
+                s_gL[tid] = 0;
+            }
+            int v[1] = {head ? 1 : 0}, total[1];
+            block_scan<1>(v, total, s_w);
+            const int gid = v[0] + (head ? 1 : 0) - 1;  // (block_scan ends with a barrier: the zeros above are in place)
+            const bool cand = on && left > 0 && P >= kPackMinPrefix;
+            if (on) s_gid[tid] = gid;
+            if (cand) atomicAdd(&s_gn[gid], 1);
+            __syncthreads();
+            const bool packed = cand && s_gn[gid] >= 2;
+            packed_me = packed;
+            int v2[2] = {packed ? left : 0, packed ? 1 : 0}, total2[2];
+            block_scan<2>(v2, total2, s_w);
+            if (head) {
+                s_gbase[gid] = v2[0];
+                s_gm0[gid] = v2[1];
+            }
+            if (packed) atomicAdd(&s_gL[gid], left);
+            __syncthreads();
+            if (on) s_R[tid] = packed ? v2[0] - s_gbase[gid] : -1;
+            if (packed) {
+                member_tab[v2[1]] = make_int4(v2[0] - s_gbase[gid], s_e0[r], full * mt, E);
+                s_mR[v2[1]] = v2[0] - s_gbase[gid];
+                s_mE[v2[1]] = E;
+            }
+            if (head && s_gn[gid] >= 2) nshared = (s_gL[gid] + mt - 1) / mt;
+            if (on) s_nshared[tid] = nshared;
         }
-        int v[1] = {cnt}, total[1];
+        int v[1] = {on ? nshared + full + (left > 0 && !packed_me ? 1 : 0) : 0}, total[1];
         block_scan<1>(v, total, s_w);
-        if (tid < B) s_gkey[tid] = v[0];  // (s_gkey is free again)
+        if (on) s_gkey[tid] = v[0];  // (s_gkey is free again: the first tile of the position)
         __syncthreads();
-        const int nt = min(total[0], tiles_cap);
-        for (int t = tid; t < nt; t += kPlanThreads) {
+        n_tiles = min(total[0], tiles_cap);
+        for (int t = tid; t < n_tiles; t += kPlanThreads) {
             int lo = 0, hi = B;  // the last position whose first tile is <= t
             while (hi - lo > 1) {
                 const int mid = (lo + hi) >> 1;
                 if (s_gkey[mid] <= t) lo = mid; else hi = mid;
             }
-            const int r = s_order[lo];
-            const int c = (s_E[r] * G + mt - 1) / mt;
-            s_trow[t] = (r << 16) | (c - 1 - (t - s_gkey[lo]));
+            s_tpos[t] = (lo << 12) | (t - s_gkey[lo]);
         }
-        if (tid == 0) s_carry = total[0];
         __syncthreads();
     } else {
         for (int base = 0; base < B; base += kPlanThreads) {
@@ -270,37 +341,76 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
             int v[1] = {cnt}, total[1];
             block_scan<1>(v, total, s_w);
             const int start = s_carry + v[0];
-            for (int j = 0; j < cnt; ++j)
+            for (int j = 0; j < cnt; ++j)  // a request's last rows - the most keys - first
                 if (start + j < tiles_cap) tile_tab[start + j] = make_int4(1, -1, r, (cnt - 1 - j) * mt);
             __syncthreads();
             if (tid == 0) s_carry += total[0];
             __syncthreads();
         }
+        n_tiles = min(s_carry, tiles_cap);
     }
-    const int n_tiles = min(s_carry, tiles_cap);
+    // what tile t is
+    auto describe = [&](int t) {
+        TileDesc d{};
+        if (in_lds) {
+            const int pos = s_tpos[t] >> 12;
+            int j = s_tpos[t] & 0xFFF;
+            const int r = s_order[pos];
+            const int P = s_P[r], rows = s_E[r] * G, full = rows / mt;
+            d.r = r;
+            const int nshared = packing ? s_nshared[pos] : 0;
+            if (j < nshared) {  // a shared tile of the group this position heads
+                const int gid = s_gid[pos];
+                const int m0 = s_gm0[gid], nm = s_gn[gid], L = s_gL[gid];
+                d.kind = kTileShared;
+                d.row0 = j * mt;
+                d.rows_total = L;
+                // the members whose rows meet rows [row0, row_end): the one holding row0 ... the one holding row_end - 1
+                const int row_end = min(L, d.row0 + mt);
+                int ka = 0, kb = 0;
+                for (int k = 0; k < nm; ++k) {
+                    ka = s_mR[m0 + k] <= d.row0 ? k : ka;
+                    kb = s_mR[m0 + k] <= row_end - 1 ? k : kb;
+                }
+                int ext = 0;
+                for (int k = ka; k <= kb; ++k) ext += s_mE[m0 + k];
+                d.member0 = m0 + ka;
+                d.n_members = kb - ka + 1;
+                d.kv_lo = 0;
+                d.kv_end = P + ext;
+                return d;
+            }
+            j -= nshared;
+            d.rows_total = rows;
+            d.kv_lo = 0;
+            if (j < full) {  // the request's last rows - the most keys - first
+                d.kind = kTileWhole;
+                d.row0 = (full - 1 - j) * mt;
+                d.kv_end = P + (d.row0 + mt - 1) / G + 1;
+                return d;
+            }
+            d.kind = kTileWhole;  // left-over rows that were not packed
+            d.row0 = full * mt;
+            d.kv_end = P + (rows - 1) / G + 1;
+            return d;
+        }
+        const int4 tt = tile_tab[t];
+        d.kind = kTileWhole;
+        d.r = tt.z;
+        d.row0 = tt.w;
+        d.rows_total = E_of(tt.z) * G;
+        d.kv_lo = 0;
+        d.kv_end = P_of(tt.z) + (tt.w + min(mt, d.rows_total - tt.w) - 1) / G + 1;
+        return d;
+    };
     // cost of a tile = its key tiles + a fixed overhead; thread i owns tiles [i * per, (i + 1) * per)
     const int per = (n_tiles + kPlanThreads - 1) / kPlanThreads;
     const int t_lo = min(n_tiles, tid * per), t_hi = min(n_tiles, t_lo + per);
     int my_cost = 0;
-    for (int t = t_lo; t < t_hi; ++t) {  // the end of the tile's key range is kept for the passes below
-        int r, row0;
-        if (in_lds) {
-            r = s_trow[t] >> 16;
-            row0 = (s_trow[t] & 0xFFFF) * mt;
-        } else {
-            const int4 tt = tile_tab[t];
-            r = tt.z;
-            row0 = tt.w;
-        }
-        const int rows_here = min(mt, E_of(r) * G - row0);
-        const int kv_end = P_of(r) + (row0 + rows_here - 1) / G + 1;
-        if (in_lds)
-            s_tkv[t] = kv_end;
-        else
-            tile_tab[t] = make_int4(1, kv_end, r, row0);
-        my_cost += (kv_end + kKT - 1) / kKT + kItemOverhead;
+    for (int t = t_lo; t < t_hi; ++t) {
+        const TileDesc d = describe(t);
+        my_cost += (d.kv_end - d.kv_lo + kKT - 1) / kKT + kItemOverhead;
     }
-    auto kv_end_of = [&](int t) { return in_lds ? s_tkv[t] : tile_tab[t].y; };
     int W;
     {
         int v[1] = {my_cost}, total[1];
@@ -316,53 +426,50 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
         n = min(min(n, K / kMinChunkTiles), kMaxParts);
         return max(n, 1);
     };
-    int my_items = 0, my_parts = 0, my_split = 0;
+    // a tile's output rows come from partial results, joined by the merge kernel, if it is split
+    int my_items = 0, my_parts = 0, my_merge = 0;
     for (int t = t_lo; t < t_hi; ++t) {
-        const int n = parts_of((kv_end_of(t) + kKT - 1) / kKT);
+        const TileDesc d = describe(t);
+        const int n = parts_of((d.kv_end - d.kv_lo + kKT - 1) / kKT);
         my_items += n;
         my_parts += n > 1 ? n : 0;
-        my_split += n > 1;
+        my_merge += n > 1;
     }
-    int base3[3] = {my_items, my_parts, my_split}, total3[3];
+    int base3[3] = {my_items, my_parts, my_merge}, total3[3];
     block_scan<3>(base3, total3, s_w);
-    int item0 = base3[0], part0 = base3[1], split0 = base3[2];
-    int n_items = total3[0], n_split = total3[2];
-    const bool whole = n_items > items_cap || total3[1] > parts_cap;  // cannot happen by the bound; then nothing is split
-    if (whole) {
-        item0 = t_lo;
-        n_items = n_tiles;
-        n_split = 0;
-    }
-    {
-        for (int t = t_lo; t < t_hi; ++t) {
-            int4 tt;
-            if (in_lds)
-                tt = make_int4(0, s_tkv[t], s_trow[t] >> 16, (s_trow[t] & 0xFFFF) * mt);
-            else
-                tt = tile_tab[t];
-            const int kv_end = tt.y, r = tt.z;
-            const int K = (kv_end + kKT - 1) / kKT;
-            const int n = whole ? 1 : parts_of(K);
-            tile_tab[t] = make_int4(n, n > 1 ? part0 : -1, r, tt.w);
-            if (n > 1) split_tiles[split0++] = t;
-            const int4 rec1 = make_int4(0, P_of(r), E_of(r), staged ? s_e0[r] : ext_offsets[r]);
-            const int slot_off = staged ? s_so[r] : slot_offsets[r];
-            for (int j = 0; j < n; ++j) {
-                const int lo = static_cast<int>(static_cast<int64_t>(K) * j / n) * kKT;
-                const int hi = min(kv_end, static_cast<int>(static_cast<int64_t>(K) * (j + 1) / n) * kKT);
-                int4* rec = item_tab + 3 * static_cast<size_t>(item0 + j);
-                rec[0] = make_int4(r, tt.w, lo, hi);
-                rec[1] = make_int4(n > 1 ? part0 + j : -1, rec1.y, rec1.z, rec1.w);
-                rec[2] = make_int4(slot_off, t, 0, 0);
-            }
-            item0 += n;
-            part0 += n > 1 ? n : 0;
+    int item0 = base3[0], part0 = base3[1], merge0 = base3[2];
+    const int n_items = total3[0], n_merge = total3[2];
+    // (by the bounds the capacities were sized from this cannot happen; an empty list makes it visible: no output)
+    const bool overflow = n_items > items_cap || total3[1] > parts_cap || n_merge > merge_cap;
+    for (int t = t_lo; t < t_hi && !overflow; ++t) {
+        const TileDesc d = describe(t);
+        const int K = (d.kv_end - d.kv_lo + kKT - 1) / kKT;
+        const int n = parts_of(K);
+        const bool partial = n > 1;
+        tile_tab[t] = make_int4(n, partial ? part0 : -1, d.r, d.row0);
+        tile_aux[t] = make_int4(d.kind, d.member0, d.n_members, d.kind == kTileShared ? d.rows_total : 0);
+        if (partial) merge_tiles[merge0++] = t;
+        const int r = d.r;
+        const int e0 = staged ? s_e0[r] : ext_offsets[r];
+        const int slot_off = staged ? s_so[r] : slot_offsets[r];
+        const int P = P_of(r);
+        const int e_or_rows = d.kind == kTileShared ? d.rows_total : E_of(r);
+        for (int j = 0; j < n; ++j) {
+            const int lo = d.kv_lo + static_cast<int>(static_cast<int64_t>(K) * j / n) * kKT;
+            const int hi = min(d.kv_end, d.kv_lo + static_cast<int>(static_cast<int64_t>(K) * (j + 1) / n) * kKT);
+            int4* rec = item_tab + 3 * static_cast<size_t>(item0 + j);
+            rec[0] = make_int4(r, d.row0, lo, hi);
+            rec[1] = make_int4(partial ? part0 + j : -1, P, e_or_rows, e0);
+            rec[2] = make_int4(slot_off, t, d.member0, d.n_members);
         }
+        item0 += n;
+        part0 += partial ? n : 0;
     }
     if (tid == 0) {
-        hdr[0] = n_tiles;
-        hdr[1] = n_items;
-        hdr[2] = n_split;
+        hdr[0] = overflow ? 0 : n_tiles;
+        hdr[1] = overflow ? 0 : n_items;
+        hdr[2] = overflow ? 0 : n_merge;
+        hdr[3] = overflow;
     }
 }
 
@@ -450,8 +557,8 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     const __hip_bfloat16* __restrict__ v_ext, const __hip_bfloat16* __restrict__ pool,
     const int32_t* __restrict__ slot_idx, int Hq, int Hkv, int page_size, int page_shift, int num_slots,
     int fast_ok, float scale_log2e, __hip_bfloat16* __restrict__ out, const int32_t* __restrict__ hdr,
-    const int4* __restrict__ item_tab, float* __restrict__ part_o, float* __restrict__ part_ml,
-    unsigned long long* __restrict__ clk) {
+    const int4* __restrict__ item_tab, const int4* __restrict__ member_tab, float* __restrict__ part_o,
+    float* __restrict__ part_ml, unsigned long long* __restrict__ clk) {
     constexpr int WR = 32 * RB;              // packed query rows per wave (RB blocks of 32)
     constexpr int MT = WR * NW;              // packed query rows per workgroup
     constexpr int NB = D / 32;               // MFMA row blocks of the head dimension in O^T
@@ -471,12 +578,17 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     const int item = blockIdx.x / Hkv;
     if (item >= hdr[1]) return;
     const int4 rec0 = item_tab[3 * static_cast<size_t>(item)], rec1 = item_tab[3 * static_cast<size_t>(item) + 1];
-    const int slot_off = item_tab[3 * static_cast<size_t>(item) + 2].x;
+    const int4 rec2 = item_tab[3 * static_cast<size_t>(item) + 2];
+    const int slot_off = rec2.x;
     const int row0 = rec0.y, kv_lo = rec0.z, kv_hi = rec0.w;
     const int part = rec1.x;  // index of this item's partial result; -1: the item covers all keys and writes the output
-    const int P = rec1.y, E = rec1.z;
+    const int P = rec1.y;
     const int G = Hq / Hkv;
-    const int rows_total = E * G;
+    // a shared tile: left-over rows of n_members requests with this prefix, laid end to end; after the prefix keys
+    // come the members' extend tokens, member after member
+    const int member0 = __builtin_amdgcn_readfirstlane(rec2.z), n_members = __builtin_amdgcn_readfirstlane(rec2.w);
+    const bool shared = n_members > 0;
+    const int rows_total = shared ? rec1.z : rec1.z * G;
     const int rows_here = min(MT, rows_total - row0);
 
     const int tid = threadIdx.x;
@@ -488,21 +600,41 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
 
     // this lane's query rows: one per row block
     const bool wave_on = wave * WR < rows_here;
-    const int wave_i_last = (row0 + min(rows_here, wave * WR + WR) - 1) / G;
+    // (the rows of a shared tile are their requests' last ones: no tile of its key range is skipped)
+    const int wave_i_last = shared ? max(0, kv_hi - P) : (row0 + min(rows_here, wave * WR + WR) - 1) / G;
     bool row_ok[RB];
     int qi[RB], qh[RB];          // extend index and query head of the row
-    int vis_end[RB];             // keys [.., vis_end) are visible to the row
+    int vis_end[RB];             // keys [.., vis_end) are visible to the row ...
+    int vis_lo[RB];              // ... except, in a shared tile, the other members' extend tokens [P, vis_lo)
+    int64_t e0_row[RB];          // first extend token of the row's request
     int blk_vis_min[RB];         // every row of the block sees keys [.., this)
     bf16x8 qreg[RB][KS];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        const int rho = row0 + wave * WR + rb * 32 + n;
+        int rho = row0 + wave * WR + rb * 32 + n;
         row_ok[rb] = rho < rows_total;
+        e0_row[rb] = e0;
+        vis_lo[rb] = P;
+        if (shared) {
+            // whose row this is: the last member that starts at or before it; its place in that request; where
+            // that member's extend tokens begin on the tile's key axis
+            const int want = row_ok[rb] ? rho : member_tab[member0].x;
+            int seg = P;
+            for (int k = 0; k < n_members; ++k) {
+                const int4 mem = member_tab[member0 + k];  // (same address in every lane)
+                if (mem.x <= want) {
+                    e0_row[rb] = mem.y;
+                    rho = mem.z + (want - mem.x);
+                    vis_lo[rb] = seg;
+                }
+                seg += mem.w;
+            }
+        }
         qi[rb] = row_ok[rb] ? rho / G : 0;
         qh[rb] = g * G + (row_ok[rb] ? rho % G : 0);
-        vis_end[rb] = min(kv_hi, P + qi[rb] + 1);
-        blk_vis_min[rb] = min(kv_hi, P + (row0 + wave * WR + rb * 32) / G + 1);
-        const uint4* qp = reinterpret_cast<const uint4*>(q_ext + ((e0 + qi[rb]) * Hq + qh[rb]) * static_cast<int64_t>(D));
+        vis_end[rb] = min(kv_hi, vis_lo[rb] + qi[rb] + 1);
+        blk_vis_min[rb] = shared ? min(kv_hi, P) : min(kv_hi, P + (row0 + wave * WR + rb * 32) / G + 1);
+        const uint4* qp = reinterpret_cast<const uint4*>(q_ext + ((e0_row[rb] + qi[rb]) * Hq + qh[rb]) * static_cast<int64_t>(D));
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             uint4 v = make_uint4(0, 0, 0, 0);
@@ -552,7 +684,17 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
             const unsigned sl = static_cast<unsigned>(min(max(sl_next[u], 0), num_slots - 1));  // never outside the pool
             const size_t pool_off = static_cast<size_t>(sl >> page_shift) * page_stride +
                                     (sl & static_cast<unsigned>(page_size - 1)) * static_cast<unsigned>(ROWB);
-            const size_t off = ext ? static_cast<size_t>(p - P) * x_stride : pool_off;
+            int64_t xrow = p - P;  // extend token, counted from the first one of the request of this item
+            if (shared && ext) {
+                // the member whose extend tokens hold key p, and that token relative to e0
+                int seg = P;
+                for (int k = 0; k < n_members; ++k) {
+                    const int4 mem = member_tab[member0 + k];
+                    if (p >= seg) xrow = (static_cast<int64_t>(mem.y) - e0) + (p - seg);
+                    seg += mem.w;
+                }
+            }
+            const size_t off = ext ? static_cast<size_t>(xrow) * x_stride : pool_off;
             const unsigned char* ka = (ext ? kx_g : pool_g) + off + ld_koff(u);
             const unsigned char* va = (ext ? vx_g : pool_g + v_off32) + off + ld_voff(u);
             load_to_lds_16(ka, sk + blk * 1024);
@@ -623,7 +765,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int p = pb0 + 8 * (i / 4) + 4 * hh + (i % 4);
-                    if (p >= vis_end[rb]) sacc[rb][i] = -INFINITY;
+                    if (p >= vis_end[rb] || (p >= P && p < vis_lo[rb])) sacc[rb][i] = -INFINITY;
                 }
             }
             // row maximum of the block, in every lane of the row
@@ -813,7 +955,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
         if (!row_ok[rb]) continue;
         if (part < 0) {
             const float inv = 1.f / l_row;
-            __hip_bfloat16* orow = out + ((e0 + qi[rb]) * Hq + qh[rb]) * static_cast<int64_t>(D);
+            __hip_bfloat16* orow = out + ((e0_row[rb] + qi[rb]) * Hq + qh[rb]) * static_cast<int64_t>(D);
 #pragma unroll
             for (int b = 0; b < NB; ++b)
 #pragma unroll
@@ -841,59 +983,79 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     }
 }
 
-// Merge of the parts of a split tile: out = sum_s 2^(m_s - m) O_s / sum_s 2^(m_s - m) l_s.
+// Merge of the parts of a split tile: out = sum_s 2^(m_s - m) O_s / sum_s 2^(m_s - m) l_s over the parts s.
 template <int D>
 __global__ __launch_bounds__(256) void extend_merge_kernel(const int32_t* __restrict__ ext_len,
                                                           const int32_t* __restrict__ ext_offsets, int Hq, int Hkv,
                                                           __hip_bfloat16* __restrict__ out,
                                                           const int32_t* __restrict__ hdr,
                                                           const int4* __restrict__ tile_tab,
-                                                          const int32_t* __restrict__ split_tiles, int mt,
+                                                          const int4* __restrict__ tile_aux,
+                                                          const int4* __restrict__ member_tab,
+                                                          const int32_t* __restrict__ merge_tiles, int mt,
                                                           const float* __restrict__ part_o,
                                                           const float* __restrict__ part_ml) {
-    const int g = blockIdx.y;
-    if (static_cast<int>(blockIdx.x) >= hdr[2]) return;
-    const int t = split_tiles[blockIdx.x];
-    const int4 tt = tile_tab[t];
-    const int n_act = tt.x, part0 = tt.y, r = tt.z, row0 = tt.w;
-    if (n_act <= 1) return;
-    const int G = Hq / Hkv;
-    const int rows_here = min(mt, ext_len[r] * G - row0);
-    const int64_t e0 = ext_offsets[r];
     constexpr int V4 = D / 4;           // 16-byte pieces per partial row
-    constexpr int RPBK = 256 / V4;      // rows per block: one thread per (row, piece)
-    const int lrow = blockIdx.z * RPBK + threadIdx.x / V4, c = threadIdx.x % V4;
-    if (lrow >= rows_here) return;
-    float m = -INFINITY;
-    for (int s = 0; s < n_act; ++s) {
-        const size_t unit = static_cast<size_t>(part0 + s) * Hkv + g;
-        m = fmaxf(m, part_ml[(unit * mt + lrow) * 2]);
+    constexpr int RPBK = 256 / V4;      // rows per pass of a block: one thread per (row, piece)
+    const int G = Hq / Hkv;
+    const int chunks = mt / RPBK;
+    // a fixed grid strides over (tile to merge, kv head, chunk of rows): how many there are is known on the device only
+    const int n_work = hdr[2] * Hkv * chunks;
+    for (int w = blockIdx.x; w < n_work; w += gridDim.x) {
+        const int chunk = w % chunks, g = (w / chunks) % Hkv;
+        const int t = merge_tiles[w / (chunks * Hkv)];
+        const int4 tt = tile_tab[t];
+        const int4 aux = tile_aux[t];
+        const int n_parts = tt.x, part0 = tt.y, row0 = tt.w;
+        const bool shared = aux.x == kTileShared;
+        const int rows_here = min(mt, (shared ? aux.w : ext_len[tt.z] * G) - row0);
+        const int lrow = chunk * RPBK + threadIdx.x / V4, c = threadIdx.x % V4;
+        if (lrow >= rows_here) continue;
+        // whose row it is: the tile's request, or in a shared tile the last member that starts at or before it
+        int64_t e0 = 0;
+        int rho = row0 + lrow;
+        if (shared) {
+            for (int k = 0; k < aux.z; ++k) {
+                const int4 mem = member_tab[aux.y + k];
+                if (mem.x <= row0 + lrow) {
+                    e0 = mem.y;
+                    rho = mem.z + (row0 + lrow - mem.x);
+                }
+            }
+        } else {
+            e0 = ext_offsets[tt.z];
+        }
+        float m = -INFINITY;
+        for (int s = 0; s < n_parts; ++s) {
+            const size_t at = (static_cast<size_t>(part0 + s) * Hkv + g) * mt + lrow;
+            m = fmaxf(m, part_ml[at * 2]);
+        }
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        float l = 0.f;
+        for (int s = 0; s < n_parts; ++s) {
+            const size_t at = (static_cast<size_t>(part0 + s) * Hkv + g) * mt + lrow;
+            const float2 ml = reinterpret_cast<const float2*>(part_ml)[at];
+            const float wgt = (ml.x == -INFINITY) ? 0.f : exp2f(ml.x - m);
+            l += wgt * ml.y;
+            const float4 o = reinterpret_cast<const float4*>(part_o + at * D)[c];
+            acc.x += wgt * o.x; acc.y += wgt * o.y; acc.z += wgt * o.z; acc.w += wgt * o.w;
+        }
+        const float inv = 1.f / l;
+        __hip_bfloat16* orow = out + ((e0 + rho / G) * Hq + g * G + rho % G) * static_cast<int64_t>(D);
+        uint2 v;
+        v.x = pack_bf16x2(acc.x * inv, acc.y * inv);
+        v.y = pack_bf16x2(acc.z * inv, acc.w * inv);
+        reinterpret_cast<uint2*>(orow)[c] = v;
     }
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    float l = 0.f;
-    for (int s = 0; s < n_act; ++s) {
-        const size_t unit = static_cast<size_t>(part0 + s) * Hkv + g;
-        const float2 ml = reinterpret_cast<const float2*>(part_ml)[unit * mt + lrow];
-        const float w = (ml.x == -INFINITY) ? 0.f : exp2f(ml.x - m);
-        l += w * ml.y;
-        const float4 o = reinterpret_cast<const float4*>(part_o + (unit * mt + lrow) * D)[c];
-        acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
-    }
-    const float inv = 1.f / l;
-    const int rho = row0 + lrow;
-    __hip_bfloat16* orow = out + ((e0 + rho / G) * Hq + g * G + rho % G) * static_cast<int64_t>(D);
-    uint2 v;
-    v.x = pack_bf16x2(acc.x * inv, acc.y * inv);
-    v.y = pack_bf16x2(acc.z * inv, acc.w * inv);
-    reinterpret_cast<uint2*>(orow)[c] = v;
 }
 
 template <int D, int NW, int RB>
 static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_ext, const void* v_ext,
                          const void* kv_pool, const int32_t* slot_idx, const int32_t* ext_len, const int32_t* ext_offsets,
                          int Hq, int Hkv, int page_size, int64_t num_slots, int64_t T_total, float scale_log2e, void* out,
-                         const int32_t* hdr, const int4* tile_tab, const int4* item_tab, const int32_t* split_tiles, float* part_o,
-                         float* part_ml, unsigned long long* clk, hipStream_t stream) {
+                         const int32_t* hdr, const int4* tile_tab, const int4* tile_aux, const int4* member_tab,
+                         const int4* item_tab, const int32_t* merge_tiles, float* part_o, float* part_ml,
+                         unsigned long long* clk, hipStream_t stream) {
     constexpr size_t lds_bytes = static_cast<size_t>(kStages) * 2 * kKT * D * 2;
     int page_shift = -1;
     if ((page_size & (page_size - 1)) == 0) {
@@ -914,13 +1076,14 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
                            static_cast<const __hip_bfloat16*>(q_ext), static_cast<const __hip_bfloat16*>(k_ext),
                            static_cast<const __hip_bfloat16*>(v_ext), static_cast<const __hip_bfloat16*>(kv_pool), slot_idx,
                            Hq, Hkv, page_size, page_shift, static_cast<int>(num_slots), fast_ok, scale_log2e,
-                           static_cast<__hip_bfloat16*>(out), hdr, item_tab, part_o, part_ml, clk);
+                           static_cast<__hip_bfloat16*>(out), hdr, item_tab, member_tab, part_o, part_ml, clk);
     }
     if (p.parts_cap > 0) {  // whether any tile was split is known on the device only: unsplit tiles leave at once
         ProfScope prof(kProfMerge, stream);
-        hipLaunchKernelGGL((extend_merge_kernel<D>), dim3((p.parts_cap + 1) / 2, Hkv, (32 * RB * NW) / (256 / (D / 4))), dim3(256), 0,
-                           stream, ext_len, ext_offsets, Hq, Hkv, static_cast<__hip_bfloat16*>(out), hdr, tile_tab, split_tiles,
-                           32 * RB * NW, part_o, part_ml);
+        const int64_t most = static_cast<int64_t>(p.merge_cap) * Hkv * ((32 * RB * NW) / (256 / (D / 4)));
+        hipLaunchKernelGGL((extend_merge_kernel<D>), dim3(static_cast<unsigned>(most < 2048 ? most : 2048)), dim3(256), 0, stream,
+                           ext_len, ext_offsets, Hq, Hkv, static_cast<__hip_bfloat16*>(out), hdr, tile_tab, tile_aux, member_tab,
+                           merge_tiles, 32 * RB * NW, part_o, part_ml);
     }
     return PA_OK;
 }
@@ -949,8 +1112,10 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
     int32_t* hdr = reinterpret_cast<int32_t*>(ws);
     int32_t* order = reinterpret_cast<int32_t*>(ws + p.off_order);
     int4* tile_tab = reinterpret_cast<int4*>(ws + p.off_tile);
+    int4* tile_aux = reinterpret_cast<int4*>(ws + p.off_aux);
+    int4* member_tab = reinterpret_cast<int4*>(ws + p.off_member);
     int4* item_tab = reinterpret_cast<int4*>(ws + p.off_item);
-    int32_t* split_tiles = reinterpret_cast<int32_t*>(ws + p.off_split);
+    int32_t* merge_tiles = reinterpret_cast<int32_t*>(ws + p.off_split);
     float* part_o = reinterpret_cast<float*>(ws + p.off_part_o);
     float* part_ml = reinterpret_cast<float*>(ws + p.off_part_ml);
     // with the clock probe on, a few workgroups also add their cycle counts to two counters in the header
@@ -960,15 +1125,15 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
     {
         ProfScope prof(kProfPlan, stream);
         hipLaunchKernelGGL(extend_plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, prefix_len, ext_len, ext_offsets, slot_offsets, slot_idx, B,
-                           G, 32 * p.rb * p.nw, p.tiles_cap, p.items_cap, p.parts_cap, p.slots, hdr, order, tile_tab, item_tab,
-                           split_tiles);
+                           G, 32 * p.rb * p.nw, p.tiles_cap, p.items_cap, p.parts_cap, p.merge_cap, p.slots, p.pack, hdr, order,
+                           tile_tab, tile_aux, member_tab, item_tab, merge_tiles);
     }
     if (D == 64)
         launch_extend<64, 4, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots, T,
-                             scale_log2e, out, hdr, tile_tab, item_tab, split_tiles, part_o, part_ml, clk, stream);
+                             scale_log2e, out, hdr, tile_tab, tile_aux, member_tab, item_tab, merge_tiles, part_o, part_ml, clk, stream);
     else
         launch_extend<128, 4, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots, T,
-                              scale_log2e, out, hdr, tile_tab, item_tab, split_tiles, part_o, part_ml, clk, stream);
+                              scale_log2e, out, hdr, tile_tab, tile_aux, member_tab, item_tab, merge_tiles, part_o, part_ml, clk, stream);
     PA_HIP(hipGetLastError());
     return PA_OK;
 }

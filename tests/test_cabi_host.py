@@ -79,7 +79,7 @@ def test_size_queries_and_errors(pa):
     tiny = pa.extend_workspace_bytes(4, 100, 128, 8, 2, 64, torch.bfloat16)
     # partial results of split row tiles dominate: bounded by the work-list rule at serving sizes, by the number of
     # 512-key pieces at small ones
-    assert 0 < tiny < 1 << 20 and tiny < small <= 512 << 20 and 0 < split <= 512 << 20
+    assert 0 < tiny < 4 << 20 and tiny < small <= 512 << 20 and 0 < split <= 512 << 20
     with pytest.raises(ValueError):
         pa.extend_workspace_bytes(1, 1, 1, 32, 5, 128, torch.bfloat16)  # Hq not a multiple of Hkv
     lib = C.CDLL(pa.LIB_PATH)

@@ -434,6 +434,35 @@ def test_full_config_extend_sampled_rows(pa, gpu_device, full_cache, name):
     assert float(out.float().abs().max()) <= vmax * (1 + 2 ** -7)
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_extend_packs_leftover_rows_of_requests_with_a_common_prefix(pa, gpu_device, seed):
+    """Requests that share a prefix of 512 keys or more have the rows past their last full 128-row tile laid end to
+    end into shared tiles, which walk the prefix and then each member's extend tokens: every element against the
+    oracle, and the header of the work list says that there are fewer tiles than one request at a time would need."""
+    say(f"[case] packed left-over rows, seed {seed}")
+    wl = W.tool_use(seed, B=9, sys_len=520, n_tools=2, tool_lo=30, tool_hi=140, ext_lo=3, ext_hi=90, Hq=8, Hkv=2,
+                    num_slots=8192)
+    assert (wl.designed_prefix_len >= 512).all()
+    g, o = GpuSide(wl, gpu_device), OracleSide(wl)
+    pl, si = g.match()
+    nbytes = pa.extend_workspace_bytes(wl.B, wl.T, g.max_kv_len, wl.Hq, wl.Hkv, wl.D, g.tdtype)
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device=gpu_device)
+    out = g.extend(pl, si, workspace=ws)
+    torch.cuda.synchronize()
+    n_tiles, n_items, n_merge, overflow = ws[:16].view(torch.int32).tolist()
+    groups = len(set(wl.notes["tool_of_request"].tolist()))
+    rows = wl.ext_len.astype(np.int64) * (wl.Hq // wl.Hkv)
+    unpacked = int(((rows + 127) // 128).sum())
+    say(f"  tiles {n_tiles} (one request at a time: {unpacked}), items {n_items}, merged tiles {n_merge}; {groups} prefix groups")
+    assert overflow == 0 and n_tiles < unpacked
+    pl_ref, si_ref = o.match()
+    assert_match_equal(wl, pl, si, pl_ref, si_ref)
+    ref = o.extend(pl_ref, si_ref)
+    err = np.abs(out_to_f64(out) - ref).max()
+    say(f"  max abs err {err:.3e}")
+    assert err <= TOL[wl.dtype]
+
+
 @pytest.mark.parametrize("case", ["many_requests", "many_tiles"])
 def test_extend_work_list_beyond_the_small_table_sizes(pa, gpu_device, case):
     """The kernel that plans a launch keeps its tables in LDS for up to 1,024 requests and 3,072 row tiles and in
