@@ -29,8 +29,8 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3
 # HBM bytes per launch of the extend-attention kernel, measured with rocprofv3 --pmc: FETCH_SIZE x 1.984 +
 # WRITE_SIZE x 1.000 (KiB), the factors being what the same counters read for append_kv, a plain copy of
 # known size; the runs are summarised in profiles/extend_attention_<workload>.md.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"tool_use": 248_639_878, "agent_tree": 2_871_238_233, "long_doc_qa": 1_311_929_340,
-                          "video_qa": 538_494_213, "programming": 289_392_562}
+MEASURED_TRAFFIC_BYTES = {"tool_use": 246_820_946, "agent_tree": 3_189_850_325, "long_doc_qa": 937_641_675,
+                          "video_qa": 415_963_927, "programming": 309_799_688}
 
 
 def algorithmic_work(wl, prefix_len):
