@@ -69,9 +69,24 @@ int pa_tree_create(pa_tree** out);
 int pa_tree_insert(pa_tree* tree, const int32_t* tokens, const int32_t* slots, int32_t n,
                    int32_t* n_already_cached);
 
-/* Flatten the tree and copy it to the current device (allocates device memory owned by
- * the tree, frees the previous mirror).  Synchronises `stream` before returning. */
+/* Bring the mirror on the current device up to date.  The flat form of the tree lives in a pinned
+ * host buffer owned by the tree and follows every change of the tree as it happens (a new leaf
+ * appends its tokens and adds two table entries, a split rewrites a few words, an eviction shortens
+ * or deletes entries); an upload copies the byte ranges that changed since the last one, so its
+ * cost follows the size of the change, not of the tree.  The first upload, and one after changes
+ * that outgrew the room left in the flat form (it is rebuilt with half as much again) or left more
+ * than half of its token array dead, copies everything.  Copies are enqueued on `stream` and the
+ * call returns without waiting for them, so pa_match_prefixes calls that follow on the same stream
+ * see the new tree; work that still reads the mirror on another stream must have finished before
+ * the call.  A change of the tree waits for the copies of the upload before it. */
 int pa_tree_upload(pa_tree* tree, void* stream);
+
+/* on = 0: every upload rebuilds and copies the whole flat form (for comparison).  Default: 1. */
+int pa_tree_set_incremental_upload(pa_tree* tree, int on);
+
+/* Uploads so far that copied everything / only the changes, and the bytes the last one copied
+ * (each may be NULL). */
+int pa_tree_upload_stats(const pa_tree* tree, int64_t* full, int64_t* incremental, int64_t* last_bytes);
 
 /* Number of nodes (including the virtual root) and of stored tokens.  Either pointer may be NULL. */
 int pa_tree_stats(const pa_tree* tree, int64_t* n_nodes, int64_t* n_tokens);

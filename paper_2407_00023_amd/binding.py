@@ -32,6 +32,8 @@ _SIGS = {
     "pa_tree_create": (_i, [C.POINTER(_vp)]),
     "pa_tree_insert": (_i, [_vp, _vp, _vp, C.c_int32, C.POINTER(C.c_int32)]),
     "pa_tree_upload": (_i, [_vp, _vp]),
+    "pa_tree_set_incremental_upload": (_i, [_vp, _i]),
+    "pa_tree_upload_stats": (_i, [_vp, C.POINTER(_i64), C.POINTER(_i64), C.POINTER(_i64)]),
     "pa_tree_stats": (_i, [_vp, C.POINTER(_i64), C.POINTER(_i64)]),
     "pa_tree_destroy": (_i, [_vp]),
     "pa_tree_attach_pool": (_i, [_vp, _i64, _i]),
@@ -116,6 +118,15 @@ class Tree:
 
     def upload(self, stream=None):
         _check(_lib.pa_tree_upload(self._h, _stream(stream)), "pa_tree_upload")
+
+    def set_incremental_upload(self, on: bool) -> None:
+        _check(_lib.pa_tree_set_incremental_upload(self._h, 1 if on else 0), "pa_tree_set_incremental_upload")
+
+    def upload_stats(self):
+        """-> (uploads that copied everything, uploads that copied only the changes, bytes of the last one)."""
+        a, b, c = _i64(0), _i64(0), _i64(0)
+        _check(_lib.pa_tree_upload_stats(self._h, C.byref(a), C.byref(b), C.byref(c)), "pa_tree_upload_stats")
+        return int(a.value), int(b.value), int(c.value)
 
     # ---- cache bookkeeping on the host (pa_tree_attach_pool / admit / release / evict) ----
     def attach_pool(self, num_slots: int, page_size: int) -> None:

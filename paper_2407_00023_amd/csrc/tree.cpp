@@ -29,6 +29,30 @@ int fail(int code, const char* fmt, ...) {
     return code;
 }
 
+// Byte offsets of the arrays of the flat form (what the device sees) for given capacities.
+struct FlatLayout {
+    int64_t tok_cap = 0, node_cap = 0;
+    uint64_t tab_cap = 0;  // entries of each hash table, a power of two
+    size_t o_tok = 0, o_slot = 0, o_start = 0, o_len = 0, o_key = 0, o_val = 0, o_phe = 0, o_end = 0, total = 0;
+    void set(int64_t tokens, int64_t nodes, uint64_t table) {
+        auto up = [](size_t x) { return (x + 255) & ~size_t(255); };
+        tok_cap = tokens;
+        node_cap = nodes;
+        tab_cap = table;
+        o_tok = 0;
+        o_slot = o_tok + up(static_cast<size_t>(tokens) * 4);
+        o_start = o_slot + up(static_cast<size_t>(tokens) * 4);
+        o_len = o_start + up(static_cast<size_t>(nodes) * 4);
+        o_key = o_len + up(static_cast<size_t>(nodes) * 4);
+        o_val = o_key + up(table * 8);
+        o_phe = o_val + up(table * 4);
+        o_end = o_phe + up(table * sizeof(PathEntry));
+        total = o_end + up(static_cast<size_t>(nodes) * 8);
+    }
+};
+
+constexpr unsigned long long kDeletedKey = ~0ull - 1;  // child table: an entry that was removed (never a real key)
+
 struct Node {
     std::vector<int32_t> tok;   // edge tokens leading into this node
     std::vector<int32_t> slot;  // KV slot of each edge token
@@ -57,7 +81,23 @@ struct pa_tree {
     bool uploaded = false;
     int device = -1;
     void* d_blob = nullptr;
+    size_t d_cap = 0;                 // bytes allocated at d_blob
+    void* h_stage = nullptr;          // pinned host buffer the flat form is built in, kept between uploads
+    size_t h_cap = 0;
+    hipEvent_t copied = nullptr;      // recorded after the last copy out of h_stage
+    bool copy_pending = false;        // ... and not yet waited for
     pa::DeviceTree view{};
+    // The flat form in h_stage is kept up to date by every change of the tree (mirror_ok), so that an upload copies
+    // only what changed since the last one (dirty byte ranges).  When a change does not fit the capacities of the
+    // flat form, or too much of its token array is dead, mirror_ok goes false and the next upload rebuilds it.
+    bool incremental = true;
+    bool mirror_ok = false;
+    pa::FlatLayout flat{};
+    int64_t arena_end = 0, arena_holes = 0;  // tokens of the token array in use (live or dead), dead ones
+    int64_t table_used = 0;                  // entries of each hash table in use (live or deleted)
+    std::vector<int32_t> ht_pos, phe_pos, end_depth;  // per node: its entry in either table, depth of its last token
+    std::vector<std::pair<size_t, size_t>> dirty;     // (offset, bytes) changed in h_stage since the last upload
+    int64_t n_full_uploads = 0, n_incremental_uploads = 0, last_upload_bytes = 0;
     std::mutex mu;
 };
 
@@ -108,6 +148,168 @@ static int32_t split_node(pa_tree* t, int32_t c, int32_t k) {
     return h;
 }
 
+// ---- keeping the flat form in step with the tree ----------------------------------------------------------------
+struct FlatView {
+    int32_t *tok, *slot, *start, *len, *val;
+    unsigned long long *key, *end;
+    PathEntry* phe;
+};
+static FlatView flat_view(pa_tree* t) {
+    unsigned char* b = static_cast<unsigned char*>(t->h_stage);
+    const FlatLayout& f = t->flat;
+    return {reinterpret_cast<int32_t*>(b + f.o_tok),   reinterpret_cast<int32_t*>(b + f.o_slot),
+            reinterpret_cast<int32_t*>(b + f.o_start), reinterpret_cast<int32_t*>(b + f.o_len),
+            reinterpret_cast<int32_t*>(b + f.o_val),   reinterpret_cast<unsigned long long*>(b + f.o_key),
+            reinterpret_cast<unsigned long long*>(b + f.o_end), reinterpret_cast<PathEntry*>(b + f.o_phe)};
+}
+template <class T>
+static void mark(pa_tree* t, const T* first, size_t count) {
+    const size_t off = static_cast<size_t>(reinterpret_cast<const unsigned char*>(first) - static_cast<unsigned char*>(t->h_stage));
+    t->dirty.emplace_back(off, count * sizeof(T));
+}
+// May the flat form be changed now?  Not if it is stale anyway; and the copy of the last upload must be done with it.
+static bool mirror_open(pa_tree* t) {
+    if (!t->mirror_ok) return false;
+    if (t->copy_pending) {
+        if (hipEventSynchronize(t->copied) != hipSuccess) {
+            (void)hipGetLastError();
+            t->mirror_ok = false;
+            return false;
+        }
+        t->copy_pending = false;
+    }
+    return true;
+}
+static int32_t child_table_put(pa_tree* t, FlatView& v, int32_t parent, int32_t first_tok, int32_t node) {
+    const uint64_t mask = t->flat.tab_cap - 1;
+    const unsigned long long key = (static_cast<unsigned long long>(static_cast<uint32_t>(parent)) << 32) | static_cast<uint32_t>(first_tok);
+    uint64_t h = hash_key(key) & mask;
+    while (v.key[h] != kEmptyKey) h = (h + 1) & mask;  // (deleted entries are not reused: a probe for a key stops at the first empty one)
+    v.key[h] = key;
+    v.val[h] = node;
+    mark(t, v.key + h, 1);
+    mark(t, v.val + h, 1);
+    return static_cast<int32_t>(h);
+}
+static int32_t path_table_put(pa_tree* t, FlatView& v, unsigned long long hash, int32_t depth, int32_t node, int32_t parent) {
+    const uint64_t mask = t->flat.tab_cap - 1;
+    uint64_t at = path_slot(hash, depth) & mask;
+    while (v.phe[at].node != -1) at = (at + 1) & mask;
+    v.phe[at].hash = hash;
+    v.phe[at].depth = depth;
+    v.phe[at].node = node;
+    v.phe[at].edge_start = v.start[node];
+    v.phe[at].edge_len = v.len[node];
+    v.phe[at].parent = parent;
+    mark(t, v.phe + at, 1);
+    return static_cast<int32_t>(at);
+}
+static unsigned long long hash_through(unsigned long long h, const std::vector<int32_t>& tok, size_t from, size_t to) {
+    for (size_t i = from; i < to; ++i) h = path_hash_push(h, tok[i]);
+    return h;
+}
+
+// A new leaf c (its tokens, slots and parent are set).
+static void mirror_new_leaf(pa_tree* t, int32_t c) {
+    if (!mirror_open(t)) return;
+    const Node& nd = t->nodes[c];
+    const int64_t len = static_cast<int64_t>(nd.tok.size());
+    if (c >= t->flat.node_cap || t->arena_end + len + 64 > t->flat.tok_cap ||
+        2 * static_cast<uint64_t>(t->table_used + 1) > t->flat.tab_cap) {
+        t->mirror_ok = false;
+        return;
+    }
+    FlatView v = flat_view(t);
+    const int32_t p = nd.parent;
+    std::memcpy(v.tok + t->arena_end, nd.tok.data(), static_cast<size_t>(len) * 4);
+    std::memcpy(v.slot + t->arena_end, nd.slot.data(), static_cast<size_t>(len) * 4);
+    mark(t, v.tok + t->arena_end, static_cast<size_t>(len));
+    mark(t, v.slot + t->arena_end, static_cast<size_t>(len));
+    v.start[c] = static_cast<int32_t>(t->arena_end);
+    v.len[c] = static_cast<int32_t>(len);
+    t->arena_end += len;
+    const unsigned long long first_hash = path_hash_push(v.end[p], nd.tok[0]);
+    v.end[c] = hash_through(first_hash, nd.tok, 1, nd.tok.size());
+    t->end_depth[c] = t->end_depth[p] + static_cast<int32_t>(len);
+    mark(t, v.start + c, 1);
+    mark(t, v.len + c, 1);
+    mark(t, v.end + c, 1);
+    t->ht_pos[c] = child_table_put(t, v, p, nd.tok[0], c);
+    t->phe_pos[c] = path_table_put(t, v, first_hash, t->end_depth[p], c, p);
+    ++t->table_used;
+}
+
+// Node c was split after k tokens: c keeps the tail, the new node h holds the head (both already updated).
+static void mirror_split(pa_tree* t, int32_t c, int32_t h, int32_t k) {
+    if (!mirror_open(t)) return;
+    if (h >= t->flat.node_cap || 2 * static_cast<uint64_t>(t->table_used + 1) > t->flat.tab_cap) {
+        t->mirror_ok = false;
+        return;
+    }
+    FlatView v = flat_view(t);
+    const Node& head = t->nodes[h];
+    const Node& tail = t->nodes[c];
+    const int32_t p = head.parent;
+    // the tokens stay where they are: the head is their first k, the tail the rest
+    v.start[h] = v.start[c];
+    v.len[h] = k;
+    v.start[c] += k;
+    v.len[c] -= k;
+    v.end[h] = hash_through(v.end[p], head.tok, 0, head.tok.size());
+    t->end_depth[h] = t->end_depth[p] + k;
+    mark(t, v.start + h, 1);
+    mark(t, v.len + h, 1);
+    mark(t, v.end + h, 1);
+    mark(t, v.start + c, 1);
+    mark(t, v.len + c, 1);
+    // the entries that led to c lead to the head now (same keys: same parent, same first token, same depth)
+    t->ht_pos[h] = t->ht_pos[c];
+    v.val[t->ht_pos[h]] = h;
+    mark(t, v.val + t->ht_pos[h], 1);
+    t->phe_pos[h] = t->phe_pos[c];
+    PathEntry& eh = v.phe[t->phe_pos[h]];
+    eh.node = h;
+    eh.edge_len = k;
+    mark(t, &eh, 1);
+    // and the tail gets entries of its own under the head
+    t->ht_pos[c] = child_table_put(t, v, h, tail.tok[0], c);
+    t->phe_pos[c] = path_table_put(t, v, path_hash_push(v.end[h], tail.tok[0]), t->end_depth[h], c, h);
+    ++t->table_used;
+}
+
+// Leaf c lost `removed` tokens from its tail and keeps some.
+static void mirror_trim(pa_tree* t, int32_t c, int32_t removed) {
+    if (!mirror_open(t)) return;
+    FlatView v = flat_view(t);
+    const Node& nd = t->nodes[c];
+    v.len[c] = static_cast<int32_t>(nd.tok.size());
+    v.end[c] = hash_through(v.end[nd.parent], nd.tok, 0, nd.tok.size());
+    t->end_depth[c] -= removed;
+    v.phe[t->phe_pos[c]].edge_len = v.len[c];
+    mark(t, v.len + c, 1);
+    mark(t, v.end + c, 1);
+    mark(t, v.phe + t->phe_pos[c], 1);
+    t->arena_holes += removed;
+}
+
+// Node c is gone (it held `removed` tokens when it went).
+static void mirror_remove(pa_tree* t, int32_t c, int32_t removed) {
+    if (!mirror_open(t)) return;
+    FlatView v = flat_view(t);
+    v.len[c] = 0;
+    mark(t, v.len + c, 1);
+    v.key[t->ht_pos[c]] = kDeletedKey;
+    mark(t, v.key + t->ht_pos[c], 1);
+    PathEntry& e = v.phe[t->phe_pos[c]];  // stays in its probe chain, matches nothing: no position is negative
+    e.node = 0;
+    e.depth = -1;
+    e.edge_len = 0;
+    mark(t, &e, 1);
+    t->arena_holes += removed;
+    // a token array that is mostly dead is compacted by the next full rebuild
+    if (t->arena_holes > 4096 && 2 * t->arena_holes > t->arena_end) t->mirror_ok = false;
+}
+
 }  // namespace pa
 
 extern "C" int pa_tree_insert(pa_tree* tree, const int32_t* tokens, const int32_t* slots, int32_t n,
@@ -131,6 +333,7 @@ extern "C" int pa_tree_insert(pa_tree* tree, const int32_t* tokens, const int32_
             if (k < elen) {
                 if (pos + k == n) { pos = n; break; }  // the sequence ends inside this edge: nothing new to store
                 cur = pa::split_node(tree, c, k);
+                pa::mirror_split(tree, c, cur, k);
                 pos += k;
                 break;  // tokens[pos] differs from the tail's first token, so the walk ends here
             }
@@ -146,6 +349,7 @@ extern "C" int pa_tree_insert(pa_tree* tree, const int32_t* tokens, const int32_
             nodes[cur].child.emplace(tokens[pos], lid);
             tree->n_tokens += n - pos;
             tree->uploaded = false;
+            pa::mirror_new_leaf(tree, lid);
         }
     } catch (const std::bad_alloc&) {
         return pa::fail(PA_ENOMEM, "pa_tree_insert: out of host memory");
@@ -208,6 +412,7 @@ extern "C" int pa_tree_admit(pa_tree* tree, const int32_t* tokens, int32_t n, in
             while (k < lim && nodes[c].tok[k] == tokens[pos + k]) ++k;
             if (k < elen) {
                 cur = pa::split_node(tree, c, k);
+                pa::mirror_split(tree, c, cur, k);
                 pos += k;
                 break;
             }
@@ -237,6 +442,7 @@ extern "C" int pa_tree_admit(pa_tree* tree, const int32_t* tokens, int32_t n, in
             leaf.parent = cur;
             nodes[cur].child.emplace(tokens[pos], lid);
             tree->n_tokens += rem;
+            pa::mirror_new_leaf(tree, lid);
             cur = lid;
         }
         const bool forget = tree->hit_window > 0 && now > INT64_MIN + tree->hit_window;
@@ -388,6 +594,9 @@ static int evict_locked(pa_tree* tree, int64_t need_slots, const std::unordered_
             nd.parent = -1;
             nd.hits.clear();
             tree->free_nodes.push_back(st.node);
+            mirror_remove(tree, st.node, st.tokens);
+        } else {
+            mirror_trim(tree, st.node, st.tokens);
         }
     }
     tree->n_tokens -= gone;
@@ -505,6 +714,7 @@ static void release_device(pa_tree* t) {
         (void)hipFree(t->d_blob);
         if (prev >= 0 && prev != t->device) (void)hipSetDevice(prev);
         t->d_blob = nullptr;
+        t->d_cap = 0;
     }
     t->uploaded = false;
 }
@@ -515,68 +725,110 @@ extern "C" int pa_tree_upload(pa_tree* tree, void* stream_) {
     std::lock_guard<std::mutex> lk(tree->mu);
     const auto& nodes = tree->nodes;
     const int64_t nn = static_cast<int64_t>(nodes.size());
-    if (tree->n_tokens > INT32_MAX - 64 || nn > INT32_MAX / 4)
+    if (tree->n_tokens > INT32_MAX / 2 - 64 || nn > INT32_MAX / 8)
         return pa::fail(PA_EINVAL, "pa_tree_upload: tree too large for 32-bit indices");
+    int cur_dev = -1;
+    PA_HIP(hipGetDevice(&cur_dev));
+    if (tree->copy_pending) {  // the copy before this one still reads the host buffer
+        PA_HIP(hipEventSynchronize(tree->copied));
+        tree->copy_pending = false;
+    }
+    if (!tree->copied) PA_HIP(hipEventCreateWithFlags(&tree->copied, hipEventDisableTiming));
 
-    // hash capacity: power of two >= 2 * (#edges), at least 64 so a 64-lane probe window never wraps onto itself
-    uint64_t cap = 64;
-    while (cap < 2ull * static_cast<uint64_t>(nn)) cap <<= 1;
+    // ---- only what changed since the last upload ----
+    if (tree->incremental && tree->mirror_ok && tree->d_blob && tree->device == cur_dev) {
+        auto& dirty = tree->dirty;
+        std::sort(dirty.begin(), dirty.end());
+        size_t bytes = 0, n_copies = 0;
+        unsigned char* h = static_cast<unsigned char*>(tree->h_stage);
+        unsigned char* d = static_cast<unsigned char*>(tree->d_blob);
+        for (size_t i = 0; i < dirty.size();) {
+            size_t lo = dirty[i].first, hi = lo + dirty[i].second;
+            // neighbours closer than 512 bytes go in one copy
+            for (++i; i < dirty.size() && dirty[i].first <= hi + 512; ++i) hi = std::max(hi, dirty[i].first + dirty[i].second);
+            PA_HIP(hipMemcpyAsync(d + lo, h + lo, hi - lo, hipMemcpyHostToDevice, stream));
+            bytes += hi - lo;
+            ++n_copies;
+        }
+        dirty.clear();
+        if (n_copies) {
+            PA_HIP(hipEventRecord(tree->copied, stream));
+            tree->copy_pending = true;
+        }
+        tree->view.n_nodes = static_cast<int32_t>(nn);
+        tree->uploaded = true;
+        ++tree->n_incremental_uploads;
+        tree->last_upload_bytes = static_cast<int64_t>(bytes);
+        return PA_OK;
+    }
 
-    auto up = [](size_t x) { return (x + 255) & ~size_t(255); };
-    const size_t ntok = static_cast<size_t>(tree->n_tokens);
-    const size_t o_tok = 0;
-    const size_t o_slot = o_tok + up((ntok + 64) * 4);
-    const size_t o_start = o_slot + up((ntok + 64) * 4);
-    const size_t o_len = o_start + up(nn * 4);
-    const size_t o_key = o_len + up(nn * 4);
-    const size_t o_val = o_key + up(cap * 8);
-    const size_t o_phe = o_val + up(cap * 4);
-    const size_t o_end = o_phe + up(cap * sizeof(pa::PathEntry));
-    const size_t total = o_end + up(nn * 8);
-
-    std::vector<unsigned char> blob;
+    // ---- the whole flat form, rebuilt with room to grow ----
+    tree->mirror_ok = false;
+    tree->dirty.clear();
+    const int64_t ntok = tree->n_tokens;
+    uint64_t cap = 64;  // power of two >= 4 * (#nodes): at most half full after as many more entries; and at least 64
+    while (cap < 4ull * static_cast<uint64_t>(nn)) cap <<= 1;  // so a 64-lane probe window never wraps onto itself
+    tree->flat.set(ntok + ntok / 2 + 4096, nn + nn / 2 + 256, cap);
+    const pa::FlatLayout& f = tree->flat;
+    if (tree->h_cap < f.total) {
+        if (tree->h_stage) (void)hipHostFree(tree->h_stage);
+        tree->h_stage = nullptr;
+        tree->h_cap = 0;
+        if (hipHostMalloc(&tree->h_stage, f.total, hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError();
+            return pa::fail(PA_ENOMEM, "pa_tree_upload: %zu bytes of pinned host memory", f.total);
+        }
+        tree->h_cap = f.total;
+    }
+    pa::FlatView v = pa::flat_view(tree);
     try {
-        blob.assign(total, 0);
+        tree->ht_pos.assign(static_cast<size_t>(f.node_cap), -1);
+        tree->phe_pos.assign(static_cast<size_t>(f.node_cap), -1);
+        tree->end_depth.assign(static_cast<size_t>(f.node_cap), 0);
     } catch (const std::bad_alloc&) {
         return pa::fail(PA_ENOMEM, "pa_tree_upload: out of host memory");
     }
-    int32_t* h_tok = reinterpret_cast<int32_t*>(blob.data() + o_tok);
-    int32_t* h_slot = reinterpret_cast<int32_t*>(blob.data() + o_slot);
-    int32_t* h_start = reinterpret_cast<int32_t*>(blob.data() + o_start);
-    int32_t* h_len = reinterpret_cast<int32_t*>(blob.data() + o_len);
-    unsigned long long* h_key = reinterpret_cast<unsigned long long*>(blob.data() + o_key);
-    int32_t* h_val = reinterpret_cast<int32_t*>(blob.data() + o_val);
-    for (uint64_t i = 0; i < cap; ++i) { h_key[i] = pa::kEmptyKey; h_val[i] = -1; }
+    const uint64_t mask = cap - 1;
+    for (uint64_t i = 0; i < cap; ++i) {
+        v.key[i] = pa::kEmptyKey;
+        v.val[i] = -1;
+    }
+    std::memset(v.start, 0, static_cast<size_t>(f.node_cap) * 4);
+    std::memset(v.len, 0, static_cast<size_t>(f.node_cap) * 4);
+    std::memset(v.end, 0, static_cast<size_t>(f.node_cap) * 8);
+    std::memset(v.phe, 0, cap * sizeof(pa::PathEntry));
+    for (uint64_t i = 0; i < cap; ++i) v.phe[i].node = -1;
 
-    int64_t cursor = 0;
+    int64_t cursor = 0, entries = 0;
     for (int64_t i = 0; i < nn; ++i) {
         const auto& nd = nodes[i];
-        h_start[i] = static_cast<int32_t>(cursor);
-        h_len[i] = static_cast<int32_t>(nd.tok.size());
+        v.start[i] = static_cast<int32_t>(cursor);
+        v.len[i] = static_cast<int32_t>(nd.tok.size());
         if (!nd.tok.empty()) {
-            std::memcpy(h_tok + cursor, nd.tok.data(), nd.tok.size() * 4);
-            std::memcpy(h_slot + cursor, nd.slot.data(), nd.slot.size() * 4);
+            std::memcpy(v.tok + cursor, nd.tok.data(), nd.tok.size() * 4);
+            std::memcpy(v.slot + cursor, nd.slot.data(), nd.slot.size() * 4);
         }
         cursor += static_cast<int64_t>(nd.tok.size());
         for (const auto& kv : nd.child) {
             const unsigned long long key =
                 (static_cast<unsigned long long>(static_cast<uint32_t>(i)) << 32) | static_cast<uint32_t>(kv.first);
-            uint64_t h = pa::hash_key(key) & (cap - 1);
-            while (h_key[h] != pa::kEmptyKey) h = (h + 1) & (cap - 1);
-            h_key[h] = key;
-            h_val[h] = kv.second;
+            uint64_t h = pa::hash_key(key) & mask;
+            while (v.key[h] != pa::kEmptyKey) h = (h + 1) & mask;
+            v.key[h] = key;
+            v.val[h] = kv.second;
+            tree->ht_pos[static_cast<size_t>(kv.second)] = static_cast<int32_t>(h);
+            ++entries;
         }
     }
+    std::memset(v.tok + cursor, 0, static_cast<size_t>(f.tok_cap - cursor) * 4);  // (edge reads may run past an edge's end)
+    std::memset(v.slot + cursor, 0, static_cast<size_t>(f.tok_cap - cursor) * 4);
 
     // positional index: depth-first walk carrying the hash of the path so far (explicit stack: paths can be deep)
-    pa::PathEntry* h_phe = reinterpret_cast<pa::PathEntry*>(blob.data() + o_phe);
-    unsigned long long* h_end = reinterpret_cast<unsigned long long*>(blob.data() + o_end);
-    for (uint64_t i = 0; i < cap; ++i) h_phe[i].node = -1;
     try {
         struct Item { int32_t node; int32_t parent; int32_t depth; unsigned long long hash; };  // depth, hash: of the path BEFORE the node's edge
         std::vector<Item> stack;
         stack.push_back({0, -1, 0, 0ull});
-        h_end[0] = 0ull;
+        v.end[0] = 0ull;
         while (!stack.empty()) {
             const Item it = stack.back();
             stack.pop_back();
@@ -584,53 +836,91 @@ extern "C" int pa_tree_upload(pa_tree* tree, void* stream_) {
             unsigned long long h = it.hash;
             if (it.node != 0) {
                 const unsigned long long key = pa::path_hash_push(h, nd.tok[0]);
-                uint64_t at = pa::path_slot(key, it.depth) & (cap - 1);
-                while (h_phe[at].node != -1) at = (at + 1) & (cap - 1);
-                h_phe[at].hash = key;
-                h_phe[at].depth = it.depth;
-                h_phe[at].node = it.node;
-                h_phe[at].edge_start = h_start[it.node];
-                h_phe[at].edge_len = h_len[it.node];
-                h_phe[at].parent = it.parent;
+                uint64_t at = pa::path_slot(key, it.depth) & mask;
+                while (v.phe[at].node != -1) at = (at + 1) & mask;
+                v.phe[at].hash = key;
+                v.phe[at].depth = it.depth;
+                v.phe[at].node = it.node;
+                v.phe[at].edge_start = v.start[it.node];
+                v.phe[at].edge_len = v.len[it.node];
+                v.phe[at].parent = it.parent;
+                tree->phe_pos[static_cast<size_t>(it.node)] = static_cast<int32_t>(at);
                 for (int32_t t : nd.tok) h = pa::path_hash_push(h, t);
-                h_end[it.node] = h;
+                v.end[it.node] = h;
             }
             const int32_t end_depth = it.depth + static_cast<int32_t>(nd.tok.size());
+            tree->end_depth[static_cast<size_t>(it.node)] = end_depth;
             for (const auto& kv : nd.child) stack.push_back({kv.second, it.node, end_depth, h});
         }
     } catch (const std::bad_alloc&) {
         return pa::fail(PA_ENOMEM, "pa_tree_upload: out of host memory");
     }
 
-    release_device(tree);
-    PA_HIP(hipGetDevice(&tree->device));
-    void* d = nullptr;
-    if (hipMalloc(&d, total) != hipSuccess) {
-        (void)hipGetLastError();
-        return pa::fail(PA_ENOMEM, "pa_tree_upload: hipMalloc of %zu bytes failed", total);
+    tree->uploaded = false;
+    if (tree->d_blob == nullptr || tree->d_cap < f.total || tree->device != cur_dev) {
+        release_device(tree);  // (hipFree waits for whatever still reads the old buffer)
+        tree->device = cur_dev;
+        void* fresh = nullptr;
+        if (hipMalloc(&fresh, f.total) != hipSuccess) {
+            (void)hipGetLastError();
+            return pa::fail(PA_ENOMEM, "pa_tree_upload: hipMalloc of %zu bytes failed", f.total);
+        }
+        tree->d_blob = fresh;
+        tree->d_cap = f.total;
     }
-    tree->d_blob = d;
-    PA_HIP(hipMemcpyAsync(d, blob.data(), total, hipMemcpyHostToDevice, stream));
-    PA_HIP(hipStreamSynchronize(stream));
+    void* d = tree->d_blob;
+    PA_HIP(hipMemcpyAsync(d, tree->h_stage, f.total, hipMemcpyHostToDevice, stream));
+    PA_HIP(hipEventRecord(tree->copied, stream));
+    tree->copy_pending = true;
     unsigned char* b = static_cast<unsigned char*>(d);
-    tree->view.edge_tok = reinterpret_cast<const int32_t*>(b + o_tok);
-    tree->view.edge_slot = reinterpret_cast<const int32_t*>(b + o_slot);
-    tree->view.node_start = reinterpret_cast<const int32_t*>(b + o_start);
-    tree->view.node_len = reinterpret_cast<const int32_t*>(b + o_len);
-    tree->view.ht_key = reinterpret_cast<const unsigned long long*>(b + o_key);
-    tree->view.ht_val = reinterpret_cast<const int32_t*>(b + o_val);
+    tree->view.edge_tok = reinterpret_cast<const int32_t*>(b + f.o_tok);
+    tree->view.edge_slot = reinterpret_cast<const int32_t*>(b + f.o_slot);
+    tree->view.node_start = reinterpret_cast<const int32_t*>(b + f.o_start);
+    tree->view.node_len = reinterpret_cast<const int32_t*>(b + f.o_len);
+    tree->view.ht_key = reinterpret_cast<const unsigned long long*>(b + f.o_key);
+    tree->view.ht_val = reinterpret_cast<const int32_t*>(b + f.o_val);
     tree->view.ht_mask = static_cast<uint32_t>(cap - 1);
-    tree->view.ph_entry = reinterpret_cast<const pa::PathEntry*>(b + o_phe);
-    tree->view.node_endhash = reinterpret_cast<const unsigned long long*>(b + o_end);
+    tree->view.ph_entry = reinterpret_cast<const pa::PathEntry*>(b + f.o_phe);
+    tree->view.node_endhash = reinterpret_cast<const unsigned long long*>(b + f.o_end);
     tree->view.ph_mask = static_cast<uint32_t>(cap - 1);
     tree->view.n_nodes = static_cast<int32_t>(nn);
     tree->uploaded = true;
+    tree->mirror_ok = tree->incremental;
+    tree->arena_end = cursor;
+    tree->arena_holes = 0;
+    tree->table_used = entries;
+    ++tree->n_full_uploads;
+    tree->last_upload_bytes = static_cast<int64_t>(f.total);
+    return PA_OK;
+}
+
+extern "C" int pa_tree_set_incremental_upload(pa_tree* tree, int on) {
+    PA_REQUIRE(tree != nullptr, "pa_tree_set_incremental_upload: tree is NULL");
+    std::lock_guard<std::mutex> lk(tree->mu);
+    tree->incremental = on != 0;
+    if (!tree->incremental) {
+        tree->mirror_ok = false;
+        tree->dirty.clear();
+    }
+    return PA_OK;
+}
+
+extern "C" int pa_tree_upload_stats(const pa_tree* tree, int64_t* full, int64_t* incremental, int64_t* last_bytes) {
+    PA_REQUIRE(tree != nullptr, "pa_tree_upload_stats: tree is NULL");
+    if (full) *full = tree->n_full_uploads;
+    if (incremental) *incremental = tree->n_incremental_uploads;
+    if (last_bytes) *last_bytes = tree->last_upload_bytes;
     return PA_OK;
 }
 
 extern "C" int pa_tree_destroy(pa_tree* tree) {
     if (!tree) return PA_OK;
+    if (tree->copied) {
+        (void)hipEventSynchronize(tree->copied);
+        (void)hipEventDestroy(tree->copied);
+    }
     release_device(tree);
+    if (tree->h_stage) (void)hipHostFree(tree->h_stage);
     delete tree;
     return PA_OK;
 }

@@ -594,6 +594,82 @@ def test_decode_shape_one_new_token(pa, gpu_device):
     assert c["T"] >= 8 and err <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("seed", [0, 1])
+def test_uploads_that_copy_only_the_changes(pa, gpu_device, seed):
+    """Many rounds of admissions (new leaves, splits), releases and evictions (shortened and deleted nodes) with an
+    upload after each: the mirror that follows the changes piece by piece and a second tree that is re-flattened
+    whole every time must both give the matcher what the per-token cache oracle says, for prompts along cached
+    paths, cut anywhere, with fresh tails.  The numbers of either kind of upload are checked too."""
+    from oracle.cache_oracle import CacheOracle
+    rng = np.random.default_rng(900 + seed)
+    page, nslots = 16, 16384
+    dev = gpu_device
+    trees = [pa.Tree(), pa.Tree()]
+    trees[1].set_incremental_upload(False)
+    co = CacheOracle(nslots, page)
+    for t in trees:
+        t.attach_pool(nslots, page)
+    tt = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    history, live, now, evictions, matched = [], [], 0, 0, 0
+    for rnd in range(60):
+        for _ in range(int(rng.integers(1, 5))):
+            if history and rng.random() < 0.75:
+                base = history[int(rng.integers(len(history)))]
+                head = base[:int(rng.integers(1, len(base) + 1))]
+            else:
+                head = np.zeros(0, np.int32)
+            p = np.concatenate([head, rng.integers(0, 300, int(rng.integers(1, 400)))]).astype(np.int32)
+            need = (len(p) + page - 1) // page * page
+            if co.free_slots() < need:
+                while len(live) > 2:
+                    hs = live.pop(0)
+                    for t, h in zip(trees, hs[:2]):
+                        t.release(h)
+                    co.release(hs[2])
+                want = co.evict(need)
+                for t in trees:
+                    assert t.evict(need) == want
+                evictions += 1
+            now += 1
+            ref = co.admit(list(p), now)
+            if ref is None:
+                now -= 1
+                continue
+            hs = []
+            for t in trees:
+                got = t.admit(p, now)
+                assert got[0] == ref[0] and got[1].tolist() == ref[1]
+                hs.append(got[2])
+            live.append((hs[0], hs[1], ref[2]))
+            history.append(p)
+        # what the matcher sees after this round's upload
+        prompts = []
+        for _ in range(6):
+            base = history[int(rng.integers(len(history)))]
+            prompts.append(np.concatenate([base[:int(rng.integers(1, len(base) + 1))],
+                                           rng.integers(0, 300, int(rng.integers(0, 40)))]).astype(np.int32))
+        toks = np.concatenate(prompts)
+        off = np.zeros(len(prompts) + 1, np.int32)
+        off[1:] = np.cumsum([len(p) for p in prompts])
+        want = [co.match(p) for p in prompts]
+        for t in trees:
+            t.upload()
+            pl, si = pa.match_prefixes(t, tt(toks), tt(off))
+            pln, sin = pl.cpu().numpy(), si.cpu().numpy()
+            for j in range(len(prompts)):
+                assert pln[j] == want[j][0], (rnd, j)
+                assert list(sin[off[j]:off[j] + want[j][0]]) == want[j][1], (rnd, j)
+                matched += want[j][0]
+    full_a, incr_a, last_a = trees[0].upload_stats()
+    full_b, incr_b, last_b = trees[1].upload_stats()
+    say(f"  following the changes: {full_a} whole + {incr_a} partial uploads, last {last_a} B; "
+        f"re-flattened: {full_b} whole, last {last_b} B; {evictions} evictions, {matched} tokens matched")
+    assert incr_b == 0 and full_b == 60
+    assert incr_a >= 40 and full_a >= 2        # the first one, and at least one after the flat form was outgrown
+    assert last_a * 20 < last_b or full_a + incr_a == 60
+    assert evictions >= 3
+
+
 def test_cache_loop_with_eviction(pa, gpu_device):
     """Rounds of upload -> match (GPU) -> admit (host: pages for the new tokens, pins) -> extend -> append, with
     releases and LRU evictions in between, so that pages are reused and pool rows overwritten.  Every round the
