@@ -463,6 +463,42 @@ def test_extend_packs_leftover_rows_of_requests_with_a_common_prefix(pa, gpu_dev
     assert err <= TOL[wl.dtype]
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_extend_random_shapes_against_the_oracle(pa, gpu_device, seed):
+    """Small batches of random shape - head counts, head size, page size, number of requests, how many share a
+    prefix and whether it is long enough to be packed, extend lengths from one token to a few tiles - every element
+    against the oracle.  (The work list, the packing of left-over rows and the split of long key ranges all take
+    their decisions from these numbers.)"""
+    rng = np.random.default_rng(7000 + seed)
+    Hkv = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    D = int(rng.choice([64, 128]))
+    page = int(rng.choice([1, 4, 16, 32]))
+    B = int(rng.integers(1, 24))
+    sys_len = int(rng.choice([1, 40, 300, 520, 700, 1500]))
+    n_tools = int(rng.integers(1, 5))
+    tool_hi = int(rng.choice([2, 30, 200, 600]))
+    ext_hi = int(rng.choice([1, 3, 40, 130, 400]))
+    say(f"[case] random shape {seed}: B={B} Hq={Hkv * G} Hkv={Hkv} D={D} page={page} sys={sys_len} tools={n_tools}x<={tool_hi} "
+        f"ext<={ext_hi}")
+    wl = W.tool_use(seed, B=B, sys_len=sys_len, n_tools=n_tools, tool_lo=1, tool_hi=tool_hi, ext_lo=1, ext_hi=ext_hi,
+                    Hq=Hkv * G, Hkv=Hkv, D=D, num_slots=32768, page_size=page)
+    g, o = GpuSide(wl, gpu_device), OracleSide(wl)
+    pl, si = g.match()
+    nbytes = pa.extend_workspace_bytes(wl.B, wl.T, g.max_kv_len, wl.Hq, wl.Hkv, wl.D, g.tdtype)
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device=gpu_device)
+    out = g.extend(pl, si, workspace=ws)
+    torch.cuda.synchronize()
+    n_tiles, n_items, n_merge, overflow = ws[:16].view(torch.int32).tolist()
+    assert overflow == 0 and n_items >= n_tiles >= 1
+    pl_ref, si_ref = o.match()
+    assert_match_equal(wl, pl, si, pl_ref, si_ref)
+    ref = o.extend(pl_ref, si_ref)
+    err = np.abs(out_to_f64(out) - ref).max()
+    say(f"  tiles {n_tiles}, items {n_items}, merged {n_merge}; max abs err {err:.3e}")
+    assert err <= TOL[wl.dtype]
+
+
 @pytest.mark.parametrize("case", ["many_requests", "many_tiles"])
 def test_extend_work_list_beyond_the_small_table_sizes(pa, gpu_device, case):
     """The kernel that plans a launch keeps its tables in LDS for up to 1,024 requests and 3,072 row tiles and in
