@@ -51,7 +51,9 @@ __device__ __forceinline__ int32_t find_child(const DeviceTree& t, int32_t node,
 // loop head takes over from the last confirmed position with an exact child lookup, so the result never
 // depends on the hash being free of collisions: a collision can only cost time.
 // ---------------------------------------------------------------------------------------------------
-constexpr int kWin = 1024;        // prompt positions per window = threads per workgroup
+constexpr int kWin = 1024;        // threads per workgroup
+constexpr int kPos = 2;           // prompt positions per thread and window (consecutive ones)
+constexpr int kWinP = kWin * kPos;  // prompt positions per window
 constexpr int kGroupEdge = 64;    // edges with at most this many tokens to compare are compared by 16 lanes, in one round
 constexpr int kWaveEdge = 1024;   // ... by one wave, 256 tokens per round; longer ones by the whole workgroup
 constexpr int kDirectEdge = 256;  // a next edge at least this long is compared directly, without opening a window
@@ -73,12 +75,12 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
     __shared__ unsigned long long s_wtot[kWaves];
     // per window position: {candidate node or -1, its parent, its edge length, tokens of the edge that match the
     // prompt (-2 = not compared yet: very long edge)}
-    __shared__ int4 s_rec[kWin];
-    __shared__ int32_t s_es[kWin];      // index of the candidate's first edge token
-    __shared__ int32_t s_list[kWin];    // window positions of candidates compared by 16 lanes
-    __shared__ int32_t s_list2[kWin];   // ... by one wave
-    __shared__ int32_t s_jump[kWin];    // position reached from a window position after 2^round valid hops, -1 = none
-    __shared__ int32_t s_mark[kWin];    // 1 = the position starts a node on the prompt's path
+    __shared__ int4 s_rec[kWinP];
+    __shared__ int32_t s_es[kWinP];      // index of the candidate's first edge token
+    __shared__ int16_t s_list[kWinP];    // window positions of candidates compared by 16 lanes
+    __shared__ int16_t s_list2[kWinP];   // ... by one wave
+    __shared__ int16_t s_jump[kWinP];    // position reached from a window position after 2^round valid hops, -1 = none
+    __shared__ uint8_t s_mark[kWinP];    // 1 = the position starts a node on the prompt's path
     __shared__ int32_t s_wmax[kWaves];
     __shared__ int32_t s_count, s_count2;
     __shared__ int32_t s_red[2][kWaves];
@@ -89,15 +91,17 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
     const int32_t* __restrict__ prompt = tokens + base;
     int32_t* __restrict__ out_slots = slot_idx + base;
 
-    // B^(2^k), and B^(lane + 1)
+    // With b = B^kPos (a thread's positions hash as one step of the scan): b^(2^k), and b^lane
     unsigned long long bp2[7];
-    bp2[0] = kPathHashBase;
+    bp2[0] = 1ull;
+#pragma unroll
+    for (int i = 0; i < kPos; ++i) bp2[0] *= kPathHashBase;
 #pragma unroll
     for (int k = 1; k < 7; ++k) bp2[k] = bp2[k - 1] * bp2[k - 1];
-    unsigned long long bpow_lane1 = 1ull;
+    unsigned long long bpow_lane = 1ull;
 #pragma unroll
-    for (int k = 0; k < 7; ++k)
-        if ((lane + 1) >> k & 1) bpow_lane1 *= bp2[k];
+    for (int k = 0; k < 6; ++k)
+        if (lane >> k & 1) bpow_lane *= bp2[k];
 
     int32_t pos = 0, cur = 0;        // matched so far; node whose edge ends at pos
     int red_round = 0;
@@ -148,10 +152,21 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
         }
         const unsigned long long h = t.node_endhash[cur];  // hash of prompt[0 .. pos)
         const int32_t w0 = pos;
-        const int32_t p = w0 + tid;
-        // ---- A. prefix hashes of the window: inclusive scan of x -> x * B + (token + 1); within a wave by
-        // shuffles (after step k a lane holds the hash of the 2^(k+1) positions ending at it), then across waves
-        unsigned long long c = p < n ? static_cast<unsigned long long>(static_cast<uint32_t>(prompt[p])) + 1ull : 0ull;
+        const int32_t rel0 = tid * kPos;  // this thread's first position in the window; its positions are rel0 + i
+        // ---- A. prefix hashes of the window: inclusive scan of x -> x * B + (token + 1).  A thread folds its own
+        // positions, then the scan runs over threads with B^kPos as the step: within a wave by shuffles, then
+        // across waves ----
+        unsigned long long loc[kPos];  // hash of this thread's positions 0 .. i
+        {
+            unsigned long long run = 0ull;
+#pragma unroll
+            for (int i = 0; i < kPos; ++i) {
+                const int32_t p = w0 + rel0 + i;
+                run = run * kPathHashBase + (p < n ? static_cast<unsigned long long>(static_cast<uint32_t>(prompt[p])) + 1ull : 0ull);
+                loc[i] = run;
+            }
+        }
+        unsigned long long c = loc[kPos - 1];
 #pragma unroll
         for (int k = 0; k < 6; ++k) {
             const unsigned long long left = __shfl_up(c, 1u << k);
@@ -159,37 +174,48 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
         }
         if (lane == 63) s_wtot[wave] = c;
         if (tid == 0) { s_count = 0; s_count2 = 0; }
+        unsigned long long excl = __shfl_up(c, 1);  // hash of the wave's positions before this thread's
+        if (lane == 0) excl = 0ull;
         lds_barrier();
-        unsigned long long before = h;  // hash of everything before this wave's 64 positions
+        unsigned long long before = h;  // hash of everything before this wave's positions
         for (int v = 0; v < wave; ++v) before = before * bp2[6] + s_wtot[v];
-        const unsigned long long hp = before * bpow_lane1 + c;  // hash of prompt[0 .. p]
+        const unsigned long long upto = before * bpow_lane + excl;  // hash of prompt[0 .. w0 + rel0)
         // ---- B. candidates: nodes whose edge starts at p after exactly this prefix (by hash) ----
-        int4 rec = make_int4(-1, -1, 0, 0);
-        if (p < n) {
-            uint32_t at = path_slot(hp, p) & t.ph_mask;
-            for (uint32_t probes = 0; probes <= t.ph_mask; ++probes) {
-                const uint4 lo = reinterpret_cast<const uint4*>(t.ph_entry + at)[0];  // hash, depth, node
-                const int32_t nd = static_cast<int32_t>(lo.w);
-                if (nd < 0) break;
-                const unsigned long long eh = (static_cast<unsigned long long>(lo.y) << 32) | lo.x;
-                if (eh == hp && static_cast<int32_t>(lo.z) == p) {
-                    const uint4 hi = reinterpret_cast<const uint4*>(t.ph_entry + at)[1];  // edge start, length, parent
-                    rec = make_int4(nd, static_cast<int32_t>(hi.z), static_cast<int32_t>(hi.y), -2);
-                    s_es[tid] = static_cast<int32_t>(hi.x);
-                    break;
+        {
+            unsigned long long bi = 1ull;
+#pragma unroll
+            for (int i = 0; i < kPos; ++i) {
+                bi *= kPathHashBase;
+                const int32_t rel = rel0 + i, p = w0 + rel;
+                const unsigned long long hp = upto * bi + loc[i];  // hash of prompt[0 .. p]
+                int4 rec = make_int4(-1, -1, 0, 0);
+                if (p < n) {
+                    uint32_t at = path_slot(hp, p) & t.ph_mask;
+                    for (uint32_t probes = 0; probes <= t.ph_mask; ++probes) {
+                        const uint4 lo = reinterpret_cast<const uint4*>(t.ph_entry + at)[0];  // hash, depth, node
+                        const int32_t nd = static_cast<int32_t>(lo.w);
+                        if (nd < 0) break;
+                        const unsigned long long eh = (static_cast<unsigned long long>(lo.y) << 32) | lo.x;
+                        if (eh == hp && static_cast<int32_t>(lo.z) == p) {
+                            const uint4 hi = reinterpret_cast<const uint4*>(t.ph_entry + at)[1];  // edge start, length, parent
+                            rec = make_int4(nd, static_cast<int32_t>(hi.z), static_cast<int32_t>(hi.y), -2);
+                            s_es[rel] = static_cast<int32_t>(hi.x);
+                            break;
+                        }
+                        at = (at + 1) & t.ph_mask;
+                    }
                 }
-                at = (at + 1) & t.ph_mask;
+                if (rel == 0) {  // position 0 holds the node found exactly above, whatever the probe said
+                    rec = make_int4(child, cur, c_len, -2);
+                    s_es[0] = c_es;
+                }
+                s_rec[rel] = rec;
+                if (rec.x >= 0) {
+                    const int32_t lim = min(rec.z, n - p);
+                    if (lim <= kGroupEdge) s_list[atomicAdd(&s_count, 1)] = static_cast<int16_t>(rel);
+                    else if (lim <= kWaveEdge) s_list2[atomicAdd(&s_count2, 1)] = static_cast<int16_t>(rel);
+                }
             }
-        }
-        if (tid == 0) {  // position 0 holds the node found exactly above, whatever the probe said
-            rec = make_int4(child, cur, c_len, -2);
-            s_es[0] = c_es;
-        }
-        s_rec[tid] = rec;
-        if (rec.x >= 0) {
-            const int32_t lim = min(rec.z, n - p);
-            if (lim <= kGroupEdge) s_list[atomicAdd(&s_count, 1)] = tid;
-            else if (lim <= kWaveEdge) s_list2[atomicAdd(&s_count2, 1)] = tid;
         }
         lds_barrier();
         // ---- C. compare the candidates' edges with the prompt, all candidates at once ----
@@ -229,8 +255,8 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
                     int32_t first = -1;
 #pragma unroll
                     for (int u = kWideUnroll - 1; u >= 0; --u) {
-                        const unsigned long long b = __ballot(bad[u]);
-                        if (b) first = c0 + 64 * u + __ffsll(static_cast<long long>(b)) - 1;
+                        const unsigned long long bb = __ballot(bad[u]);
+                        if (bb) first = c0 + 64 * u + __ffsll(static_cast<long long>(bb)) - 1;
                     }
                     if (first >= 0) { m = first; break; }
                 }
@@ -241,43 +267,69 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
         // ---- D. which candidates lie on the prompt's path: follow "edge fully matched, and the candidate at its
         // end is a child of this node" links from position 0, by pointer doubling ----
         {
-            rec = s_rec[tid];
-            int32_t link = -1;
-            if (rec.x >= 0 && rec.w == rec.z && tid + rec.z < kWin) {
-                const int4 nx = s_rec[tid + rec.z];
-                if (nx.x >= 0 && nx.y == rec.x) link = tid + rec.z;
+#pragma unroll
+            for (int i = 0; i < kPos; ++i) {
+                const int rel = rel0 + i;
+                const int4 rec = s_rec[rel];
+                int32_t link = -1;
+                if (rec.x >= 0 && rec.w == rec.z && rel + rec.z < kWinP) {
+                    const int4 nx = s_rec[rel + rec.z];
+                    if (nx.x >= 0 && nx.y == rec.x) link = rel + rec.z;
+                }
+                s_jump[rel] = static_cast<int16_t>(link);
+                s_mark[rel] = rel == 0 ? 1 : 0;
             }
-            s_jump[tid] = link;
-            s_mark[tid] = tid == 0 ? 1 : 0;
             lds_barrier();
 #pragma unroll 1
-            for (int round = 0; round < 10; ++round) {
-                const int32_t j = s_jump[tid];
-                if (j >= 0 && s_mark[tid]) s_mark[j] = 1;
-                const int32_t jj = j >= 0 ? s_jump[j] : -1;
+            for (int round = 0; round < 11; ++round) {  // 2^11 = kWinP hops at most
+                int32_t jj[kPos];
+#pragma unroll
+                for (int i = 0; i < kPos; ++i) {
+                    const int rel = rel0 + i;
+                    const int32_t j = s_jump[rel];
+                    if (j >= 0 && s_mark[rel]) s_mark[j] = 1;
+                    jj[i] = j >= 0 ? s_jump[j] : -1;
+                }
                 lds_barrier();
-                s_jump[tid] = jj;
+#pragma unroll
+                for (int i = 0; i < kPos; ++i) s_jump[rel0 + i] = static_cast<int16_t>(jj[i]);
                 lds_barrier();
             }
         }
         // ---- E. slots of the matched positions: position i belongs to the last path node starting at or before it ----
-        int32_t cov = s_mark[tid] ? tid : -1;
+        int32_t covs[kPos];
+        {
+            int32_t run = -1;
+#pragma unroll
+            for (int i = 0; i < kPos; ++i) {
+                run = max(run, s_mark[rel0 + i] ? rel0 + i : -1);
+                covs[i] = run;
+            }
+        }
+        int32_t cov = covs[kPos - 1];
 #pragma unroll
         for (int k = 0; k < 6; ++k) {
             const int32_t left = __shfl_up(cov, 1u << k);
             if (lane >= (1 << k)) cov = max(cov, left);
         }
         if (lane == 63) s_wmax[wave] = cov;
+        int32_t cov_before = __shfl_up(cov, 1);  // last path node before this thread's positions, in this wave
+        if (lane == 0) cov_before = -1;
         lds_barrier();
         int32_t z = -1;  // last path node of the window
         for (int v = 0; v < kWaves; ++v) {
             const int32_t x = s_wmax[v];
-            if (v < wave) cov = max(cov, x);
+            if (v < wave) cov_before = max(cov_before, x);
             z = max(z, x);
         }
-        if (cov >= 0) {
-            const int4 cr = s_rec[cov];
-            if (cr.w >= 0 && tid < cov + cr.w) out_slots[w0 + tid] = t.edge_slot[s_es[cov] + (tid - cov)];
+#pragma unroll
+        for (int i = 0; i < kPos; ++i) {
+            const int rel = rel0 + i;
+            const int32_t cv = max(cov_before, covs[i]);
+            if (cv >= 0) {
+                const int4 cr = s_rec[cv];
+                if (cr.w >= 0 && rel < cv + cr.w) out_slots[w0 + rel] = t.edge_slot[s_es[cv] + (rel - cv)];
+            }
         }
         // ---- F. where the walk stands after this window (the same in every thread).  The loop head decides
         // what follows: the hash only nominated the nodes, the child table has the last word. ----
@@ -290,7 +342,7 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
                 const int32_t m = zr.w;
                 const int32_t es = s_es[z];
                 // the part of the last node's edge that reaches past the window
-                for (int32_t k = kWin - z + tid; k < m; k += kWin) out_slots[w0 + z + k] = t.edge_slot[es + k];
+                for (int32_t k = kWinP - z + tid; k < m; k += kWin) out_slots[w0 + z + k] = t.edge_slot[es + k];
                 pos = w0 + z + m;
                 if (m == zr.z) cur = zr.x;
                 else if (m == 0) cur = zr.y;  // the nominated node is not the child (only a hash collision does that)
