@@ -78,7 +78,9 @@ int pa_tree_insert(pa_tree* tree, const int32_t* tokens, const int32_t* slots, i
  * than half of its token array dead, copies everything.  Copies are enqueued on `stream` and the
  * call returns without waiting for them, so pa_match_prefixes calls that follow on the same stream
  * see the new tree; work that still reads the mirror on another stream must have finished before
- * the call.  A change of the tree waits for the copies of the upload before it. */
+ * the call.  Changed ranges are copied from a snapshot taken at the call, so the tree may change
+ * again at once; only after an upload that copied everything does the next change of the tree wait
+ * for the copy. */
 int pa_tree_upload(pa_tree* tree, void* stream);
 
 /* on = 0: every upload rebuilds and copies the whole flat form (for comparison).  Default: 1. */

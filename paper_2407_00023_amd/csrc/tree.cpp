@@ -84,8 +84,15 @@ struct pa_tree {
     size_t d_cap = 0;                 // bytes allocated at d_blob
     void* h_stage = nullptr;          // pinned host buffer the flat form is built in, kept between uploads
     size_t h_cap = 0;
-    hipEvent_t copied = nullptr;      // recorded after the last copy out of h_stage
+    hipEvent_t copied = nullptr;      // recorded after the last copy out of h_stage (a whole upload)
     bool copy_pending = false;        // ... and not yet waited for
+    // Partial uploads copy from one of two small pinned buffers, filled from h_stage at upload time, so that the
+    // tree can go on changing (and h_stage with it) while the copies are in flight.
+    void* h_xfer[2] = {nullptr, nullptr};
+    size_t xfer_cap[2] = {0, 0};
+    hipEvent_t xfer_done[2] = {nullptr, nullptr};
+    bool xfer_pending[2] = {false, false};
+    int xfer_next = 0;
     pa::DeviceTree view{};
     // The flat form in h_stage is kept up to date by every change of the tree (mirror_ok), so that an upload copies
     // only what changed since the last one (dirty byte ranges).  When a change does not fit the capacities of the
@@ -739,21 +746,48 @@ extern "C" int pa_tree_upload(pa_tree* tree, void* stream_) {
     if (tree->incremental && tree->mirror_ok && tree->d_blob && tree->device == cur_dev) {
         auto& dirty = tree->dirty;
         std::sort(dirty.begin(), dirty.end());
-        size_t bytes = 0, n_copies = 0;
-        unsigned char* h = static_cast<unsigned char*>(tree->h_stage);
-        unsigned char* d = static_cast<unsigned char*>(tree->d_blob);
+        // neighbours closer than 512 bytes go in one copy
+        std::vector<std::pair<size_t, size_t>> runs;  // (offset, end)
+        size_t bytes = 0;
         for (size_t i = 0; i < dirty.size();) {
             size_t lo = dirty[i].first, hi = lo + dirty[i].second;
-            // neighbours closer than 512 bytes go in one copy
             for (++i; i < dirty.size() && dirty[i].first <= hi + 512; ++i) hi = std::max(hi, dirty[i].first + dirty[i].second);
-            PA_HIP(hipMemcpyAsync(d + lo, h + lo, hi - lo, hipMemcpyHostToDevice, stream));
+            runs.emplace_back(lo, hi);
             bytes += hi - lo;
-            ++n_copies;
         }
         dirty.clear();
-        if (n_copies) {
-            PA_HIP(hipEventRecord(tree->copied, stream));
-            tree->copy_pending = true;
+        if (bytes) {
+            // the runs are gathered into a transfer buffer (two take turns) and copied from there
+            const int x = tree->xfer_next;
+            tree->xfer_next ^= 1;
+            if (tree->xfer_pending[x]) {  // the upload before the last one, long done as a rule
+                PA_HIP(hipEventSynchronize(tree->xfer_done[x]));
+                tree->xfer_pending[x] = false;
+            }
+            if (tree->xfer_cap[x] < bytes) {
+                if (tree->h_xfer[x]) (void)hipHostFree(tree->h_xfer[x]);
+                tree->h_xfer[x] = nullptr;
+                tree->xfer_cap[x] = 0;
+                const size_t want = bytes * 2 > (size_t(64) << 10) ? bytes * 2 : (size_t(64) << 10);
+                if (hipHostMalloc(&tree->h_xfer[x], want, hipHostMallocDefault) != hipSuccess) {
+                    (void)hipGetLastError();
+                    tree->mirror_ok = false;
+                    return pa::fail(PA_ENOMEM, "pa_tree_upload: %zu bytes of pinned host memory", want);
+                }
+                tree->xfer_cap[x] = want;
+            }
+            if (!tree->xfer_done[x]) PA_HIP(hipEventCreateWithFlags(&tree->xfer_done[x], hipEventDisableTiming));
+            unsigned char* h = static_cast<unsigned char*>(tree->h_stage);
+            unsigned char* d = static_cast<unsigned char*>(tree->d_blob);
+            unsigned char* xb = static_cast<unsigned char*>(tree->h_xfer[x]);
+            size_t at = 0;
+            for (const auto& run : runs) {
+                std::memcpy(xb + at, h + run.first, run.second - run.first);
+                PA_HIP(hipMemcpyAsync(d + run.first, xb + at, run.second - run.first, hipMemcpyHostToDevice, stream));
+                at += run.second - run.first;
+            }
+            PA_HIP(hipEventRecord(tree->xfer_done[x], stream));
+            tree->xfer_pending[x] = true;
         }
         tree->view.n_nodes = static_cast<int32_t>(nn);
         tree->uploaded = true;
@@ -918,6 +952,13 @@ extern "C" int pa_tree_destroy(pa_tree* tree) {
     if (tree->copied) {
         (void)hipEventSynchronize(tree->copied);
         (void)hipEventDestroy(tree->copied);
+    }
+    for (int x = 0; x < 2; ++x) {
+        if (tree->xfer_done[x]) {
+            (void)hipEventSynchronize(tree->xfer_done[x]);
+            (void)hipEventDestroy(tree->xfer_done[x]);
+        }
+        if (tree->h_xfer[x]) (void)hipHostFree(tree->h_xfer[x]);
     }
     release_device(tree);
     if (tree->h_stage) (void)hipHostFree(tree->h_stage);
