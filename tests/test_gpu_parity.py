@@ -499,14 +499,20 @@ def test_extend_random_shapes_against_the_oracle(pa, gpu_device, seed):
     assert err <= TOL[wl.dtype]
 
 
-@pytest.mark.parametrize("case", ["many_requests", "many_tiles"])
+@pytest.mark.parametrize("case", ["many_requests", "many_tiles", "pack_256", "no_pack_300"])
 def test_extend_work_list_beyond_the_small_table_sizes(pa, gpu_device, case):
     """The kernel that plans a launch keeps its tables in LDS for up to 1,024 requests and 3,072 row tiles and in
-    global memory beyond (more than 1,024 requests also keep their given order): both larger shapes against the
-    oracle."""
+    global memory beyond (more than 1,024 requests also keep their given order), and packs left-over rows in batches
+    of up to 256 requests: shapes on either side of these limits against the oracle."""
     say(f"[case] work list {case}")
     if case == "many_requests":
         wl = W.tiny_fp32(seed=11, B=1100, prefix=96, ext_lo=1, ext_hi=5, n_distract=2, Hq=8, Hkv=2, D=64,
+                         num_slots=32768, page_size=16, dtype="bf16")
+    elif case == "pack_256":   # one prefix of 600 keys shared by 256 requests of 1..9 new tokens: 4..36 rows each
+        wl = W.tiny_fp32(seed=13, B=256, prefix=600, ext_lo=1, ext_hi=9, n_distract=2, Hq=8, Hkv=2, D=128,
+                         num_slots=32768, page_size=16, dtype="bf16")
+    elif case == "no_pack_300":
+        wl = W.tiny_fp32(seed=14, B=300, prefix=600, ext_lo=1, ext_hi=9, n_distract=2, Hq=8, Hkv=2, D=128,
                          num_slots=32768, page_size=16, dtype="bf16")
     else:
         wl = W.tiny_fp32(seed=12, B=8, prefix=200, ext_lo=12800, ext_hi=13100, n_distract=0, Hq=8, Hkv=2, D=128,
