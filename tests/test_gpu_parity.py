@@ -434,6 +434,36 @@ def test_full_config_extend_sampled_rows(pa, gpu_device, full_cache, name):
     assert float(out.float().abs().max()) <= vmax * (1 + 2 ** -7)
 
 
+def test_the_path_on_a_stream_of_the_callers(pa, gpu_device):
+    """Every call takes the stream it enqueues on.  Upload, match, extend and append on a side stream, with the
+    default stream kept busy by unrelated work, give bit for bit what the same calls give on the default stream."""
+    wl = W.small_variant("agent_tree", 9)
+    ga, gb = GpuSide(wl, gpu_device), GpuSide(wl, gpu_device)
+    pl_a, si_a = ga.match()
+    out_a = ga.extend(pl_a, si_a)
+    ga.append()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    busy = torch.randn(4096, 4096, device=gpu_device)
+    for _ in range(4):
+        busy = busy @ busy * 1e-3          # on the default stream, meanwhile
+    with torch.cuda.stream(side):
+        gb.tree.insert(np.array([5, 6, 7], np.int32), np.array([0, 1, 2], np.int32) + wl.num_slots)  # makes the mirror stale
+        gb.tree.upload(stream=side)
+        pl_b, si_b = pa.match_prefixes(gb.tree, gb.tokens, gb.offsets, stream=side)
+        out_b = pa.extend_attention(gb.q, gb.k, gb.v, gb.pool, si_b, gb.offsets, pl_b, gb.ext_len, gb.ext_offsets, wl.scale,
+                                    max_kv_len=gb.max_kv_len, stream=side, **gb.kw)
+        pa.append_kv(gb.pool, gb.new_slots, gb.k, gb.v, stream=side, **gb.kw)
+    side.synchronize()
+    torch.cuda.synchronize()
+    assert torch.equal(pl_a, pl_b)
+    for r in range(wl.B):
+        lo, P = int(wl.offsets[r]), int(pl_a[r])
+        assert torch.equal(si_a[lo:lo + P], si_b[lo:lo + P])
+    assert torch.equal(out_a, out_b)
+    assert torch.equal(ga.pool, gb.pool)
+
+
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_extend_packs_leftover_rows_of_requests_with_a_common_prefix(pa, gpu_device, seed):
     """Requests that share a prefix of 512 keys or more have the rows past their last full 128-row tile laid end to
