@@ -89,9 +89,10 @@ def cpu_baseline(wl, budget_s=15.0):
 
 
 def extras(pa, g, wl, prefix_len, slot_idx, out, ws, main_k, nbytes):
-    """Two measurements beside the step: the extend-attention kernel with cold caches (1 GiB streamed through the
+    """Measurements beside the step: the extend-attention kernel with cold caches (1 GiB streamed through the
     chip between launches: the L2s and the memory-side cache hold none of the K/V when it starts), and the matcher
-    on a batch large enough to show its bandwidth (4,096 requests resampled from the workload's)."""
+    on a batch large enough to show its bandwidth (4,096 requests resampled from the workload's), and what it costs to
+    bring the tree's device mirror up to date after a small change."""
     import numpy as np
     import torch
     dev = g.tokens.device
@@ -137,6 +138,32 @@ def extras(pa, g, wl, prefix_len, slot_idx, out, ws, main_k, nbytes):
         matched = int(wl.designed_prefix_len[pick].astype(np.int64).sum())
         ex["match_scaled"] = {"requests": Bbig, "avg_kernel_us": t * 1e6, "reqs_per_s": Bbig / t, "matched_tokens_per_s": matched / t,
                               "GBps": 16.0 * matched / t / 1e9, "bytes_per_matched_token": 16}
+    # ---- tree mirror: an upload after one small change, and one that copies the whole flat form ----
+    import time
+    vocab_hi = int(wl.tokens.max()) + 1 if wl.tokens.size else 1
+
+    def timed_uploads(n_up):
+        call, landed = [], []
+        for i in range(n_up):
+            junk = np.array([vocab_hi + i, 1, 2, 3], np.int32)            # a sequence no prompt starts with
+            g.tree.insert(junk, np.arange(4, dtype=np.int32) + wl.num_slots)  # (slots no request can reach)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            g.tree.upload()
+            t1 = time.perf_counter()
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            call.append((t1 - t0) * 1e6)
+            landed.append((t2 - t0) * 1e6)
+        return float(np.mean(call[1:])), float(np.mean(landed[1:]))
+
+    nodes, toks_in_tree = g.tree.stats()
+    part = timed_uploads(9)
+    g.tree.set_incremental_upload(False)
+    whole = timed_uploads(5)
+    g.tree.set_incremental_upload(True)
+    ex["tree_upload"] = {"tree_nodes": nodes, "tree_tokens": toks_in_tree, "after_one_insert_call_us": part[0],
+                         "after_one_insert_landed_us": part[1], "whole_tree_call_us": whole[0], "whole_tree_landed_us": whole[1]}
     return ex
 
 
