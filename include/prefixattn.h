@@ -208,6 +208,13 @@ int pa_e2_load_cost(const pa_cost_model* model, const int32_t* hist_missed_len, 
 int pa_e2_schedule(int32_t prompt_len, int32_t cached_len, const uint8_t* on_longest_node, const double* cost,
                    const double* decode_ratio, double imbal_r, int32_t n_gpus, int32_t* gpu, int32_t* mode);
 
+/* The flags pa_e2_schedule takes, from the cached lengths alone, for callers that keep one prefix tree
+ * per GPU and no global tree with its nodes: the matched path (as long as the longest cached_len[i])
+ * is cut where the GPUs' cached lengths differ, the longest piece (the first, if several are as long)
+ * stands for the longest node, and on_longest_node[i] = 1 for the GPUs whose cache reaches its end.
+ * All zero if nothing is cached anywhere. */
+int pa_e2_longest_piece(const int32_t* cached_len, int32_t n_gpus, uint8_t* on_longest_node);
+
 /* Per-GPU request history over the window H of Sec. 3.2 (first cost): what L and the decode ratio
  * are computed from.  Times are the caller's integers (any unit; the window is in the same unit);
  * a request counts at time `now` if now - window < its time <= now. */

@@ -28,6 +28,9 @@ Readings where the paper is silent (the same list is in the design document):
 * DecodeRatio of a GPU = decode time / (prefill time + decode time) over its window (0 if the window is
   empty).  ImbalR is a parameter.
 * Ties between GPUs (equal cost, equal ratio) go to the lowest GPU index.
+* ``longest_piece``: Algorithm 1 sends an exploited request to the GPUs that cache the longest node of the matched
+  path, which presupposes the global tree.  With one tree per GPU only the cached lengths are known: the path is cut
+  where they differ and the longest piece stands for the longest node.
 """
 from fractions import Fraction
 from typing import List, Optional, Sequence, Tuple
@@ -124,6 +127,19 @@ def e2_schedule(prompt_len: int, cached_len: int, on_longest_node: Sequence[bool
     if decode_ratio[top] > imbal_r:
         return top, EXPLORE_DECODE
     return min(range(n), key=lambda i: (cost[i], i)), EXPLORE_COST
+
+
+def longest_piece(cached_len: Sequence[int]) -> List[bool]:
+    """Which GPUs cache the longest node of the matched path, when only each GPU's cached length is known: the path
+    is cut at every distinct cached length, the longest piece (the earliest among equals) is the node."""
+    pieces, prev = [], 0
+    for cut in sorted(set(c for c in cached_len if c > 0)):
+        pieces.append((cut - prev, -cut))  # (length, minus its end): max() prefers longer, then earlier
+        prev = cut
+    if not pieces:
+        return [False] * len(cached_len)
+    end = -max(pieces)[1]
+    return [c >= end for c in cached_len]
 
 
 class ClusterHistory:

@@ -49,6 +49,7 @@ _SIGS = {
     "pa_priority_select": (_i, [_vp, _vp, _i64, C.c_int32, _i64, _vp, C.POINTER(_i64)]),
     "pa_e2_load_cost": (_i, [_vp, _vp, _i64, C.c_double, _vp, _vp, _i64, _i64, C.c_int32] + [C.POINTER(C.c_double)] * 3),
     "pa_e2_schedule": (_i, [C.c_int32, C.c_int32, _vp, _vp, _vp, C.c_double, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "pa_e2_longest_piece": (_i, [_vp, C.c_int32, _vp]),
     "pa_history_create": (_i, [C.c_int32, _i64, _vp, C.POINTER(_vp)]),
     "pa_history_destroy": (_i, [_vp]),
     "pa_history_assign": (_i, [_vp, C.c_int32, _i64, C.c_int32]),
@@ -256,6 +257,14 @@ def e2_schedule(prompt_len: int, cached_len: int, on_longest_node, cost, decode_
     _check(_lib.pa_e2_schedule(prompt_len, cached_len, _ptr(f), _ptr(c), _ptr(r), imbal_r, c.numel(), C.byref(gpu),
                                C.byref(mode)), "pa_e2_schedule")
     return int(gpu.value), int(mode.value)
+
+
+def e2_longest_piece(cached_len) -> torch.Tensor:
+    """-> flags (uint8 host tensor): the GPUs that cache the longest piece of the matched path."""
+    c = _host_i32(cached_len)
+    flags = torch.zeros(c.numel(), dtype=torch.uint8)
+    _check(_lib.pa_e2_longest_piece(_ptr(c), c.numel(), _ptr(flags)), "pa_e2_longest_piece")
+    return flags
 
 
 class History:

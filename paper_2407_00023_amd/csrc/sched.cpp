@@ -154,6 +154,31 @@ extern "C" int pa_e2_schedule(int32_t prompt_len, int32_t cached_len, const uint
     return PA_OK;
 }
 
+extern "C" int pa_e2_longest_piece(const int32_t* cached_len, int32_t n_gpus, uint8_t* on_longest_node) {
+    PA_REQUIRE(n_gpus >= 1 && cached_len && on_longest_node, "pa_e2_longest_piece: bad argument");
+    try {
+        std::vector<int32_t> cuts;
+        for (int32_t i = 0; i < n_gpus; ++i) {
+            PA_REQUIRE(cached_len[i] >= 0, "pa_e2_longest_piece: negative length");
+            if (cached_len[i] > 0) cuts.push_back(cached_len[i]);
+        }
+        std::sort(cuts.begin(), cuts.end());
+        cuts.erase(std::unique(cuts.begin(), cuts.end()), cuts.end());
+        int32_t prev = 0, best_len = 0, best_end = -1;
+        for (int32_t cut : cuts) {  // the first of the longest pieces wins
+            if (cut - prev > best_len) {
+                best_len = cut - prev;
+                best_end = cut;
+            }
+            prev = cut;
+        }
+        for (int32_t i = 0; i < n_gpus; ++i) on_longest_node[i] = best_end >= 0 && cached_len[i] >= best_end;
+    } catch (const std::bad_alloc&) {
+        return pa::fail(PA_ENOMEM, "pa_e2_longest_piece: out of host memory");
+    }
+    return PA_OK;
+}
+
 struct pa_history {
     struct Gpu {
         std::deque<std::pair<int64_t, int32_t>> assigned;  // (time, missed_len)

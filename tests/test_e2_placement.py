@@ -8,9 +8,9 @@ and the two must take the same decision at every step.  On the CPU the library s
 inputs (they are the matcher's output, and the matcher runs on the GPU); the GPU test takes them from
 pa_match_prefixes on each instance's tree.
 
-One reading belongs to this harness, not to the library: the paper's "GPUs with the longest node in the matched
-path" needs the nodes of a global tree, which is not built here.  The matched path is cut where the instances'
-cached lengths differ; the longest piece stands for the longest node, and the instances that cache it are flagged.
+The paper's "GPUs with the longest node in the matched path" needs the nodes of a global tree, which is not built
+here: the matched path is cut where the instances' cached lengths differ, the longest piece stands for the longest
+node, and the instances that cache it are flagged (pa_e2_longest_piece, and its twin in the oracle).
 
 Streams: prompts of the synthetic tool_use and agent_tree generators under several seeds (each seed is one
 application with its own shared context), shuffled together.
@@ -67,6 +67,9 @@ class OracleSide:
     def schedule(self, *a):
         return so.e2_schedule(*a)
 
+    def longest_piece(self, c):
+        return [1 if x else 0 for x in so.longest_piece(c)]
+
     def evict_for(self, g, prompt):
         return self.caches[g].evict_for(prompt.tolist())
 
@@ -101,6 +104,9 @@ class LibSide:
     def schedule(self, *a):
         return self.pa.e2_schedule(*a)
 
+    def longest_piece(self, c):
+        return self.pa.e2_longest_piece(c).tolist()
+
     def evict_for(self, g, prompt):
         return self.trees[g].evict_for(prompt)
 
@@ -116,13 +122,6 @@ class LibSide:
         self.trees[g].release(h)
 
 
-def longest_piece_flags(c):
-    cuts, prev, best_len, best_end = sorted(set(x for x in c if x > 0)), 0, 0, None
-    for cut in cuts:
-        if cut - prev > best_len:
-            best_len, best_end = cut - prev, cut
-        prev = cut
-    return [1 if best_end is not None and x >= best_end else 0 for x in c]
 
 
 def run_cluster(side, prompts, out_lens, n_gpus, page, policy="e2"):
@@ -141,7 +140,7 @@ def run_cluster(side, prompts, out_lens, n_gpus, page, policy="e2"):
             costs.append(L + M + P)
             ratios.append(ratio)
         if policy == "e2":
-            gpu, mode = side.schedule(n, max(c), longest_piece_flags(c), costs, ratios, IMBAL_R)
+            gpu, mode = side.schedule(n, max(c), side.longest_piece(c), costs, ratios, IMBAL_R)
         else:
             gpu, mode = r % n_gpus, -1
         missed = n - c[gpu]

@@ -238,6 +238,19 @@ def test_ties_go_to_the_lowest_index_and_no_flag_means_explore(impl):
     assert impl.schedule(10, 9, [0, 0, 0], [2.0, 1.0, 3.0], [0, 0, 0], 0.5) == (1, so.EXPLORE_COST)
 
 
+def test_longest_piece_of_the_matched_path(pa):
+    for impl in (so.longest_piece, lambda c: [bool(x) for x in pa.e2_longest_piece(c).tolist()]):
+        assert impl([0, 0, 0]) == [False, False, False]
+        assert impl([1800, 2200, 0, 1800]) == [True, True, False, True]      # pieces 1800 and 400: the first
+        assert impl([100, 900, 0, 900]) == [False, True, False, True]        # pieces 100 and 800: the second
+        assert impl([500, 1000]) == [True, True]                             # equal pieces: the earlier one
+        assert impl([7]) == [True]
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        c = rng.integers(0, 6, int(rng.integers(1, 9))) * int(rng.integers(1, 50))
+        assert [bool(x) for x in pa.e2_longest_piece(c).tolist()] == so.longest_piece(c.tolist())
+
+
 # ---- history window ------------------------------------------------------------------------------------------------
 def test_history_window_edges_and_ratio(impl):
     m = impl.model(1.0, 0.0, 2.0, 0.0, 7.0)
