@@ -245,9 +245,12 @@ def tiny_fp32(seed=0, B=4, prefix=96, ext_lo=16, ext_hi=32, n_distract=8, dist_l
 # config 2: tool-use shaped
 # --------------------------------------------------------------------------------------
 def tool_use(seed=0, B=64, sys_len=1800, n_tools=16, tool_lo=200, tool_hi=600, ext_lo=50, ext_hi=150,
-             Hq=32, Hkv=8, D=128, num_slots=262144, page_size=16, vocab=128256, dtype="bf16") -> Workload:
+             Hq=32, Hkv=8, D=128, num_slots=262144, page_size=16, vocab=128256, dtype="bf16", zipf=0.0,
+             name="tool_use") -> Workload:
     """Every prompt = system prefix + one of n_tools tool-demonstration prefixes (all
-    cached) + new tokens.  Stand-in for the tool-use workload (Table 1, first row)."""
+    cached) + new tokens.  Stand-in for the tool-use workload (Table 1, first row).  With zipf > 0 the
+    tool of a request is drawn with probability proportional to rank**-zipf instead of uniformly (the
+    skewed tool popularity of the ablation study, which uses 1.1)."""
     rng = np.random.default_rng(seed)
     pages = _Pages(rng, num_slots, page_size)
     stok = rng.integers(0, vocab, size=sys_len).astype(np.int32)
@@ -257,10 +260,14 @@ def tool_use(seed=0, B=64, sys_len=1800, n_tools=16, tool_lo=200, tool_hi=600, e
         n = int(rng.integers(tool_lo, tool_hi + 1))
         tools.append((rng.integers(0, vocab, size=n).astype(np.int32), pages.take(n)))
     cached = [(np.concatenate([stok, t]), np.concatenate([sslot, s])) for t, s in tools]
-    which = rng.integers(0, n_tools, size=B)
+    if zipf > 0:
+        weight = np.arange(1, n_tools + 1, dtype=np.float64) ** -float(zipf)
+        which = rng.choice(n_tools, size=B, p=weight / weight.sum())
+    else:
+        which = rng.integers(0, n_tools, size=B)
     ext = rng.integers(ext_lo, ext_hi + 1, size=B)
     backed = _unique_slots([c[1] for c in cached])
-    return _finish("tool_use", dtype, Hq, Hkv, D, page_size, num_slots, vocab, rng, seed,
+    return _finish(name, dtype, Hq, Hkv, D, page_size, num_slots, vocab, rng, seed,
                    cached, [cached[int(w)] for w in which], ext, [set()] * B, pages, backed,
                    notes={"tool_of_request": which})
 
@@ -431,6 +438,7 @@ CONFIGS = {
     "agent_tree": agent_tree,
     "video_qa": video_qa,
     "programming": programming,
+    "tool_use_zipf": lambda seed=0: tool_use(seed, zipf=1.1, name="tool_use_zipf"),
 }
 
 
@@ -440,6 +448,9 @@ def small_variant(name: str, seed: int = 0) -> Workload:
     if name == "tool_use":
         return tool_use(seed, B=6, sys_len=333, n_tools=3, tool_lo=40, tool_hi=130, ext_lo=5, ext_hi=70,
                         Hq=8, Hkv=2, num_slots=4096)
+    if name == "tool_use_zipf":
+        return tool_use(seed, B=9, sys_len=333, n_tools=4, tool_lo=40, tool_hi=130, ext_lo=5, ext_hi=70,
+                        Hq=8, Hkv=2, num_slots=4096, zipf=1.1, name="tool_use_zipf")
     if name == "long_doc_qa":
         return long_doc_qa(seed, n_docs=2, per_doc=2, doc_len=1500, n_distract=3, ext_lo=3, ext_hi=40,
                            Hq=8, Hkv=2, num_slots=16384)
