@@ -91,8 +91,9 @@ def cpu_baseline(wl, budget_s=15.0):
 def extras(pa, g, wl, prefix_len, slot_idx, out, ws, main_k, nbytes):
     """Measurements beside the step: the extend-attention kernel with cold caches (1 GiB streamed through the
     chip between launches: the L2s and the memory-side cache hold none of the K/V when it starts), and the matcher
-    on a batch large enough to show its bandwidth (4,096 requests resampled from the workload's), and what it costs to
-    bring the tree's device mirror up to date after a small change."""
+    on a batch large enough to show its bandwidth (4,096 requests resampled from the workload's), what it costs to
+    bring the tree's device mirror up to date after a small change, and what the machine itself reaches on a plain
+    copy and on a loop of nothing but MFMAs (the published peaks are 8 TB/s and 2.5 PFLOP/s)."""
     import numpy as np
     import torch
     dev = g.tokens.device
@@ -113,6 +114,28 @@ def extras(pa, g, wl, prefix_len, slot_idx, out, ws, main_k, nbytes):
         ex["extend_cold_cache"] = {"avg_kernel_us": t * 1e6, "launches": n, "GBps_algorithmic": nbytes / t / 1e9,
                                    "hbm_frac": nbytes / t / 1e9 / HBM_PEAK_GBS, "flushed_bytes_between_launches": 1 << 30}
     del flush
+    # ---- what the machine reaches: a plain copy of 1 GiB, and a loop of nothing but bf16 MFMAs ----
+    src = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    cal = torch.zeros(1 << 16, dtype=torch.uint8, device=dev)
+    iters = 4096
+    for _ in range(2):
+        pa.calib_copy(dst, src)
+        flops = pa.calib_mfma(cal, iters)
+    pa.profile_enable(True)
+    for _ in range(5):
+        pa.calib_copy(dst, src)
+    for _ in range(5):
+        pa.calib_mfma(cal, iters)
+    torch.cuda.synchronize()
+    pa.profile_enable(False)
+    ms_c, n_c = pa.profile_read("calib_copy")
+    ms_m, n_m = pa.profile_read("calib_mfma")
+    cyc, ticks = cal[:16].view(torch.int64).tolist()
+    ex["achievable"] = {"copy_GBps": 2.0 * src.numel() / (ms_c / n_c * 1e-3) / 1e9, "copy_bytes_moved": 2 * src.numel(),
+                        "mfma_bf16_TFLOPs": flops / (ms_m / n_m * 1e-3) / 1e12, "mfma_flops_per_launch": flops,
+                        "mfma_shader_mhz": 100.0 * cyc / ticks if ticks else 0.0}
+    del src, dst
     # ---- matcher at a batch that fills the chip ----
     rng = np.random.default_rng(0)
     Bbig = 4096
@@ -317,6 +340,11 @@ def main():
         res["append_GBps"] = app_bytes / (kern["append_kv"]["avg_us"] * 1e-6) / 1e9
     if not args.no_extras and not args.only:
         res["extras"] = extras(pa, g, wl, prefix_len, slot_idx, out, ws, main_k, nbytes)
+        ach = res["extras"].get("achievable")
+        if ach and roofline and wl.dtype == "bf16":
+            # beside the fractions of the published peaks: of what a bare MFMA loop and a bare copy reach on this machine
+            roofline["compute_frac_of_mfma_loop"] = roofline["compute_frac"] * MFMA_BF16_PEAK_TFLOPS / ach["mfma_bf16_TFLOPs"]
+            roofline["hbm_frac_of_copy"] = roofline["hbm_frac"] * HBM_PEAK_GBS / ach["copy_GBps"]
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(res))

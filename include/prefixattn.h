@@ -317,7 +317,7 @@ int pa_gather_kv(const void* kv_pool, const int32_t* slots, int64_t n, int Hkv, 
  * records and starts recording, pa_profile_enable(0) stops.  pa_profile_read waits for the
  * recorded events and returns the summed device time (ms) and the number of launches of one
  * kernel, named "match_prefixes", "extend_plan", "extend_attention", "extend_merge",
- * "extend_attention_f32", "append_kv" or "gather_kv".  At most 65536 launches are recorded.
+ * "extend_attention_f32", "append_kv", "gather_kv", "calib_copy" or "calib_mfma".  At most 65536 launches are recorded.
  * --------------------------------------------------------------------------------- */
 int pa_profile_enable(int on);
 int pa_profile_read(const char* kernel, double* total_ms, int64_t* launches);
@@ -329,6 +329,17 @@ int pa_profile_read(const char* kernel, double* total_ms, int64_t* launches);
  * reset != 0 zeroes the counters; reset == 0 reads them: *shader_mhz = 100 * cycles / ticks, the clock
  * the kernel actually ran at (0 if nothing was recorded).  Synchronises the device. */
 int pa_profile_clock(void* workspace, int reset, double* shader_mhz);
+
+/* Calibration kernels, for benchmarks (not part of the method): what this GPU reaches on a plain streaming copy and on
+ * a loop of nothing but bf16 MFMAs, to set a kernel's distance from the published peaks against.  Both are
+ * asynchronous on the stream and are recorded by the per-kernel timing above as "calib_copy" and "calib_mfma".
+ * pa_calib_copy: dst[0..bytes) = src[0..bytes) (device pointers, 16-byte aligned, bytes a multiple of 16); it moves
+ * 2 * bytes.  pa_calib_mfma: 512 workgroups of four waves (two per compute unit) each run `iters` rounds of four
+ * independent 32x32x16 bf16 MFMAs per wave; *flops (host) receives the flops of the launch.  out: device, 16-byte
+ * aligned, at least 16,400 bytes; its first two 64-bit words receive the shader cycles and the ticks of the 100 MHz
+ * constant counter that one wave spent in its loop (clock in MHz = 100 * cycles / ticks).  PA_EINVAL on bad arguments. */
+int pa_calib_copy(void* dst, const void* src, size_t bytes, void* stream);
+int pa_calib_mfma(void* out, size_t out_bytes, int iters, int64_t* flops, void* stream);
 
 #ifdef __cplusplus
 }

@@ -64,6 +64,8 @@ _SIGS = {
     "pa_profile_enable": (_i, [_i]),
     "pa_profile_read": (_i, [C.c_char_p, C.POINTER(C.c_double), C.POINTER(_i64)]),
     "pa_profile_clock": (_i, [_vp, _i, C.POINTER(C.c_double)]),
+    "pa_calib_copy": (_i, [_vp, _vp, _sz, _vp]),
+    "pa_calib_mfma": (_i, [_vp, _sz, _i, C.POINTER(_i64), _vp]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _fn = getattr(_lib, _name)
@@ -398,6 +400,21 @@ def profile_clock(workspace: torch.Tensor, reset: bool = False) -> float:
     mhz = C.c_double(0.0)
     _check(_lib.pa_profile_clock(_ptr(workspace), 1 if reset else 0, C.byref(mhz)), "pa_profile_clock")
     return float(mhz.value)
+
+
+def calib_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    """dst = src by the library's plain streaming-copy kernel (uint8 tensors of equal size).  Asynchronous."""
+    assert dst.dtype == torch.uint8 and src.dtype == torch.uint8 and dst.numel() == src.numel()
+    _check(_lib.pa_calib_copy(_ptr(dst), _ptr(src), dst.numel(), _stream(stream)), "pa_calib_copy")
+
+
+def calib_mfma(out: torch.Tensor, iters: int, stream=None) -> int:
+    """One launch of the MFMA-only loop; -> its flops.  out: uint8 device tensor of >= 16,400 bytes whose first two
+    int64 receive (shader cycles, 100 MHz ticks) of one wave's loop.  Asynchronous."""
+    flops = _i64(0)
+    _check(_lib.pa_calib_mfma(_ptr(out), out.numel() * out.element_size(), int(iters), C.byref(flops), _stream(stream)),
+           "pa_calib_mfma")
+    return int(flops.value)
 
 
 def profile_read(kernel: str) -> Tuple[float, int]:

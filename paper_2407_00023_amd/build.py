@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libprefixattn.so")
-SOURCES = ["tree.cpp", "sched.cpp", "profile.cpp", "match.hip", "kvpool.hip", "extend.cpp", "extend_f32.hip", "extend_bf16.hip"]
+SOURCES = ["tree.cpp", "sched.cpp", "profile.cpp", "match.hip", "kvpool.hip", "extend.cpp", "extend_f32.hip", "extend_bf16.hip", "calib.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 code generation
          "-Wall", "-Wno-unused-function"]

@@ -103,7 +103,7 @@ __host__ __device__ inline int64_t pool_row(int64_t slot, int which, int g, int 
 constexpr size_t kClockProbeOffset = 128;
 bool prof_clock_enabled();
 
-enum ProfKernel { kProfMatch = 0, kProfPlan, kProfExtend, kProfMerge, kProfExtendF32, kProfAppend, kProfGather, kProfKernels };
+enum ProfKernel { kProfMatch = 0, kProfPlan, kProfExtend, kProfMerge, kProfExtendF32, kProfAppend, kProfGather, kProfCalibCopy, kProfCalibMfma, kProfKernels };
 bool prof_begin(int kernel, hipStream_t stream, size_t* slot);
 void prof_end(size_t slot, hipStream_t stream);
 struct ProfScope {

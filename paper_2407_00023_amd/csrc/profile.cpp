@@ -11,7 +11,7 @@ namespace pa {
 
 static const char* const kKernelNames[kProfKernels] = {"match_prefixes", "extend_plan",        "extend_attention",
                                                        "extend_merge",   "extend_attention_f32", "append_kv",
-                                                       "gather_kv"};
+                                                       "gather_kv",      "calib_copy",           "calib_mfma"};
 
 struct ProfRecord {
     hipEvent_t start, stop;

@@ -93,3 +93,8 @@ def test_size_queries_and_errors(pa):
     lib.pa_append_kv.argtypes = [C.c_void_p] * 4 + [C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int64, C.c_int, C.c_void_p]
     assert lib.pa_append_kv(None, None, None, None, 4, 8, 100, 16, 64, 1, None) == -1   # D unsupported
     assert lib.pa_append_kv(None, None, None, None, 0, 8, 128, 16, 64, 1, None) == 0    # empty append is a no-op
+    # the calibration kernels refuse bad arguments before any GPU call
+    lib.pa_calib_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    assert lib.pa_calib_copy(None, None, 1024, None) == -1
+    lib.pa_calib_mfma.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.POINTER(C.c_int64), C.c_void_p]
+    assert lib.pa_calib_mfma(None, 1 << 16, 16, None, None) == -1

@@ -821,3 +821,22 @@ def test_cache_loop_with_eviction(pa, gpu_device):
         oracle.append_kv(opk, opv, ns, k, v, "bf16")
     say(f"  cache loop: {evictions} evictions, worst max abs err over the rounds {worst:.3e}")
     assert evictions >= 2 and worst <= TOL["bf16"]
+
+
+@pytest.mark.gpu
+def test_calibration_kernels(pa, gpu_device):
+    """The two benchmark-support kernels: the copy copies, and the MFMA loop reports its work and a plausible clock."""
+    say("calibration kernels")
+    src = torch.randint(0, 256, (1 << 22,), dtype=torch.uint8, device=gpu_device)
+    dst = torch.zeros_like(src)
+    pa.calib_copy(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    cal = torch.zeros(1 << 16, dtype=torch.uint8, device=gpu_device)
+    flops = pa.calib_mfma(cal, 64)
+    torch.cuda.synchronize()
+    assert flops == 512 * 4 * 64 * 4 * 2 * 32 * 32 * 16
+    cycles, ticks = cal[:16].view(torch.int64).tolist()
+    assert cycles > 0 and ticks > 0 and 200.0 < 100.0 * cycles / ticks < 4000.0
+    with pytest.raises(Exception):
+        pa.calib_mfma(torch.zeros(64, dtype=torch.uint8, device=gpu_device), 64)  # output buffer too small
