@@ -431,6 +431,40 @@ def programming(seed=0, B=64, sys_len=1500, n_problems=6, n_new=3, prob_mean=237
                    notes={"new_problem": is_new, "problem_of_request": which})
 
 
+# --------------------------------------------------------------------------------------
+# decode-phase batch of the tool-use shape
+# --------------------------------------------------------------------------------------
+def decode(seed=0, B=256, sys_len=1800, n_tools=16, tool_lo=200, tool_hi=600, own_lo=51, own_hi=350,
+           Hq=32, Hkv=8, D=128, num_slots=262144, page_size=16, vocab=128256, dtype="bf16") -> Workload:
+    """A batch in the decoding phase: every request's prompt and the tokens it has generated so far are
+    cached (system prefix + one of n_tools tool prefixes, shared; then own_lo..own_hi tokens of its own: its
+    question and its output so far) and it brings ONE new token.  The tool-use shape (Table 1, first row:
+    43-token outputs behind 1,835-token prompts) in the phase the paper calls the decoding-phase unit
+    (Sec. 3.3)."""
+    rng = np.random.default_rng(seed)
+    pages = _Pages(rng, num_slots, page_size)
+    stok = rng.integers(0, vocab, size=sys_len).astype(np.int32)
+    sslot = pages.take(sys_len)
+    tools = []
+    for _ in range(n_tools):
+        n = int(rng.integers(tool_lo, tool_hi + 1))
+        tools.append((rng.integers(0, vocab, size=n).astype(np.int32), pages.take(n)))
+    which = rng.integers(0, n_tools, size=B)
+    cached, firsts = [], [set() for _ in range(n_tools)]
+    for r in range(B):
+        w = int(which[r])
+        n = int(rng.integers(own_lo, own_hi + 1))
+        own = rng.integers(0, vocab, size=n).astype(np.int32)
+        while int(own[0]) in firsts[w]:     # requests on one tool part ways at their first own token
+            own[0] = rng.integers(0, vocab)
+        firsts[w].add(int(own[0]))
+        cached.append((np.concatenate([stok, tools[w][0], own]), np.concatenate([sslot, tools[w][1], pages.take(n)])))
+    backed = _unique_slots([c[1] for c in cached])
+    return _finish("decode", dtype, Hq, Hkv, D, page_size, num_slots, vocab, rng, seed,
+                   cached, list(cached), np.ones(B, dtype=np.int64), [set()] * B, pages, backed,
+                   notes={"tool_of_request": which})
+
+
 CONFIGS = {
     "tiny_fp32": tiny_fp32,
     "tool_use": tool_use,
@@ -439,6 +473,7 @@ CONFIGS = {
     "video_qa": video_qa,
     "programming": programming,
     "tool_use_zipf": lambda seed=0: tool_use(seed, zipf=1.1, name="tool_use_zipf"),
+    "decode": decode,
 }
 
 
@@ -451,6 +486,9 @@ def small_variant(name: str, seed: int = 0) -> Workload:
     if name == "tool_use_zipf":
         return tool_use(seed, B=9, sys_len=333, n_tools=4, tool_lo=40, tool_hi=130, ext_lo=5, ext_hi=70,
                         Hq=8, Hkv=2, num_slots=4096, zipf=1.1, name="tool_use_zipf")
+    if name == "decode":
+        return decode(seed, B=11, sys_len=333, n_tools=3, tool_lo=40, tool_hi=130, own_lo=3, own_hi=90,
+                      Hq=8, Hkv=2, num_slots=8192)
     if name == "long_doc_qa":
         return long_doc_qa(seed, n_docs=2, per_doc=2, doc_len=1500, n_distract=3, ext_lo=3, ext_hi=40,
                            Hq=8, Hkv=2, num_slots=16384)

@@ -18,8 +18,8 @@ pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "radix_hand_example.txt")
-SMALL = ["tiny_fp32", "tool_use", "long_doc_qa", "agent_tree", "video_qa", "programming", "tool_use_zipf"]
-FULL = ["tool_use", "long_doc_qa", "agent_tree", "video_qa", "programming", "tool_use_zipf"]
+SMALL = ["tiny_fp32", "tool_use", "long_doc_qa", "agent_tree", "video_qa", "programming", "tool_use_zipf", "decode"]
+FULL = ["tool_use", "long_doc_qa", "agent_tree", "video_qa", "programming", "tool_use_zipf", "decode"]
 
 
 def say(*a):

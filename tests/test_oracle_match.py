@@ -113,7 +113,7 @@ def test_empty_tree_and_empty_prompts():
     assert list(pl) == [0, 0] and all(si == -1)
 
 
-@pytest.mark.parametrize("name", ["tiny_fp32", "tool_use", "long_doc_qa", "agent_tree", "video_qa", "programming", "tool_use_zipf"])
+@pytest.mark.parametrize("name", ["tiny_fp32", "tool_use", "long_doc_qa", "agent_tree", "video_qa", "programming", "tool_use_zipf", "decode"])
 def test_designed_prefix_small_variants(name):
     """Generators build prompts whose cached prefix is known by construction; the trie must
     find exactly that, and brute force over the raw cached list must agree."""
@@ -130,7 +130,7 @@ def test_designed_prefix_small_variants(name):
     assert int((wl.ext_len == (wl.offsets[1:] - wl.offsets[:-1]) - pl).all())
 
 
-@pytest.mark.parametrize("name", ["tool_use", "long_doc_qa", "agent_tree", "video_qa", "programming", "tool_use_zipf"])
+@pytest.mark.parametrize("name", ["tool_use", "long_doc_qa", "agent_tree", "video_qa", "programming", "tool_use_zipf", "decode"])
 def test_designed_prefix_full_configs(name):
     wl = W.CONFIGS[name]()
     tr = oracle.Trie()
