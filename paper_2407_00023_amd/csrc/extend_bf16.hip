@@ -79,6 +79,7 @@ struct ExtendPlan {
     int slots;       // workgroup slots per KV head
     int merge_cap;   // upper bound on the number of row tiles whose output rows are merged from partial results
     int pack;        // 1: left-over rows of requests with a common prefix may be packed (B <= kPackMax)
+    int tile_parts;  // parts of one row tile at most
     size_t off_order, off_tile, off_aux, off_member, off_item, off_split, off_part_o, off_part_ml, total;
 };
 
@@ -103,8 +104,11 @@ static ExtendPlan make_plan(int B, int64_t T, int64_t max_kv_len, int Hq, int Hk
     p.tiles_cap = static_cast<int>(est + B);  // (packing only lowers the number of tiles)
     p.slots = kWgSlots / Hkv > 0 ? kWgSlots / Hkv : 1;
     const int64_t by_rule = static_cast<int64_t>(p.slots) * kRounds + 1;                  // sum of (parts - 1) over the tiles
-    const int64_t per_tile = (max_kv_len / kKT) / kMinChunkTiles > 1 ? (max_kv_len / kKT) / kMinChunkTiles : 1;
-    const int64_t by_size = static_cast<int64_t>(p.tiles_cap) * (per_tile < kMaxParts ? per_tile : kMaxParts);
+    // (the key range of a shared tile holds the own keys of every member: of up to mt requests)
+    const int64_t longest = p.pack ? max_kv_len * (B < mt ? (B > 0 ? B : 1) : mt) : max_kv_len;
+    const int64_t per_tile = (longest / kKT) / kMinChunkTiles > 1 ? (longest / kKT) / kMinChunkTiles : 1;
+    p.tile_parts = static_cast<int>(per_tile < kMaxParts ? per_tile : kMaxParts);
+    const int64_t by_size = static_cast<int64_t>(p.tiles_cap) * p.tile_parts;
     p.items_cap = static_cast<int>(p.tiles_cap + (by_rule < by_size ? by_rule : by_size));
     const int64_t split_parts = 2 * by_rule < by_size ? 2 * by_rule : by_size;
     p.parts_cap = static_cast<int>(split_parts);
@@ -113,7 +117,7 @@ static ExtendPlan make_plan(int B, int64_t T, int64_t max_kv_len, int Hq, int Hk
     p.off_tile = p.off_order + up256(sizeof(int32_t) * (B > 0 ? B : 1));
     p.off_aux = p.off_tile + up256(sizeof(int4) * p.tiles_cap);
     p.off_member = p.off_aux + up256(sizeof(int4) * p.tiles_cap);
-    p.off_item = p.off_member + up256(sizeof(int4) * (B > 0 ? B : 1));
+    p.off_item = p.off_member + up256(sizeof(int4) * 2 * (B > 0 ? B : 1));
     p.off_split = p.off_item + up256(sizeof(int4) * 3 * p.items_cap);
     p.off_part_o = p.off_split + up256(sizeof(int32_t) * (p.merge_cap + 1));
     const size_t units = static_cast<size_t>(p.parts_cap) * Hkv;
@@ -167,31 +171,40 @@ __device__ __forceinline__ void block_scan(int (&v)[N], int (&total)[N], int (*s
 //   tile_tab[t] = (parts, index of its first partial result or -1, request, first packed row)
 //   tile_aux[t] = (kind, first member, members, rows of the group)               (shared tiles; zeros otherwise)
 //   item_tab[3 i ..] = (request, first packed row, first key, end key),
-//                      (partial index or -1: writes the output, prefix length, extend length or rows of the
-//                       group, first extend token), (first slot-list entry, tile, first member, members or 0)
-//   member_tab[m]   = (first row among the group's left-over rows, first extend token, first left-over row of the
-//                      request, extend length)
+//                      (partial index or -1: writes the output, prefix length or common part, extend length or rows
+//                       of the group, first extend token), (first slot-list entry, tile, first member, members or 0)
+//   member_tab[2 m]     = (first row among the group's left-over rows, first extend token, first left-over row of
+//                          the request, extend length)
+//   member_tab[2 m + 1] = (keys of its prefix past the group's common part, its first slot-list entry, own keys
+//                          (prefix part + extend tokens) of the group's members before it, 0)
 // Everything a workgroup of the attention kernel needs sits in its item record: one dependent load, not four.
 //
 // Kinds of row tile.  Whole: rows of one request over all its keys.  With packing (B <= kPackMax, tables in LDS): the
 // left-over rows of a request - those past its last full tile, fewer than a tile - cost a workgroup as much per
 // key tile as a full tile, so where two or more requests share their whole prefix (at least kPackMinPrefix keys)
 // their left-over rows are laid end to end and cut into shared tiles.  A shared tile walks the common prefix, every
-// key of it visible to every row, and then the extend tokens of each request that has rows in the tile, one
-// request's after the other's, visible to that request's rows only (and causally).  Its members are the
-// consecutive entries of member_tab whose rows meet the tile.
+// key of it visible to every row, and then the keys of each request that has rows in the tile, one request's
+// after the other's, visible to that request's rows only (and causally).  Its members are the consecutive
+// entries of member_tab whose rows meet the tile.
+// Requests may also share only the first part of their prefixes (a decode batch: a common system and tool prompt, then
+// tokens of each request's own).  Those whose rows make less than one tile, and whose whole prefix nobody shares, are
+// grouped by the deepest of kProbes evenly spaced depths at which another such request has the same slot (slots name
+// cached tokens: the same slot at a depth means the same tokens up to there); the group's common part is then
+// measured exactly, by bisection over the slot lists against the group's first member.  A member's own keys in a
+// shared tile are the rest of its prefix (pool rows through its own slot list) followed by its extend tokens.
 // ---------------------------------------------------------------------------------------
 constexpr int kTileWhole = 0, kTileShared = 1;
 
 struct TileDesc {
     int kind, r, row0, kv_lo, kv_end, rows_total;  // rows_total: rows of the request, or of the group (shared)
     int member0, n_members;                        // shared tiles: the entries of member_tab whose rows meet the tile
+    int common;                                    // shared tiles: keys that all members have in common
 };
 
 __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
     const int32_t* __restrict__ prefix_len, const int32_t* __restrict__ ext_len, const int32_t* __restrict__ ext_offsets,
     const int32_t* __restrict__ slot_offsets, const int32_t* __restrict__ slot_idx, int B, int G, int mt, int tiles_cap,
-    int items_cap, int parts_cap, int merge_cap, int slots, int pack, int32_t* __restrict__ hdr,
+    int items_cap, int parts_cap, int merge_cap, int slots, int pack, int tile_parts, int32_t* __restrict__ hdr,
     int32_t* __restrict__ order, int4* __restrict__ tile_tab, int4* __restrict__ tile_aux, int4* __restrict__ member_tab,
     int4* __restrict__ item_tab, int32_t* __restrict__ merge_tiles) {
     __shared__ int s_w[3][kPlanThreads / 64 + 1];
@@ -209,9 +222,13 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
     // ... and per group
     __shared__ int s_gn[kPackMax], s_gL[kPackMax];        // members, left-over rows
     __shared__ int s_gbase[kPackMax], s_gm0[kPackMax];    // rows / members of earlier groups
+    __shared__ int s_gown0[kPackMax];                     // own keys of the members of earlier groups
     // ... and per member (packed request)
-    __shared__ int s_mR[kPackMax], s_mE[kPackMax];        // first row among the group's left-over rows, extend length
-    __shared__ int s_carry;
+    __shared__ int s_mR[kPackMax], s_mE[kPackMax];        // first row among the group's left-over rows, keys of its own
+    // ... and per request (B <= kPackMax)
+    __shared__ int s_cut[kPackMax];                       // keys of its prefix that its group has in common
+    __shared__ int s_kstar[kPackMax], s_lead[kPackMax], s_lcp[kPackMax];
+    __shared__ int s_carry, s_maxP;
     const int tid = threadIdx.x;
     const bool staged = B <= kSortMax;
     auto P_of = [&](int r) { return staged ? s_P[r] : prefix_len[r]; };
@@ -231,6 +248,110 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
             s_grp[r] = P > 0 ? slot_idx[so + P - 1] : -1 - r;
         }
         __syncthreads();
+        if (pack && B <= kPackMax) {
+            // groups of requests that share the first part of their prefixes (see above); four threads per request
+            constexpr int kProbes = 12;
+            static_assert(kProbes * kPackMax <= kTileLds, "the probes borrow s_tpos");
+            int* s_probe = s_tpos;
+            const int r = tid >> 2, sub = tid & 3;
+            const bool on = r < B;
+            auto sum4 = [](int x) { x += __shfl_xor(x, 1); return x + __shfl_xor(x, 2); };
+            auto min4 = [](int x) { x = min(x, __shfl_xor(x, 1)); return min(x, __shfl_xor(x, 2)); };
+            auto or4 = [](int x) { x |= __shfl_xor(x, 1); return x | __shfl_xor(x, 2); };  // (over a request's four threads)
+            if (tid == 0) s_maxP = 0;
+            if (on && sub == 0) s_cut[r] = s_P[r];
+            __syncthreads();
+            int same = 0;
+            if (on)
+#pragma unroll 8
+                for (int q = sub; q < B; q += 4) same += s_grp[q] == s_grp[r];
+            same = sum4(same);
+            const bool cand = on && same == 1 && s_E[r] > 0 && s_E[r] * G < mt && s_P[r] >= kPackMinPrefix;
+            if (cand && sub == 0) atomicMax(&s_maxP, s_P[r]);
+            __syncthreads();
+            const int maxP = s_maxP;
+            if (maxP > 0) {  // (the same for every thread)
+                const int ps = kPackMinPrefix * ((maxP + kProbes * kPackMinPrefix - 1) / (kProbes * kPackMinPrefix));
+                if (on)
+                    for (int k = sub; k < kProbes; k += 4) {
+                        const int d = (k + 1) * ps;  // (who is no candidate, or shorter, matches nobody)
+                        s_probe[r * kProbes + k] = cand && d <= s_P[r] ? slot_idx[s_so[r] + d - 1] : -1 - r;
+                    }
+                __syncthreads();
+                // The deepest depth at which another candidate has the same slot.  Equal slots at a depth mean equal slots
+                // at every depth above it: another request only matters if it also matches at the first depth not
+                // matched so far.
+                int depths = 0;
+                if (cand)
+                    for (int q0 = sub; q0 < B; q0 += 32) {  // eight other requests at a time
+                        bool deeper = depths < kProbes;
+                        while (deeper) {
+                            const int mine = s_probe[r * kProbes + depths];
+                            deeper = false;
+#pragma unroll
+                            for (int u = 0; u < 8; ++u) {
+                                const int q = q0 + 4 * u;
+                                deeper |= q < B && q != r && s_probe[q * kProbes + depths] == mine;
+                            }
+                            depths += deeper;
+                            deeper = deeper && depths < kProbes;
+                        }
+                    }
+                depths = max(depths, __shfl_xor(depths, 1));
+                depths = max(depths, __shfl_xor(depths, 2));
+                const int kstar = depths - 1;
+                if (on && sub == 0) s_kstar[r] = kstar;
+                __syncthreads();
+                // the group: the candidates that chose this depth and have this slot there; its first member leads
+                int lead = B, members = 0;
+                if (kstar >= 0)
+#pragma unroll 8
+                    for (int q = sub; q < B; q += 4)
+                        if (s_kstar[q] == kstar && s_probe[q * kProbes + kstar] == s_probe[r * kProbes + kstar]) {
+                            lead = min(lead, q);
+                            ++members;
+                        }
+                lead = min4(lead);
+                members = sum4(members);
+                const bool grouped = kstar >= 0 && members >= 2;
+                int lcp = 0;
+                if (grouped) {
+                    // The slot lists agree on [0, lo); they differ at hi, or hi is where the shorter one (or the probe
+                    // interval) ends.  The request's four threads look at four places between lo and hi at once.
+                    const int d = (kstar + 1) * ps;
+                    int lo = d, hi = min(min(s_P[r], s_P[lead]), d + ps);
+                    const int32_t* a = slot_idx + s_so[r];
+                    const int32_t* b = slot_idx + s_so[lead];
+                    while (r != lead && lo < hi) {
+                        const int span = hi - lo;
+                        auto place = [&](int j) { return lo + static_cast<int>(static_cast<int64_t>(span) * (j + 1) / 5); };
+                        const int x = place(sub);  // lo <= x < hi
+                        const int first_off = __ffs(~or4((a[x] == b[x]) << sub) & 0xF) - 1;  // first place that differs, -1: none
+                        const int new_lo = first_off == 0 ? lo : place((first_off < 0 ? 4 : first_off) - 1) + 1;
+                        hi = first_off < 0 ? hi : place(first_off);
+                        lo = new_lo;
+                    }
+                    lcp = hi;
+                }
+                if (on && sub == 0) {
+                    s_lcp[r] = lcp;
+                    s_lead[r] = grouped ? lead : -1;
+                }
+                __syncthreads();
+                if (grouped) {
+                    int cut = 0x7fffffff;
+#pragma unroll 8
+                    for (int q = sub; q < B; q += 4)
+                        if (s_lead[q] == lead) cut = min(cut, s_lcp[q]);
+                    cut = min4(cut);
+                    if (sub == 0) {
+                        s_cut[r] = cut;
+                        s_grp[r] = -1 - B - lead;  // (no slot and no lone request has this key)
+                    }
+                }
+                __syncthreads();
+            }
+        }
         // tpr threads per request r, each over its share of the other requests q
         const int tpr = max(1, kPlanThreads / B);
         const int r = tid / tpr, q_first = tid % tpr;
@@ -292,25 +413,28 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
             int v[1] = {head ? 1 : 0}, total[1];
             block_scan<1>(v, total, s_w);
             const int gid = v[0] + (head ? 1 : 0) - 1;  // (block_scan ends with a barrier: the zeros above are in place)
-            const bool cand = on && left > 0 && P >= kPackMinPrefix;
+            const int cut = on ? s_cut[r] : 0;  // (the whole prefix, unless the group shares only a first part of it)
+            const bool cand = on && left > 0 && cut >= kPackMinPrefix;
             if (on) s_gid[tid] = gid;
             if (cand) atomicAdd(&s_gn[gid], 1);
             __syncthreads();
             const bool packed = cand && s_gn[gid] >= 2;
             packed_me = packed;
-            int v2[2] = {packed ? left : 0, packed ? 1 : 0}, total2[2];
-            block_scan<2>(v2, total2, s_w);
+            int v2[3] = {packed ? left : 0, packed ? 1 : 0, packed ? P - cut + E : 0}, total2[3];
+            block_scan<3>(v2, total2, s_w);
             if (head) {
                 s_gbase[gid] = v2[0];
                 s_gm0[gid] = v2[1];
+                s_gown0[gid] = v2[2];
             }
             if (packed) atomicAdd(&s_gL[gid], left);
             __syncthreads();
             if (on) s_R[tid] = packed ? v2[0] - s_gbase[gid] : -1;
             if (packed) {
-                member_tab[v2[1]] = make_int4(v2[0] - s_gbase[gid], s_e0[r], full * mt, E);
+                member_tab[2 * v2[1]] = make_int4(v2[0] - s_gbase[gid], s_e0[r], full * mt, E);
+                member_tab[2 * v2[1] + 1] = make_int4(P - cut, s_so[r], v2[2] - s_gown0[gid], 0);
                 s_mR[v2[1]] = v2[0] - s_gbase[gid];
-                s_mE[v2[1]] = E;
+                s_mE[v2[1]] = P - cut + E;
             }
             if (head && s_gn[gid] >= 2) nshared = (s_gL[gid] + mt - 1) / mt;
             if (on) s_nshared[tid] = nshared;
@@ -372,12 +496,13 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
                     ka = s_mR[m0 + k] <= d.row0 ? k : ka;
                     kb = s_mR[m0 + k] <= row_end - 1 ? k : kb;
                 }
-                int ext = 0;
-                for (int k = ka; k <= kb; ++k) ext += s_mE[m0 + k];
+                int own = 0;
+                for (int k = ka; k <= kb; ++k) own += s_mE[m0 + k];
                 d.member0 = m0 + ka;
                 d.n_members = kb - ka + 1;
                 d.kv_lo = 0;
-                d.kv_end = P + ext;
+                d.common = s_cut[r];
+                d.kv_end = d.common + own;
                 return d;
             }
             j -= nshared;
@@ -406,9 +531,13 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
     // cost of a tile = its key tiles + a fixed overhead; thread i owns tiles [i * per, (i + 1) * per)
     const int per = (n_tiles + kPlanThreads - 1) / kPlanThreads;
     const int t_lo = min(n_tiles, tid * per), t_hi = min(n_tiles, t_lo + per);
+    // (the three passes below look at the same tiles; the first of a thread's - with up to 1,024 tiles its only one -
+    // is worked out once)
+    const TileDesc d_first = t_lo < t_hi ? describe(t_lo) : TileDesc{};
+    auto tile_desc = [&](int t) { return t == t_lo ? d_first : describe(t); };
     int my_cost = 0;
     for (int t = t_lo; t < t_hi; ++t) {
-        const TileDesc d = describe(t);
+        const TileDesc d = tile_desc(t);
         my_cost += (d.kv_end - d.kv_lo + kKT - 1) / kKT + kItemOverhead;
     }
     int W;
@@ -423,13 +552,13 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
     const float target = fmaxf(static_cast<float>(W) / static_cast<float>(slots * kRounds), 1.f);
     auto parts_of = [&](int K) {
         int n = static_cast<int>(static_cast<float>(K + kItemOverhead) / target + 0.5f);
-        n = min(min(n, K / kMinChunkTiles), kMaxParts);
+        n = min(min(n, K / kMinChunkTiles), tile_parts);
         return max(n, 1);
     };
     // a tile's output rows come from partial results, joined by the merge kernel, if it is split
     int my_items = 0, my_parts = 0, my_merge = 0;
     for (int t = t_lo; t < t_hi; ++t) {
-        const TileDesc d = describe(t);
+        const TileDesc d = tile_desc(t);
         const int n = parts_of((d.kv_end - d.kv_lo + kKT - 1) / kKT);
         my_items += n;
         my_parts += n > 1 ? n : 0;
@@ -442,7 +571,7 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
     // (by the bounds the capacities were sized from this cannot happen; an empty list makes it visible: no output)
     const bool overflow = n_items > items_cap || total3[1] > parts_cap || n_merge > merge_cap;
     for (int t = t_lo; t < t_hi && !overflow; ++t) {
-        const TileDesc d = describe(t);
+        const TileDesc d = tile_desc(t);
         const int K = (d.kv_end - d.kv_lo + kKT - 1) / kKT;
         const int n = parts_of(K);
         const bool partial = n > 1;
@@ -452,7 +581,7 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
         const int r = d.r;
         const int e0 = staged ? s_e0[r] : ext_offsets[r];
         const int slot_off = staged ? s_so[r] : slot_offsets[r];
-        const int P = P_of(r);
+        const int P = d.kind == kTileShared ? d.common : P_of(r);
         const int e_or_rows = d.kind == kTileShared ? d.rows_total : E_of(r);
         for (int j = 0; j < n; ++j) {
             const int lo = d.kv_lo + static_cast<int>(static_cast<int64_t>(K) * j / n) * kKT;
@@ -582,10 +711,11 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     const int slot_off = rec2.x;
     const int row0 = rec0.y, kv_lo = rec0.z, kv_hi = rec0.w;
     const int part = rec1.x;  // index of this item's partial result; -1: the item covers all keys and writes the output
-    const int P = rec1.y;
+    const int P = rec1.y;  // keys of the prefix; in a shared tile: of the part of it that all members have in common
     const int G = Hq / Hkv;
-    // a shared tile: left-over rows of n_members requests with this prefix, laid end to end; after the prefix keys
-    // come the members' extend tokens, member after member
+    // a shared tile: left-over rows of n_members requests with this prefix, laid end to end; after the common keys
+    // come the members' own: the rest of a member's prefix (if the group shares only a first part), then its extend
+    // tokens; member after member
     const int member0 = __builtin_amdgcn_readfirstlane(rec2.z), n_members = __builtin_amdgcn_readfirstlane(rec2.w);
     const bool shared = n_members > 0;
     const int rows_total = shared ? rec1.z : rec1.z * G;
@@ -608,6 +738,29 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     int vis_lo[RB];              // ... except, in a shared tile, the other members' extend tokens [P, vis_lo)
     int64_t e0_row[RB];          // first extend token of the row's request
     int blk_vis_min[RB];         // every row of the block sees keys [.., this)
+    bool own_prefix = false;     // shared tile: some member has prefix keys of its own (uniform)
+    // the members of a shared tile: where a member's own keys begin on the tile's key axis (and, one past the last
+    // member, where they end), how many of them are prefix keys, its first slot-list entry, its first extend token
+    // counted from this item's
+    // (behind the K/V ring in the dynamic LDS, which thereby keeps its alignment)
+    int* const s_mseg = reinterpret_cast<int*>(smem + kStages * STAGEB);
+    int* const s_mown = s_mseg + (MT + 1);
+    int* const s_mso = s_mown + MT;
+    int* const s_mx0 = s_mso + MT;
+    int* const s_wave_own = s_mx0 + MT;  // per wave: the key range that holds the own keys of its rows' members; then
+                                         // one flag: some member has prefix keys of its own
+    if (shared) {
+        if (tid < n_members) {  // (a member has at least one row in the tile: there are at most MT)
+            const int4 mem = member_tab[2 * (member0 + tid)], aux = member_tab[2 * (member0 + tid) + 1];
+            const int at = P + aux.z - member_tab[2 * member0 + 1].z;
+            s_mseg[tid] = at;
+            s_mown[tid] = aux.x;
+            s_mso[tid] = aux.y;
+            s_mx0[tid] = mem.y - static_cast<int>(rec1.w);
+            if (tid == n_members - 1) s_mseg[n_members] = at + aux.x + mem.w;
+        }
+        __syncthreads();
+    }
     bf16x8 qreg[RB][KS];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -615,24 +768,26 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
         row_ok[rb] = rho < rows_total;
         e0_row[rb] = e0;
         vis_lo[rb] = P;
+        int own_row = 0;  // prefix keys of the row's request past the common part
         if (shared) {
             // whose row this is: the last member that starts at or before it; its place in that request; where
             // that member's extend tokens begin on the tile's key axis
-            const int want = row_ok[rb] ? rho : member_tab[member0].x;
-            int seg = P;
+            const int want = row_ok[rb] ? rho : member_tab[2 * member0].x;
             for (int k = 0; k < n_members; ++k) {
-                const int4 mem = member_tab[member0 + k];  // (same address in every lane)
+                const int4 mem = member_tab[2 * (member0 + k)];  // (same address in every lane)
+                const int own = s_mown[k];
+                own_prefix |= own > 0;
                 if (mem.x <= want) {
                     e0_row[rb] = mem.y;
                     rho = mem.z + (want - mem.x);
-                    vis_lo[rb] = seg;
+                    vis_lo[rb] = s_mseg[k];
+                    own_row = own;
                 }
-                seg += mem.w;
             }
         }
         qi[rb] = row_ok[rb] ? rho / G : 0;
         qh[rb] = g * G + (row_ok[rb] ? rho % G : 0);
-        vis_end[rb] = min(kv_hi, vis_lo[rb] + qi[rb] + 1);
+        vis_end[rb] = min(kv_hi, vis_lo[rb] + own_row + qi[rb] + 1);
         blk_vis_min[rb] = shared ? min(kv_hi, P) : min(kv_hi, P + (row0 + wave * WR + rb * 32) / G + 1);
         const uint4* qp = reinterpret_cast<const uint4*>(q_ext + ((e0_row[rb] + qi[rb]) * Hq + qh[rb]) * static_cast<int64_t>(D));
 #pragma unroll
@@ -642,6 +797,29 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
             qreg[rb][s] = __builtin_bit_cast(bf16x8, v);
         }
     }
+
+    // In a shared tile the keys past the common part concern one member each: the wave skips the arithmetic of a tile
+    // that holds no key of the members its rows belong to (uniform over the wave).
+    if (shared) {
+        int wave_own_lo = 0x7fffffff, wave_own_hi = 0;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            wave_own_lo = min(wave_own_lo, vis_lo[rb]);
+            wave_own_hi = max(wave_own_hi, vis_end[rb]);
+        }
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            wave_own_lo = min(wave_own_lo, __shfl_xor(wave_own_lo, off));
+            wave_own_hi = max(wave_own_hi, __shfl_xor(wave_own_hi, off));
+        }
+        if (lane == 0) {  // (kept in LDS, not in registers: read only in the own-key part of a shared tile)
+            s_wave_own[2 * wave] = wave_own_lo;
+            s_wave_own[2 * wave + 1] = wave_own_hi;
+            if (wave == 0) s_wave_own[2 * NW] = own_prefix;
+        }
+        __syncthreads();
+    }
+    auto has_own_prefix = [&]() __attribute__((always_inline)) { return shared && s_wave_own[2 * NW] != 0; };
 
     // ---- global -> LDS tile loads.  Wave w fills blocks w * UPW + u: rows blk * RPB + lane / CPR, and the
     // lane lands on chunk position lane % CPR of its row.
@@ -656,12 +834,26 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     const unsigned smem_addr = __builtin_amdgcn_readfirstlane(lds_address(smem));
     int32_t sl_next[UPW];  // pool slots of the rows this lane loads in the tile after the one in flight
 
+    // (first member of a shared tile whose own keys reach the tile asked for; the tiles are asked for in order)
+    int cur_member = 0;
+    auto member_at = [&](int cur, int p) __attribute__((always_inline)) {  // the member whose own keys hold key p >= P
+        int k = cur;
+        while (k + 1 < n_members && p >= s_mseg[k + 1]) ++k;
+        return k;
+    };
     auto load_slots = [&](int p0) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < UPW; ++u) {
             // positions past the end of the key range repeat the last valid one (see issue_tile)
             const int p = min(p0 + (wave * UPW + u) * RPB + ld_rowl, kv_hi - 1);
-            sl_next[u] = p < P ? slots[p] : 0;
+            int32_t sl = p < P ? slots[p] : 0;
+            if (p >= P && has_own_prefix()) {
+                // a key of some member's own: of its prefix (then its slot comes from its own list) or an extend token
+                const int k = member_at(cur_member, p);  // (slots are asked for ahead of the tile being issued)
+                const int q = p - s_mseg[k];
+                if (q < s_mown[k]) sl = slot_idx[s_mso[k] + P + q];
+            }
+            sl_next[u] = sl;
         }
     };
     // Byte offset, inside its K (V) row, of the 16 bytes this lane fetches for block u.  Block u of the wave holds
@@ -676,23 +868,23 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     // values that the mask zeroes).  Page sizes are powers of two (checked on the host).
     auto issue = [&](int p0, int ring) __attribute__((always_inline)) {
         const unsigned sk = __builtin_amdgcn_readfirstlane(smem_addr + ring * STAGEB);  // wave-uniform (goes to M0)
+        if (shared)
+            while (cur_member + 1 < n_members && s_mseg[cur_member + 1] <= p0) ++cur_member;
 #pragma unroll
         for (int u = 0; u < UPW; ++u) {
             const int blk = wave * UPW + u;
             const int p = min(p0 + blk * RPB + ld_rowl, kv_hi - 1);
-            const bool ext = p >= P;
+            bool ext = p >= P;
             const unsigned sl = static_cast<unsigned>(min(max(sl_next[u], 0), num_slots - 1));  // never outside the pool
             const size_t pool_off = static_cast<size_t>(sl >> page_shift) * page_stride +
                                     (sl & static_cast<unsigned>(page_size - 1)) * static_cast<unsigned>(ROWB);
             int64_t xrow = p - P;  // extend token, counted from the first one of the request of this item
             if (shared && ext) {
                 // the member whose extend tokens hold key p, and that token relative to e0
-                int seg = P;
-                for (int k = 0; k < n_members; ++k) {
-                    const int4 mem = member_tab[member0 + k];
-                    if (p >= seg) xrow = (static_cast<int64_t>(mem.y) - e0) + (p - seg);
-                    seg += mem.w;
-                }
+                const int k = member_at(cur_member, p);
+                const int q = p - s_mseg[k], own = s_mown[k];
+                xrow = static_cast<int64_t>(s_mx0[k]) + (q - own);
+                ext = q >= own;  // (a member's own prefix keys are pool rows: their slots were fetched by load_slots)
             }
             const size_t off = ext ? static_cast<size_t>(xrow) * x_stride : pool_off;
             const unsigned char* ka = (ext ? kx_g : pool_g) + off + ld_koff(u);
@@ -828,7 +1020,8 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
             issue(p0 + kKT, ring ^ 1);  // the next tile flies during this tile's arithmetic
             load_slots(p0 + 2 * kKT);
         }
-        if (wave_on && p0 <= P + wave_i_last) {
+        const bool not_ours = shared && p0 >= P && (p0 >= s_wave_own[2 * wave + 1] || p0 + kKT <= s_wave_own[2 * wave]);
+        if (wave_on && p0 <= P + wave_i_last && !not_ours) {
             bool need_mask = false;
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) need_mask |= p0 + kKT > blk_vis_min[rb];
@@ -845,7 +1038,8 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
         for (int rb = 0; rb < RB; ++rb) no_mask &= p0 + kKT <= blk_vis_min[rb];
         if (!(wave_on && p0 <= P + wave_i_last && no_mask)) return 0;
         const int first = min(p0 + kKT, kv_hi - 1), last = min(p0 + 2 * kKT - 1, kv_hi - 1);
-        return last < P ? 1 : first >= P ? 2 : 0;
+        // (after the common keys of a shared tile come several requests' keys: never one run of extend tokens)
+        return last < P ? 1 : (first >= P && !shared) ? 2 : 0;
     };
 
     // ---- prologue: first tile into ring slot 0 ----
@@ -933,6 +1127,13 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
                                       k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
                                       uni_ptr(kx_g), uni_ptr(vx_g), c, c2);
                 if (((p0 - p_start) / kKT) & 1) move_read_addresses(ring_start);
+                // (the run fetched slot ids from the common list only: where the tile they are for holds a member's own
+                // prefix keys they are fetched again, from that member's list.  That tile is the next one, or, if the
+                // run was left inside a tile - the next one's loads are in flight then - the one after it.)
+                if (has_own_prefix()) {
+                    const int pn = p0 + (st == 0 ? kKT : 2 * kKT);
+                    if (pn + kKT > P) load_slots(pn);
+                }
                 if (st == 0) continue;
                 // the tile outgrew the maximum: the general code does what is left of it, and stays (rare enough)
                 from = st - 1;
@@ -1016,7 +1217,7 @@ __global__ __launch_bounds__(256) void extend_merge_kernel(const int32_t* __rest
         int rho = row0 + lrow;
         if (shared) {
             for (int k = 0; k < aux.z; ++k) {
-                const int4 mem = member_tab[aux.y + k];
+                const int4 mem = member_tab[2 * (aux.y + k)];
                 if (mem.x <= row0 + lrow) {
                     e0 = mem.y;
                     rho = mem.z + (row0 + lrow - mem.x);
@@ -1056,7 +1257,8 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
                          const int32_t* hdr, const int4* tile_tab, const int4* tile_aux, const int4* member_tab,
                          const int4* item_tab, const int32_t* merge_tiles, float* part_o, float* part_ml,
                          unsigned long long* clk, hipStream_t stream) {
-    constexpr size_t lds_bytes = static_cast<size_t>(kStages) * 2 * kKT * D * 2;
+    // the K/V ring, and behind it the table of a shared tile's members (4 ints each, one int more) and 2 ints per wave + 1
+    constexpr size_t lds_bytes = static_cast<size_t>(kStages) * 2 * kKT * D * 2 + (4 * 32 * RB * NW + 1 + 2 * NW + 1) * sizeof(int);
     int page_shift = -1;
     if ((page_size & (page_size - 1)) == 0) {
         page_shift = 0;
@@ -1125,7 +1327,7 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
     {
         ProfScope prof(kProfPlan, stream);
         hipLaunchKernelGGL(extend_plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, prefix_len, ext_len, ext_offsets, slot_offsets, slot_idx, B,
-                           G, 32 * p.rb * p.nw, p.tiles_cap, p.items_cap, p.parts_cap, p.merge_cap, p.slots, p.pack, hdr, order,
+                           G, 32 * p.rb * p.nw, p.tiles_cap, p.items_cap, p.parts_cap, p.merge_cap, p.slots, p.pack, p.tile_parts, hdr, order,
                            tile_tab, tile_aux, member_tab, item_tab, merge_tiles);
     }
     if (D == 64)

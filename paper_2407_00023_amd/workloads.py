@@ -434,11 +434,11 @@ def programming(seed=0, B=64, sys_len=1500, n_problems=6, n_new=3, prob_mean=237
 # --------------------------------------------------------------------------------------
 # decode-phase batch of the tool-use shape
 # --------------------------------------------------------------------------------------
-def decode(seed=0, B=256, sys_len=1800, n_tools=16, tool_lo=200, tool_hi=600, own_lo=51, own_hi=350,
+def decode(seed=0, B=256, sys_len=1800, n_tools=16, tool_lo=200, tool_hi=600, own_lo=51, own_hi=350, ext=1,
            Hq=32, Hkv=8, D=128, num_slots=262144, page_size=16, vocab=128256, dtype="bf16") -> Workload:
     """A batch in the decoding phase: every request's prompt and the tokens it has generated so far are
     cached (system prefix + one of n_tools tool prefixes, shared; then own_lo..own_hi tokens of its own: its
-    question and its output so far) and it brings ONE new token.  The tool-use shape (Table 1, first row:
+    question and its output so far) and it brings `ext` new tokens (one).  The tool-use shape (Table 1, first row:
     43-token outputs behind 1,835-token prompts) in the phase the paper calls the decoding-phase unit
     (Sec. 3.3)."""
     rng = np.random.default_rng(seed)
@@ -461,7 +461,7 @@ def decode(seed=0, B=256, sys_len=1800, n_tools=16, tool_lo=200, tool_hi=600, ow
         cached.append((np.concatenate([stok, tools[w][0], own]), np.concatenate([sslot, tools[w][1], pages.take(n)])))
     backed = _unique_slots([c[1] for c in cached])
     return _finish("decode", dtype, Hq, Hkv, D, page_size, num_slots, vocab, rng, seed,
-                   cached, list(cached), np.ones(B, dtype=np.int64), [set()] * B, pages, backed,
+                   cached, list(cached), np.full(B, int(ext), dtype=np.int64), [set()] * B, pages, backed,
                    notes={"tool_of_request": which})
 
 

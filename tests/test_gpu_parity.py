@@ -493,6 +493,41 @@ def test_extend_packs_leftover_rows_of_requests_with_a_common_prefix(pa, gpu_dev
     assert err <= TOL[wl.dtype]
 
 
+@pytest.mark.parametrize("case", ["one_trunk", "two_levels", "exact_multiple", "long_own_parts", "three_tokens"])
+def test_extend_shares_tiles_between_requests_with_a_common_first_part(pa, gpu_device, case):
+    """Decode-shaped batches: every request has prefix keys of its own behind a part it shares with others.  Requests
+    with the same first part are packed into shared row tiles that walk the common keys once and then every member's
+    own (rest of its prefix from the pool through its own slot list, then its new tokens): every element against the
+    oracle, and fewer tiles than requests."""
+    say(f"[case] common first part, {case}")
+    kw = dict(Hq=8, Hkv=2, num_slots=16384)
+    if case == "one_trunk":        # one tool: a common part of sys + tool, found by bisection between two probe depths
+        wl = W.decode(1, B=9, sys_len=600, n_tools=1, tool_lo=77, tool_hi=77, own_lo=1, own_hi=120, **kw)
+    elif case == "two_levels":     # three tools behind one system prompt
+        wl = W.decode(2, B=14, sys_len=700, n_tools=3, tool_lo=150, tool_hi=500, own_lo=3, own_hi=90, **kw)
+    elif case == "exact_multiple":  # the common part ends on a probe depth and on a tile boundary
+        wl = W.decode(3, B=7, sys_len=1000, n_tools=1, tool_lo=24, tool_hi=24, own_lo=1, own_hi=70, **kw)
+    elif case == "long_own_parts":  # own parts of several tiles, shared tiles split into parts
+        wl = W.decode(4, B=12, sys_len=640, n_tools=2, tool_lo=10, tool_hi=40, own_lo=200, own_hi=900, **kw)
+    else:                          # three new tokens per request instead of one
+        wl = W.decode(5, B=10, sys_len=800, n_tools=2, tool_lo=100, tool_hi=300, own_lo=1, own_hi=200, ext=3, **kw)
+    g, o = GpuSide(wl, gpu_device), OracleSide(wl)
+    pl, si = g.match()
+    nbytes = pa.extend_workspace_bytes(wl.B, wl.T, g.max_kv_len, wl.Hq, wl.Hkv, wl.D, g.tdtype)
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device=gpu_device)
+    out = g.extend(pl, si, workspace=ws)
+    torch.cuda.synchronize()
+    n_tiles, n_items, n_merge, overflow = ws[:16].view(torch.int32).tolist()
+    say(f"  {wl.B} requests, tiles {n_tiles}, items {n_items}, merged tiles {n_merge}")
+    assert overflow == 0 and n_tiles < wl.B
+    pl_ref, si_ref = o.match()
+    assert_match_equal(wl, pl, si, pl_ref, si_ref)
+    ref = o.extend(pl_ref, si_ref)
+    err = np.abs(out_to_f64(out) - ref).max()
+    say(f"  max abs err {err:.3e}")
+    assert err <= TOL[wl.dtype]
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_extend_random_shapes_against_the_oracle(pa, gpu_device, seed):
     """Small batches of random shape - head counts, head size, page size, number of requests, how many share a
