@@ -281,7 +281,12 @@ int pa_match_prefixes(const pa_tree* tree, const int32_t* tokens, const int32_t*
  *
  * q_ext        [T, Hq, D]   k_ext, v_ext  [T, Hkv, D]   out [T, Hq, D]   (dtype elements)
  * kv_pool      pool written by pa_append_kv with the same Hkv, D, dtype, page_size, num_slots
- * slot_idx, slot_offsets   as produced by pa_match_prefixes (slot_offsets = its offsets)
+ * slot_idx, slot_offsets   as produced by pa_match_prefixes (slot_offsets = its offsets).  Slot lists name
+ *                cached tokens of one prefix tree: two requests have the same slot at a position only if
+ *                they have the same slots at every earlier position (the bf16 path groups requests that
+ *                share a prefix, or a first part of it, by comparing slots; lists that break this give
+ *                unspecified results for the requests concerned).  Lists built by hand from a request's
+ *                own slots (chunked prefill: cached prefix + its earlier chunks) keep it.
  * prefix_len, ext_len      int32 [B];  ext_offsets int32 [B + 1], ext_offsets[B] = T
  * T, max_kv_len  HOST values: total extend tokens, and an upper bound on
  *                prefix_len[r] + ext_len[r] (used to size the launch; a request exceeding
