@@ -289,9 +289,10 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
                             const int mine = s_probe[r * kProbes + depths];
                             deeper = false;
 #pragma unroll
-                            for (int u = 0; u < 8; ++u) {
+                            for (int u = 0; u < 8; ++u) {  // (loads first, all of them; then the tests)
                                 const int q = q0 + 4 * u;
-                                deeper |= q < B && q != r && s_probe[q * kProbes + depths] == mine;
+                                const int theirs = s_probe[min(q, B - 1) * kProbes + depths];
+                                deeper |= (q < B) & (q != r) & (theirs == mine);
                             }
                             depths += deeper;
                             deeper = deeper && depths < kProbes;
@@ -304,13 +305,15 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
                 __syncthreads();
                 // the group: the candidates that chose this depth and have this slot there; its first member leads
                 int lead = B, members = 0;
-                if (kstar >= 0)
+                if (kstar >= 0) {
+                    const int mine = s_probe[r * kProbes + kstar];
 #pragma unroll 8
-                    for (int q = sub; q < B; q += 4)
-                        if (s_kstar[q] == kstar && s_probe[q * kProbes + kstar] == s_probe[r * kProbes + kstar]) {
-                            lead = min(lead, q);
-                            ++members;
-                        }
+                    for (int q = sub; q < B; q += 4) {
+                        const bool with_me = (s_kstar[q] == kstar) & (s_probe[q * kProbes + kstar] == mine);
+                        lead = with_me ? min(lead, q) : lead;
+                        members += with_me;
+                    }
+                }
                 lead = min4(lead);
                 members = sum4(members);
                 const bool grouped = kstar >= 0 && members >= 2;
@@ -341,8 +344,10 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
                 if (grouped) {
                     int cut = 0x7fffffff;
 #pragma unroll 8
-                    for (int q = sub; q < B; q += 4)
-                        if (s_lead[q] == lead) cut = min(cut, s_lcp[q]);
+                    for (int q = sub; q < B; q += 4) {
+                        const int theirs = s_lcp[q];
+                        cut = s_lead[q] == lead ? min(cut, theirs) : cut;
+                    }
                     cut = min4(cut);
                     if (sub == 0) {
                         s_cut[r] = cut;
