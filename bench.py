@@ -29,8 +29,8 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3
 # HBM bytes per launch of the extend-attention kernel, measured with rocprofv3 --pmc: FETCH_SIZE x 1.984 +
 # WRITE_SIZE x 1.000 (KiB), the factors being what the same counters read for append_kv, a plain copy of
 # known size; the runs are summarised in profiles/extend_attention_<workload>.md.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"tool_use": 246_820_946, "agent_tree": 3_189_850_325, "long_doc_qa": 937_641_675,
-                          "video_qa": 415_963_927, "programming": 309_799_688}
+MEASURED_TRAFFIC_BYTES = {"tool_use": 250_993_555, "agent_tree": 3_260_208_858, "long_doc_qa": 959_303_610,
+                          "video_qa": 448_674_680, "programming": 310_043_768, "decode": 392_904_743}
 
 
 def algorithmic_work(wl, prefix_len):
