@@ -752,8 +752,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     int* const s_mown = s_mseg + (MT + 1);
     int* const s_mso = s_mown + MT;
     int* const s_mx0 = s_mso + MT;
-    int* const s_wave_own = s_mx0 + MT;  // per wave: the key range that holds the own keys of its rows' members; then
-                                         // one flag: some member has prefix keys of its own
+    int* const s_wave_own = s_mx0 + MT;  // per wave: the key range that holds the own keys of its rows' members
     if (shared) {
         if (tid < n_members) {  // (a member has at least one row in the tile: there are at most MT)
             const int4 mem = member_tab[2 * (member0 + tid)], aux = member_tab[2 * (member0 + tid) + 1];
@@ -817,14 +816,12 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
             wave_own_lo = min(wave_own_lo, __shfl_xor(wave_own_lo, off));
             wave_own_hi = max(wave_own_hi, __shfl_xor(wave_own_hi, off));
         }
-        if (lane == 0) {  // (kept in LDS, not in registers: read only in the own-key part of a shared tile)
+        if (lane == 0) {  // (kept in LDS, not in registers: read, by this wave only, in the own-key part of a shared tile)
             s_wave_own[2 * wave] = wave_own_lo;
             s_wave_own[2 * wave + 1] = wave_own_hi;
-            if (wave == 0) s_wave_own[2 * NW] = own_prefix;
         }
-        __syncthreads();
     }
-    auto has_own_prefix = [&]() __attribute__((always_inline)) { return shared && s_wave_own[2 * NW] != 0; };
+    auto has_own_prefix = [&]() __attribute__((always_inline)) { return own_prefix; };
 
     // ---- global -> LDS tile loads.  Wave w fills blocks w * UPW + u: rows blk * RPB + lane / CPR, and the
     // lane lands on chunk position lane % CPR of its row.
@@ -1262,8 +1259,8 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
                          const int32_t* hdr, const int4* tile_tab, const int4* tile_aux, const int4* member_tab,
                          const int4* item_tab, const int32_t* merge_tiles, float* part_o, float* part_ml,
                          unsigned long long* clk, hipStream_t stream) {
-    // the K/V ring, and behind it the table of a shared tile's members (4 ints each, one int more) and 2 ints per wave + 1
-    constexpr size_t lds_bytes = static_cast<size_t>(kStages) * 2 * kKT * D * 2 + (4 * 32 * RB * NW + 1 + 2 * NW + 1) * sizeof(int);
+    // the K/V ring, and behind it the table of a shared tile's members (4 ints each, one int more) and 2 ints per wave
+    constexpr size_t lds_bytes = static_cast<size_t>(kStages) * 2 * kKT * D * 2 + (4 * 32 * RB * NW + 1 + 2 * NW) * sizeof(int);
     int page_shift = -1;
     if ((page_size & (page_size - 1)) == 0) {
         page_shift = 0;

@@ -460,8 +460,11 @@ def decode(seed=0, B=256, sys_len=1800, n_tools=16, tool_lo=200, tool_hi=600, ow
         firsts[w].add(int(own[0]))
         cached.append((np.concatenate([stok, tools[w][0], own]), np.concatenate([sslot, tools[w][1], pages.take(n)])))
     backed = _unique_slots([c[1] for c in cached])
+    # (a pair (lo, hi) draws the number of new tokens per request; the default draws nothing, so the default batch
+    # stays what it was)
+    ext_lens = rng.integers(ext[0], ext[1] + 1, size=B) if isinstance(ext, tuple) else np.full(B, int(ext), dtype=np.int64)
     return _finish("decode", dtype, Hq, Hkv, D, page_size, num_slots, vocab, rng, seed,
-                   cached, list(cached), np.full(B, int(ext), dtype=np.int64), [set()] * B, pages, backed,
+                   cached, list(cached), ext_lens, [set()] * B, pages, backed,
                    notes={"tool_of_request": which})
 
 

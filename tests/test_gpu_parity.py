@@ -528,6 +528,38 @@ def test_extend_shares_tiles_between_requests_with_a_common_first_part(pa, gpu_d
     assert err <= TOL[wl.dtype]
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_extend_random_decode_batches_against_the_oracle(pa, gpu_device, seed):
+    """Random batches of requests with prefix keys of their own behind a shared part: how long the shared levels are
+    (below and above the 512 keys that grouping asks for), how many second-level prefixes, how long the own parts, one
+    to forty new tokens per request (so that some requests have more than a tile of rows and stay out of the groups),
+    head counts and page size - every element against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    Hkv = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([1, 4, 8]))
+    wl = W.decode(seed, B=int(rng.integers(2, 25)), sys_len=int(rng.choice([100, 500, 511, 512, 640, 1500])),
+                  n_tools=int(rng.integers(1, 5)), tool_lo=1, tool_hi=int(rng.choice([2, 60, 700])), own_lo=1,
+                  own_hi=int(rng.choice([1, 30, 300])), ext=(1, int(rng.choice([1, 3, 40]))), Hq=Hkv * G, Hkv=Hkv,
+                  num_slots=32768, page_size=int(rng.choice([1, 16, 64])))
+    say(f"[case] random decode batch, seed {seed}: B {wl.B}, Hq {wl.Hq}, Hkv {wl.Hkv}, page {wl.page_size}, "
+        f"prefixes {wl.designed_prefix_len.min()}..{wl.designed_prefix_len.max()}, new tokens {wl.ext_len.min()}..{wl.ext_len.max()}")
+    g, o = GpuSide(wl, gpu_device), OracleSide(wl)
+    pl, si = g.match()
+    nbytes = pa.extend_workspace_bytes(wl.B, wl.T, g.max_kv_len, wl.Hq, wl.Hkv, wl.D, g.tdtype)
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device=gpu_device)
+    out = g.extend(pl, si, workspace=ws)
+    torch.cuda.synchronize()
+    n_tiles, n_items, n_merge, overflow = ws[:16].view(torch.int32).tolist()
+    say(f"  tiles {n_tiles}, items {n_items}, merged {n_merge}")
+    assert overflow == 0
+    pl_ref, si_ref = o.match()
+    assert_match_equal(wl, pl, si, pl_ref, si_ref)
+    ref = o.extend(pl_ref, si_ref)
+    err = np.abs(out_to_f64(out) - ref).max()
+    say(f"  max abs err {err:.3e}")
+    assert err <= TOL[wl.dtype]
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_extend_random_shapes_against_the_oracle(pa, gpu_device, seed):
     """Small batches of random shape - head counts, head size, page size, number of requests, how many share a
