@@ -65,6 +65,9 @@ constexpr int kTileLds = 3072;           // up to this many row tiles the planne
 constexpr int kPackMax = 256;            // batches of up to this many requests pack the left-over rows of requests
                                          // that share their prefix into common row tiles
 constexpr int kPackMinPrefix = 512;      // ... if the shared prefix has at least this many keys
+constexpr int kPackOwnCost = 2;          // ... and the members' own keys, which a shared tile walks in the general tile
+                                         // for the few rows that see them, cost less than walking the prefix per member:
+                                         // this factor x their sum <= (members - 1) x the shared prefix
 constexpr float kRescaleThreshold = 8.f; // log2 units: the running maximum may lag the true one by this much
 // The steady-state tiles (fast_run_*.inc) never move the running maximum: a run is left, for the general tile, when
 // the probabilities of one lane and key block sum to more than 2^40.  The exponent range of fp32 and bf16 leaves that
@@ -414,6 +417,7 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
             if (tid < kPackMax) {
                 s_gn[tid] = 0;
                 s_gL[tid] = 0;
+                s_gown0[tid] = 0;  // (first the sum of the group's own keys, later those of the groups before it)
             }
             int v[1] = {head ? 1 : 0}, total[1];
             block_scan<1>(v, total, s_w);
@@ -421,9 +425,14 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
             const int cut = on ? s_cut[r] : 0;  // (the whole prefix, unless the group shares only a first part of it)
             const bool cand = on && left > 0 && cut >= kPackMinPrefix;
             if (on) s_gid[tid] = gid;
-            if (cand) atomicAdd(&s_gn[gid], 1);
+            if (cand) {
+                atomicAdd(&s_gn[gid], 1);
+                atomicAdd(&s_gown0[gid], P - cut + E);
+            }
             __syncthreads();
-            const bool packed = cand && s_gn[gid] >= 2;
+            // (requests with long extends behind a short common prefix stay on their own)
+            const bool packed = cand && s_gn[gid] >= 2 &&
+                                static_cast<int64_t>(kPackOwnCost) * s_gown0[gid] <= static_cast<int64_t>(s_gn[gid] - 1) * cut;
             packed_me = packed;
             int v2[3] = {packed ? left : 0, packed ? 1 : 0, packed ? P - cut + E : 0}, total2[3];
             block_scan<3>(v2, total2, s_w);
@@ -513,15 +522,20 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
             j -= nshared;
             d.rows_total = rows;
             d.kv_lo = 0;
-            if (j < full) {  // the request's last rows - the most keys - first
-                d.kind = kTileWhole;
-                d.row0 = (full - 1 - j) * mt;
-                d.kv_end = P + (d.row0 + mt - 1) / G + 1;
-                return d;
+            d.kind = kTileWhole;
+            // the request's last rows - the most keys - first: its left-over rows, if they were not packed, then the
+            // full tiles from the last one down
+            const bool own_left = rows > full * mt && !(packing && s_R[pos] >= 0);
+            if (own_left) {
+                if (j == 0) {
+                    d.row0 = full * mt;
+                    d.kv_end = P + (rows - 1) / G + 1;
+                    return d;
+                }
+                --j;
             }
-            d.kind = kTileWhole;  // left-over rows that were not packed
-            d.row0 = full * mt;
-            d.kv_end = P + (rows - 1) / G + 1;
+            d.row0 = (full - 1 - j) * mt;
+            d.kv_end = P + (d.row0 + mt - 1) / G + 1;
             return d;
         }
         const int4 tt = tile_tab[t];
@@ -551,12 +565,13 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
         block_scan<1>(v, total, s_w);
         W = total[0];
     }
-    // parts of a tile: its cost over the target cost of an item, rounded; never below kMinChunkTiles key tiles per
-    // part.  Summed over the tiles, parts - 1 stays below W / target = slots * kRounds (a tile of cost c adds at most
-    // c / target - 1/2), which is what the capacities are sized for.
+    // parts of a tile: its cost over the target cost of an item, rounded up from a quarter past a whole number (an item
+    // of 1.5 targets at the end of the list is a tail of its own); never below kMinChunkTiles key tiles per part.
+    // Summed over the tiles, parts - 1 stays below W / target = slots * kRounds (a tile of cost c adds at most
+    // c / target - 1/4), which is what the capacities are sized for.
     const float target = fmaxf(static_cast<float>(W) / static_cast<float>(slots * kRounds), 1.f);
     auto parts_of = [&](int K) {
-        int n = static_cast<int>(static_cast<float>(K + kItemOverhead) / target + 0.5f);
+        int n = static_cast<int>(static_cast<float>(K + kItemOverhead) / target + 0.75f);
         n = min(min(n, K / kMinChunkTiles), tile_parts);
         return max(n, 1);
     };

@@ -504,11 +504,12 @@ def test_extend_shares_tiles_between_requests_with_a_common_first_part(pa, gpu_d
     if case == "one_trunk":        # one tool: a common part of sys + tool, found by bisection between two probe depths
         wl = W.decode(1, B=9, sys_len=600, n_tools=1, tool_lo=77, tool_hi=77, own_lo=1, own_hi=120, **kw)
     elif case == "two_levels":     # three tools behind one system prompt
-        wl = W.decode(2, B=14, sys_len=700, n_tools=3, tool_lo=150, tool_hi=500, own_lo=3, own_hi=90, **kw)
+        wl = W.decode(2, B=14, sys_len=700, n_tools=3, tool_lo=400, tool_hi=900, own_lo=3, own_hi=90, **kw)
     elif case == "exact_multiple":  # the common part ends on a probe depth and on a tile boundary
         wl = W.decode(3, B=7, sys_len=1000, n_tools=1, tool_lo=24, tool_hi=24, own_lo=1, own_hi=70, **kw)
     elif case == "long_own_parts":  # own parts of several tiles, shared tiles split into parts
-        wl = W.decode(4, B=12, sys_len=640, n_tools=2, tool_lo=10, tool_hi=40, own_lo=200, own_hi=900, **kw)
+        wl = W.decode(4, B=12, sys_len=4000, n_tools=2, tool_lo=10, tool_hi=40, own_lo=200, own_hi=900,
+                      **dict(kw, num_slots=32768))
     else:                          # three new tokens per request instead of one
         wl = W.decode(5, B=10, sys_len=800, n_tools=2, tool_lo=100, tool_hi=300, own_lo=1, own_hi=200, ext=3, **kw)
     g, o = GpuSide(wl, gpu_device), OracleSide(wl)
