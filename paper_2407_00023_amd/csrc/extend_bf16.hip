@@ -878,8 +878,15 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     // u (V); for D = 64 (rows 16 w + 8 u + lane / 8) by an XOR with 4 u (K) or 2 u (V).
     const unsigned ld_koff0 = (ld_pos ^ swz_k<D>(wave * UPW * RPB + ld_rowl)) * 16;
     const unsigned ld_voff0 = (ld_pos ^ swz_v<D>(wave * UPW * RPB + ld_rowl)) * 16;
-    auto ld_koff = [&](int u) __attribute__((always_inline)) { return ld_koff0 ^ (64u * u); };
-    auto ld_voff = [&](int u) __attribute__((always_inline)) { return ld_voff0 ^ ((D == 128 ? 16u : 32u) * u); };
+    // (Worked out where they are used, from a value the compiler cannot see through: left to itself it keeps all eight
+    // of them as 64-bit addends, spills them, and each reload waits for the tile load issued just before it - eight
+    // loads in a row, one memory round trip each.)
+    auto opaque = [](unsigned x) __attribute__((always_inline)) {
+        asm volatile("" : "+v"(x));
+        return x;
+    };
+    auto ld_koff = [&](int u) __attribute__((always_inline)) { return opaque(ld_koff0) ^ (64u * u); };
+    auto ld_voff = [&](int u) __attribute__((always_inline)) { return opaque(ld_voff0) ^ ((D == 128 ? 16u : 32u) * u); };
     // The next tile's loads, general: every lane takes its row from the pool (through the slot prefetched for it) or
     // from the extend tensors, by position; rows past the end of the key range repeat the last valid row (finite
     // values that the mask zeroes).  Page sizes are powers of two (checked on the host).
