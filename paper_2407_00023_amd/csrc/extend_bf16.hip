@@ -1251,12 +1251,14 @@ __global__ __launch_bounds__(256) void extend_merge_kernel(const int32_t* __rest
             e0 = ext_offsets[tt.z];
         }
         float m = -INFINITY;
+#pragma unroll 8
         for (int s = 0; s < n_parts; ++s) {
             const size_t at = (static_cast<size_t>(part0 + s) * Hkv + g) * mt + lrow;
             m = fmaxf(m, part_ml[at * 2]);
         }
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         float l = 0.f;
+#pragma unroll 4
         for (int s = 0; s < n_parts; ++s) {
             const size_t at = (static_cast<size_t>(part0 + s) * Hkv + g) * mt + lrow;
             const float2 ml = reinterpret_cast<const float2*>(part_ml)[at];
