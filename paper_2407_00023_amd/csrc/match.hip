@@ -79,6 +79,8 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
     __shared__ int32_t s_es[kWinP];      // index of the candidate's first edge token
     __shared__ int16_t s_list[kWinP];    // window positions of candidates compared by 16 lanes
     __shared__ int16_t s_list2[kWinP];   // ... by one wave
+    __shared__ int s_live[3];             // pointer doubling: does any position still reach another (round mod 3: the
+                                          // flag of a round is cleared two barriers after its last reader)
     __shared__ int16_t s_jump[kWinP];    // position reached from a window position after 2^round valid hops, -1 = none
     __shared__ uint8_t s_mark[kWinP];    // 1 = the position starts a node on the prompt's path
     __shared__ int32_t s_wmax[kWaves];
@@ -279,21 +281,27 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
                 s_jump[rel] = static_cast<int16_t>(link);
                 s_mark[rel] = rel == 0 ? 1 : 0;
             }
+            if (threadIdx.x == 0) s_live[0] = 0;
             lds_barrier();
 #pragma unroll 1
             for (int round = 0; round < 11; ++round) {  // 2^11 = kWinP hops at most
                 int32_t jj[kPos];
+                bool live = false;  // some position of this thread still reaches another one
 #pragma unroll
                 for (int i = 0; i < kPos; ++i) {
                     const int rel = rel0 + i;
                     const int32_t j = s_jump[rel];
                     if (j >= 0 && s_mark[rel]) s_mark[j] = 1;
                     jj[i] = j >= 0 ? s_jump[j] : -1;
+                    live |= jj[i] >= 0;
                 }
+                if (threadIdx.x == 0) s_live[(round + 1) % 3] = 0;
                 lds_barrier();
 #pragma unroll
                 for (int i = 0; i < kPos; ++i) s_jump[rel0 + i] = static_cast<int16_t>(jj[i]);
+                if (live) s_live[round % 3] = 1;
                 lds_barrier();
+                if (!s_live[round % 3]) break;  // every chain has run off its end: nothing is left to mark
             }
         }
         // ---- E. slots of the matched positions: position i belongs to the last path node starting at or before it ----
