@@ -230,9 +230,10 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
                 const int32_t lim = min(s_rec[rel].z, n - (w0 + rel));
                 bool bad[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int32_t k = sub + 16 * u;
-                    bad[u] = k < lim && t.edge_tok[es + k] != prompt[w0 + rel + k];
+                for (int u = 0; u < 4; ++u) {  // (all loads go out before the first comparison: one round trip, not four)
+                    const int32_t k = sub + 16 * u, kk = min(k, lim - 1);
+                    const int32_t a = t.edge_tok[es + kk], b = prompt[w0 + rel + kk];
+                    bad[u] = (k < lim) & (a != b);
                 }
                 int32_t m = lim;
 #pragma unroll
@@ -251,8 +252,9 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
                     bool bad[kWideUnroll];
 #pragma unroll
                     for (int u = 0; u < kWideUnroll; ++u) {
-                        const int32_t k = c0 + 64 * u + lane;
-                        bad[u] = k < lim && t.edge_tok[es + k] != prompt[w0 + rel + k];
+                        const int32_t k = c0 + 64 * u + lane, kk = min(k, lim - 1);
+                        const int32_t a = t.edge_tok[es + kk], b = prompt[w0 + rel + kk];
+                        bad[u] = (k < lim) & (a != b);
                     }
                     int32_t first = -1;
 #pragma unroll
