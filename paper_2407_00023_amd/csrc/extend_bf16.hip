@@ -372,6 +372,7 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
         __syncthreads();
         if (on) {
             int gk = -1;
+#pragma unroll 8
             for (int q = q_first; q < B; q += tpr) {
                 const int kq = s_key[q], gq = s_grp[q];
                 gk = max(gk, gq == grp ? kq : -1);
@@ -382,6 +383,7 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
         int rank = 0;
         if (on) {
             const int gk = s_gkey[r];
+#pragma unroll 8
             for (int q = q_first; q < B; q += tpr) {
                 const int kq = s_key[q], gq = s_grp[q], gkq = s_gkey[q];
                 // (group keys, group, keys, index) of q sorts before that of r: more keys first, lower ids first
@@ -604,8 +606,9 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
         const int P = d.kind == kTileShared ? d.common : P_of(r);
         const int e_or_rows = d.kind == kTileShared ? d.rows_total : E_of(r);
         for (int j = 0; j < n; ++j) {
-            const int lo = d.kv_lo + static_cast<int>(static_cast<int64_t>(K) * j / n) * kKT;
-            const int hi = min(d.kv_end, d.kv_lo + static_cast<int>(static_cast<int64_t>(K) * (j + 1) / n) * kKT);
+            // (K < 2^24 key tiles and n <= 64 parts: the products fit 32 bits)
+            const int lo = d.kv_lo + static_cast<int>(static_cast<unsigned>(K) * static_cast<unsigned>(j) / static_cast<unsigned>(n)) * kKT;
+            const int hi = min(d.kv_end, d.kv_lo + static_cast<int>(static_cast<unsigned>(K) * static_cast<unsigned>(j + 1) / static_cast<unsigned>(n)) * kKT);
             int4* rec = item_tab + 3 * static_cast<size_t>(item0 + j);
             rec[0] = make_int4(r, d.row0, lo, hi);
             rec[1] = make_int4(partial ? part0 + j : -1, P, e_or_rows, e0);
