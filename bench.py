@@ -29,8 +29,8 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3
 # HBM bytes per launch of the extend-attention kernel, measured with rocprofv3 --pmc: FETCH_SIZE x 1.984 +
 # WRITE_SIZE x 1.000 (KiB), the factors being what the same counters read for append_kv, a plain copy of
 # known size; the runs are summarised in profiles/extend_attention_<workload>.md.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"tool_use": 198_347_013, "agent_tree": 2_422_883_467, "long_doc_qa": 846_093_494,
-                          "video_qa": 313_947_227, "programming": 259_820_888, "decode": 348_959_289}
+MEASURED_TRAFFIC_BYTES = {"tool_use": 198_302_353, "agent_tree": 2_422_883_467, "long_doc_qa": 846_093_494,
+                          "video_qa": 314_095_251, "programming": 259_820_888, "decode": 348_881_083}
 
 
 def algorithmic_work(wl, prefix_len):
