@@ -4,12 +4,15 @@
 One step = one pass of the whole path over one synthetic batch already resident in HBM:
 match_prefixes -> extend_attention -> append_kv.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload tool_use]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload agent_tree]
 
-value      extend (newly prefilled) tokens per second over the whole step
+value      extend (newly prefilled) tokens per second over the whole step, on --workload (default: agent_tree,
+           the largest of the configurations: 128 requests, 74 k new tokens, 2.9 TFLOP of attention)
 roofline   the extend-attention kernel against the roof that binds it for this workload:
            algorithmic bytes or flops per launch / average kernel time from HIP events
-cpu_baseline  the CPU oracle, as it stands, on a bounded sample of the same workload
+configs    the same measurement, shorter, on each of the four bf16 configurations (tool use, long-document QA,
+           agent tree, video QA): step time, per-kernel times, both roofline fractions
+cpu_baseline  the CPU oracle, as it stands, on a bounded sample of the headline workload
 """
 import argparse
 import json
@@ -18,17 +21,18 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
-for p in (ROOT, os.path.join(ROOT, "tests")):
-    if p not in sys.path:
-        sys.path.insert(0, p)
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16
 FP32_VECTOR_PEAK_TFLOPS = 157.3
+BF16_CONFIGS = ["tool_use", "long_doc_qa", "agent_tree", "video_qa"]
 
-# HBM bytes per launch of the extend-attention kernel, measured with rocprofv3 --pmc: FETCH_SIZE x 1.984 +
-# WRITE_SIZE x 1.000 (KiB), the factors being what the same counters read for append_kv, a plain copy of
-# known size; the runs are summarised in profiles/extend_attention_<workload>.md.  None = not measured.
+# HBM bytes per launch of the extend-attention kernel, measured with rocprofv3 --pmc in runs of their own (a counter
+# run cannot share a process with the timed one): FETCH_SIZE x the factor that the same counter shows for append_kv, a
+# plain copy of known size, + WRITE_SIZE x its factor (KiB).  The runs are summarised in
+# profiles/extend_attention_<workload>.md, which is the source named beside each figure.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {"tool_use": 198_302_353, "agent_tree": 2_422_883_467, "long_doc_qa": 846_093_494,
                           "video_qa": 314_095_251, "programming": 259_820_888, "decode": 348_881_083}
 
@@ -52,24 +56,34 @@ def algorithmic_work(wl, prefix_len):
     return kv_bytes + slot_bytes + io_bytes, flops
 
 
+def workspace_traffic(wl, hdr):
+    """Bytes the launch moves through its workspace beyond the algorithmic ones: every part of a row tile whose key
+    range was split writes fp32 partial outputs and (maximum, sum) for its 128 rows and every KV head, and the merge
+    kernel reads them back (counted with all 128 rows of a tile in use).  hdr = (row tiles, items, tiles merged)."""
+    n_tiles, n_items, n_merge = hdr[:3]
+    split_items = n_items - (n_tiles - n_merge)
+    return 2 * split_items * wl.Hkv * 128 * (wl.D + 2) * 4
+
+
 def cpu_baseline(wl, budget_s=15.0):
     """The oracle on the first n requests of the workload (all of their rows), n chosen so that the
     attention part takes about budget_s."""
-    import numpy as np
-
     import oracle
-    from harness import OracleSide
-    o = OracleSide(wl)
+    trie = oracle.Trie()
+    for i in range(wl.n_cached):
+        trie.insert(*wl.cached_seq(i))
+    pool_k, pool_v = oracle.new_pool(wl.num_slots, wl.Hkv, wl.D, wl.dtype)
+    oracle.append_kv(pool_k, pool_v, wl.pool_slots, wl.pool_k, wl.pool_v, wl.dtype)
     cores = int(os.environ.get("OMP_NUM_THREADS", 0)) or (os.cpu_count() or 1)
     t0 = time.perf_counter()
-    pl, si = o.match()
+    pl, si = trie.match(wl.tokens, wl.offsets)
     t_match = time.perf_counter() - t0
 
     def run(n):
         eo = wl.ext_offsets[:n + 1]
         T = int(eo[-1])
         t = time.perf_counter()
-        oracle.extend_attention(wl.q_ext[:T], wl.k_ext[:T], wl.v_ext[:T], o.pool_k, o.pool_v, si, wl.offsets[:n + 1],
+        oracle.extend_attention(wl.q_ext[:T], wl.k_ext[:T], wl.v_ext[:T], pool_k, pool_v, si, wl.offsets[:n + 1],
                                 pl[:n], wl.ext_len[:n], eo, wl.scale, wl.dtype)
         return time.perf_counter() - t, T
 
@@ -80,11 +94,11 @@ def cpu_baseline(wl, budget_s=15.0):
     else:
         t_att, Tn = t1, T1
     t = time.perf_counter()
-    oracle.append_kv(o.pool_k, o.pool_v, wl.new_slots[:Tn], wl.k_ext[:Tn], wl.v_ext[:Tn], wl.dtype)
+    oracle.append_kv(pool_k, pool_v, wl.new_slots[:Tn], wl.k_ext[:Tn], wl.v_ext[:Tn], wl.dtype)
     t_app = time.perf_counter() - t
     total = t_match * n / wl.B + t_att + t_app
     return {"value": Tn / total, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"first {n} of {wl.B} requests ({Tn} extend tokens, all heads): trie match {t_match * n / wl.B:.3f}s "
+            "sample": f"first {n} of {wl.B} requests ({Tn} of {wl.T} extend tokens, all heads): trie match {t_match * n / wl.B:.3f}s "
                       f"(whole batch {t_match:.3f}s, {wl.B / t_match:.0f} req/s), fp64 attention {t_att:.2f}s, append {t_app:.4f}s"}
 
 
@@ -162,7 +176,6 @@ def extras(pa, g, wl, prefix_len, slot_idx, out, ws, main_k, nbytes):
         ex["match_scaled"] = {"requests": Bbig, "avg_kernel_us": t * 1e6, "reqs_per_s": Bbig / t, "matched_tokens_per_s": matched / t,
                               "GBps": 16.0 * matched / t / 1e9, "bytes_per_matched_token": 16}
     # ---- tree mirror: an upload after one small change, and one that copies the whole flat form ----
-    import time
     vocab_hi = int(wl.tokens.max()) + 1 if wl.tokens.size else 1
 
     def timed_uploads(n_up):
@@ -190,33 +203,17 @@ def extras(pa, g, wl, prefix_len, slot_idx, out, ws, main_k, nbytes):
     return ex
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="tool_use", choices=["tiny_fp32", "tool_use", "long_doc_qa", "agent_tree", "video_qa", "programming", "tool_use_zipf", "decode"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="skip the cold-cache and the scaled-matcher measurements")
-    ap.add_argument("--only", default="", help="time only one call of the path: match | extend | append (for profiling)")
-    ap.add_argument("--graph", action="store_true", help="replay one captured HIP graph per step instead of launching its calls "
-                    "from the host (measured: no faster, the gaps between the dependent kernels are not host-bound)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (the path has no cross-GPU step); use --gpus 1", file=sys.stderr)
-        sys.exit(2)
-
-    import numpy as np
+def measure(name, steps, warmup, args, with_extras):
+    """All GPU measurements of one workload.  -> (result dict, the workload)."""
     import torch
 
-    from harness import GpuSide
     from paper_2407_00023_amd import binding as pa
     from paper_2407_00023_amd import workloads as W
+    from paper_2407_00023_amd.resident import ResidentWorkload
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU; there is no CPU fallback"
     dev = torch.device("cuda:0")
-    wl = W.CONFIGS[args.workload]()
-    g = GpuSide(wl, dev)
+    wl = W.CONFIGS[name]()
+    g = ResidentWorkload(wl, dev)
     tdt = g.tdtype
     # every buffer of the step is allocated once, outside the timed region
     prefix_len = torch.empty(wl.B, dtype=torch.int32, device=dev)
@@ -265,33 +262,36 @@ def main():
         except Exception as e:  # capture not possible here: fall back to host launches, and say so
             print(f"bench.py: graph capture unavailable ({e}); timing eager launches", file=sys.stderr)
             torch.cuda.synchronize()
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         launch()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         launch()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
+    ms_per_step = dt / steps * 1e3
 
     # same steps again with the library's per-kernel event timing switched on
     pa.profile_enable(True)
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     pa.profile_enable(False)
     kern = {}
-    for name in ("match_prefixes", "extend_plan", "extend_attention", "extend_merge", "extend_attention_f32", "append_kv"):
-        ms, n = pa.profile_read(name)
+    for kname in ("match_prefixes", "extend_plan", "extend_attention", "extend_merge", "extend_attention_f32", "append_kv"):
+        ms, n = pa.profile_read(kname)
         if n:
-            kern[name] = {"avg_us": ms / n * 1e3, "launches_per_step": n / args.steps}
+            kern[kname] = {"avg_us": ms / n * 1e3, "launches_per_step": n / steps}
     shader_mhz = 0.0
+    hdr = None
     if wl.dtype == "bf16":
+        pa.extend_status(ws)  # (raises if the work list of the launches above did not fit)
+        hdr = ws[:16].view(torch.int32).tolist()
         # a few more steps with the clock probe in the kernel, kept out of the times above
         pa.profile_clock(ws, reset=True)
         pa.profile_enable(True, clock_probe=True)
-        for _ in range(min(args.steps, 20)):
+        for _ in range(min(steps, 20)):
             step()
         torch.cuda.synchronize()
         pa.profile_enable(False)
@@ -312,9 +312,16 @@ def main():
         else:
             roofline = {"bound": "alu" if wl.dtype == "f32" else "mfma", "achieved": tfs, "peak": peak_f, "unit": "TFLOP/s",
                         "frac": tfs / peak_f}
-        roofline.update({"traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "kernel": main_k,
-                         "avg_kernel_us": kern[main_k]["avg_us"], "algorithmic_bytes": nbytes, "algorithmic_flops": flops,
-                         "hbm_frac": gbs / HBM_PEAK_GBS, "compute_frac": tfs / peak_f})
+        traffic = MEASURED_TRAFFIC_BYTES.get(name)
+        roofline.update({"traffic": traffic,
+                         "traffic_source": f"profiles/extend_attention_{name}.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, runs of their own)" if traffic else None,
+                         "kernel": main_k, "avg_kernel_us": kern[main_k]["avg_us"], "algorithmic_bytes": nbytes,
+                         "algorithmic_flops": flops, "hbm_frac": gbs / HBM_PEAK_GBS, "compute_frac": tfs / peak_f})
+        if hdr is not None:
+            # traffic through the workspace (partial results of split row tiles, written by the attention kernel and
+            # read back by the merge kernel): not part of algorithmic_bytes, shown beside it
+            roofline["workspace_bytes"] = workspace_traffic(wl, hdr)
+            roofline["work_list"] = {"row_tiles": hdr[0], "items": hdr[1], "tiles_merged_from_parts": hdr[2]}
         if shader_mhz > 0 and wl.dtype == "bf16":
             # the clock the kernel ran at (shader cycles against the 100 MHz constant counter, across the key loop of a
             # few workgroups), and the matrix peak at that clock: 2.5 PFLOP/s is quoted at 2,400 MHz
@@ -322,10 +329,9 @@ def main():
             roofline["compute_frac_at_measured_clock"] = tfs / (peak_f * shader_mhz / 2400.0)
 
     res = {
-        "metric": "extend_prefill_tokens_per_s", "value": wl.T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": args.workload, "requests": wl.B, "extend_tokens": wl.T, "prompt_tokens": int(wl.offsets[-1]),
+        "value": wl.T / (ms_per_step * 1e-3), "ms_per_step": ms_per_step, "steps": steps, "warmup": warmup,
+        "dtype": wl.dtype,
+        "config": {"workload": name, "requests": wl.B, "extend_tokens": wl.T, "prompt_tokens": int(wl.offsets[-1]),
                    "Hq": wl.Hq, "Hkv": wl.Hkv, "D": wl.D, "page_size": wl.page_size, "num_slots": wl.num_slots,
                    "cached_sequences": wl.n_cached, "only": args.only or "whole path", "launch": mode},
         "prompt_tokens_per_s": int(wl.offsets[-1]) / (ms_per_step * 1e-3),
@@ -338,13 +344,67 @@ def main():
         el = 4 if wl.dtype == "f32" else 2
         app_bytes = 2 * (2 * wl.T * wl.Hkv * wl.D * el) + 4 * wl.T   # K and V rows read and written, slot ids read
         res["append_GBps"] = app_bytes / (kern["append_kv"]["avg_us"] * 1e-6) / 1e9
-    if not args.no_extras and not args.only:
+    if with_extras:
         res["extras"] = extras(pa, g, wl, prefix_len, slot_idx, out, ws, main_k, nbytes)
         ach = res["extras"].get("achievable")
         if ach and roofline and wl.dtype == "bf16":
             # beside the fractions of the published peaks: of what a bare MFMA loop and a bare copy reach on this machine
             roofline["compute_frac_of_mfma_loop"] = roofline["compute_frac"] * MFMA_BF16_PEAK_TFLOPS / ach["mfma_bf16_TFLOPs"]
             roofline["hbm_frac_of_copy"] = roofline["hbm_frac"] * HBM_PEAK_GBS / ach["copy_GBps"]
+    del g, out, ws
+    torch.cuda.empty_cache()
+    return res, wl
+
+
+def summary(res):
+    """One line of the `configs` array: what the headline carries for its own workload, shortened."""
+    r = res["roofline"] or {}
+    return {"workload": res["config"]["workload"], "requests": res["config"]["requests"],
+            "extend_tokens": res["config"]["extend_tokens"], "steps": res["steps"], "ms_per_step": res["ms_per_step"],
+            "extend_tokens_per_s": res["value"], "match_reqs_per_s": res.get("match_reqs_per_s"),
+            "kernel_us": {k: round(v["avg_us"], 2) for k, v in res["kernels"].items()},
+            "bound": r.get("bound"), "frac": r.get("frac"), "compute_frac": r.get("compute_frac"), "hbm_frac": r.get("hbm_frac"),
+            "algorithmic_bytes": r.get("algorithmic_bytes"), "algorithmic_flops": r.get("algorithmic_flops"),
+            "workspace_bytes": r.get("workspace_bytes"), "traffic": r.get("traffic"), "traffic_source": r.get("traffic_source"),
+            "shader_mhz": r.get("shader_mhz")}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="agent_tree", choices=["tiny_fp32", "tool_use", "long_doc_qa", "agent_tree", "video_qa", "programming", "tool_use_zipf", "decode"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the cold-cache and the scaled-matcher measurements")
+    ap.add_argument("--no-configs", action="store_true", help="measure --workload only, not the other bf16 configurations beside it")
+    ap.add_argument("--only", default="", help="time only one call of the path: match | extend | append (for profiling)")
+    ap.add_argument("--graph", action="store_true", help="replay one captured HIP graph per step instead of launching its calls "
+                    "from the host (measured: no faster, the gaps between the dependent kernels are not host-bound)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the path has no cross-GPU step); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU; there is no CPU fallback"
+    head, wl = measure(args.workload, args.steps, args.warmup, args, with_extras=not args.no_extras and not args.only)
+    res = {"metric": "extend_prefill_tokens_per_s", "value": head["value"], "unit": "tokens/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic"}
+    for k in ("config", "prompt_tokens_per_s", "kernels", "roofline", "match_reqs_per_s", "append_GBps", "extras"):
+        if k in head:
+            res[k] = head[k]
+    if not args.no_configs and not args.only:
+        rows = []
+        for name in BF16_CONFIGS:
+            if name == args.workload:
+                rows.append(summary(head))
+            else:
+                other, _ = measure(name, min(args.steps, 100), min(args.warmup, 10), args, with_extras=False)
+                rows.append(summary(other))
+        res["configs"] = rows
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(res))

@@ -23,7 +23,7 @@
  *    on the bf16 matrix cores with fp32 accumulation, keeps softmax in fp32, and
  *    writes bf16.
  *  - Supported shapes: D in {64, 128}; Hq a multiple of Hkv; page_size >= 1 dividing
- *    num_slots.  Tensor base pointers must be 16-byte aligned.
+ *    num_slots (any size, a power of two or not).  Tensor base pointers must be 16-byte aligned.
  */
 #ifndef PREFIXATTN_H
 #define PREFIXATTN_H
@@ -40,6 +40,7 @@ extern "C" {
 #define PA_ENOMEM (-2) /* host or device allocation failed, or workspace too small */
 #define PA_ESTATE (-3) /* tree not uploaded, or changed since the last upload */
 #define PA_EHIP (-4)   /* HIP runtime error */
+#define PA_EOVERFLOW (-5) /* the batch on the device is larger than the host-side sizes the call was given */
 
 #define PA_F32 0
 #define PA_BF16 1
@@ -145,8 +146,8 @@ int pa_tree_evict_for(pa_tree* tree, const int32_t* tokens, int32_t n, int64_t* 
  * (0, the default: none is).  They are what pa_tree_evict_plan counts sharers from. */
 int pa_tree_set_hit_window(pa_tree* tree, int64_t window);
 
-/* What pa_tree_evict(tree, need_slots, ...) would drop, without dropping it (Sec. 3.2, second cost:
- * "the tree nodes that would be evicted to run the request").  node_tokens[k] receives the number
+/* What pa_tree_evict(tree, need_slots, ...) would drop, without dropping it (the eviction set behind the
+ * second cost term of Sec. 3.2 and Algorithm 2).  node_tokens[k] receives the number
  * of tokens the k-th victim would lose (all of a node, or its tail), node_sharers[k] the number of
  * admissions later than time `since` whose prompt ran through that node (a node that goes whole
  * and is followed at once by its parent with the same count forms one entry with it: where a path
@@ -281,12 +282,14 @@ int pa_match_prefixes(const pa_tree* tree, const int32_t* tokens, const int32_t*
  *
  * q_ext        [T, Hq, D]   k_ext, v_ext  [T, Hkv, D]   out [T, Hq, D]   (dtype elements)
  * kv_pool      pool written by pa_append_kv with the same Hkv, D, dtype, page_size, num_slots
- * slot_idx, slot_offsets   as produced by pa_match_prefixes (slot_offsets = its offsets).  Slot lists name
- *                cached tokens of one prefix tree: two requests have the same slot at a position only if
- *                they have the same slots at every earlier position (the bf16 path groups requests that
- *                share a prefix, or a first part of it, by comparing slots; lists that break this give
- *                unspecified results for the requests concerned).  Lists built by hand from a request's
- *                own slots (chunked prefill: cached prefix + its earlier chunks) keep it.
+ * slot_idx, slot_offsets   as produced by pa_match_prefixes (slot_offsets = its offsets).  The bf16 path lets
+ *                requests that share a prefix, or a first part of it, share row tiles, and finds them by comparing
+ *                slots: two requests count as sharing positions [0, n) if their lists agree in length (whole
+ *                prefixes) and at position n - 1 and at a few places before it.  Lists that name the cached tokens
+ *                of one prefix tree (the matcher's, or lists built from a request's own slots as in chunked
+ *                prefill: cached prefix + its earlier chunks) agree everywhere once they agree there.  For lists of
+ *                any other origin, in which two requests may hold the same slot at the same position behind different
+ *                slots, call pa_extend_set_row_sharing(0) first: every request then walks its own list only.
  * prefix_len, ext_len      int32 [B];  ext_offsets int32 [B + 1], ext_offsets[B] = T
  * T, max_kv_len  HOST values: total extend tokens, and an upper bound on
  *                prefix_len[r] + ext_len[r] (used to size the launch; a request exceeding
@@ -301,6 +304,19 @@ int pa_extend_attention(const void* q_ext, const void* k_ext, const void* v_ext,
                         int64_t max_kv_len, int Hq, int Hkv, int D, int page_size, int64_t num_slots,
                         int dtype, float scale, void* out, void* workspace, size_t workspace_bytes,
                         void* stream);
+
+/* Whether the most recent bf16 pa_extend_attention launch that used `workspace` (device pointer) could lay out its
+ * work.  The launch is sized from the host values T and max_kv_len; if ext_len on the device adds up to more
+ * row tiles than T allows, or the key ranges to more parts than max_kv_len allows, the kernels compute nothing, write
+ * no output row and leave a mark in the workspace.  This call waits for `stream`, reads the mark and returns
+ * PA_EOVERFLOW if it is set, PA_OK otherwise.  (pa_extend_attention itself never waits for the device, so it cannot
+ * report this.)  Undefined for a workspace that no bf16 launch has used. */
+int pa_extend_status(const void* workspace, void* stream);
+
+/* Process-wide switch for the bf16 path, on by default: on = 0 gives every request row tiles of its own, so that
+ * nothing is concluded from equal slots in different requests' lists (see slot_idx above); slower where prefixes
+ * are shared and rows are few.  Takes effect from the next pa_extend_attention call. */
+int pa_extend_set_row_sharing(int on);
 
 /* Cache the KV of newly computed tokens (Sec. 3.2: a prefix stays cached on its GPU from
  * its first assignment until eviction): pool[new_slots[t]] = (k_ext[t], v_ext[t]).

@@ -59,6 +59,8 @@ _SIGS = {
     "pa_extend_workspace_bytes": (_sz, [_i, _i64, _i64, _i, _i, _i, _i]),
     "pa_match_prefixes": (_i, [_vp, _vp, _vp, _i, _vp, _vp, _vp]),
     "pa_extend_attention": (_i, [_vp] * 9 + [_i, _i64, _i64, _i, _i, _i, _i, _i64, _i, _f, _vp, _vp, _sz, _vp]),
+    "pa_extend_status": (_i, [_vp, _vp]),
+    "pa_extend_set_row_sharing": (_i, [_i]),
     "pa_append_kv": (_i, [_vp, _vp, _vp, _vp, _i64, _i, _i, _i, _i64, _i, _vp]),
     "pa_gather_kv": (_i, [_vp, _vp, _i64, _i, _i, _i, _i64, _i, _vp, _vp, _vp]),
     "pa_profile_enable": (_i, [_i]),
@@ -363,6 +365,17 @@ def extend_attention(q_ext: torch.Tensor, k_ext: torch.Tensor, v_ext: torch.Tens
                                     max_kv_len, Hq, Hkv, D, page_size, num_slots, dt, float(scale), _ptr(out),
                                     _ptr(workspace), wbytes, _stream(stream)), "pa_extend_attention")
     return out
+
+
+def extend_status(workspace: torch.Tensor, stream=None) -> None:
+    """Waits for the stream; raises PrefixAttnError (code -5) if the last bf16 extend_attention launch that used
+    `workspace` was given a T or max_kv_len too small for the batch on the device (it then wrote no output)."""
+    _check(_lib.pa_extend_status(_ptr(workspace), _stream(stream)), "pa_extend_status")
+
+
+def extend_set_row_sharing(on: bool) -> None:
+    """Process-wide: False gives every request row tiles of its own (for slot lists that do not come from one prefix tree)."""
+    _check(_lib.pa_extend_set_row_sharing(1 if on else 0), "pa_extend_set_row_sharing")
 
 
 def append_kv(kv_pool: torch.Tensor, new_slots: torch.Tensor, k_ext: torch.Tensor, v_ext: torch.Tensor, *,

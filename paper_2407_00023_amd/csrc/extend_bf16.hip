@@ -32,6 +32,7 @@
 // assembly statement each (fast_run_d128.inc, written by gen_fast_run.py) with the running maximum frozen.
 #include <hip/hip_bf16.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "common.h"
@@ -57,6 +58,7 @@ constexpr int kKT = 64;                  // key tokens per tile
 constexpr int kStages = 2;               // LDS ring: one tile being read, one being filled
 constexpr int kWgSlots = 512;            // workgroups resident at once: two on each of the 256 compute units
 constexpr int kRounds = 3;               // the plan aims at about this many work items per workgroup slot
+constexpr int kRoundsStatic = 1;         // ... with the library's own scratch buffer as workspace (fewer partial results)
 constexpr int kMinChunkTiles = 8;        // never split below this many key tiles (512 keys) per part
 constexpr int kItemOverhead = 4;         // fixed cost of a work item, in key tiles (its prologue and epilogue)
 constexpr int kMaxParts = 64;            // parts of one row tile at most
@@ -80,6 +82,7 @@ struct ExtendPlan {
     int items_cap;   // upper bound on the number of work items (row tile x part of its key range)
     int parts_cap;   // upper bound on the number of items that belong to split tiles (they write partial results)
     int slots;       // workgroup slots per KV head
+    int rounds;      // work items aimed at per workgroup slot
     int merge_cap;   // upper bound on the number of row tiles whose output rows are merged from partial results
     int pack;        // 1: left-over rows of requests with a common prefix may be packed (B <= kPackMax)
     int tile_parts;  // parts of one row tile at most
@@ -96,8 +99,9 @@ static inline size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
 // the end of the list finer still evens the finish further and was measured to gain nothing: while every slot is
 // busy the chip is at its power limit, and the extra parts cost a merge.)  The bounds below follow from that rule
 // (see extend_plan_kernel).
-static ExtendPlan make_plan(int B, int64_t T, int64_t max_kv_len, int Hq, int Hkv, int D) {
+static ExtendPlan make_plan(int B, int64_t T, int64_t max_kv_len, int Hq, int Hkv, int D, int rounds = kRounds) {
     ExtendPlan p{};
+    p.rounds = rounds;
     const int G = Hq / Hkv;
     p.nw = 4;
     p.rb = 1;
@@ -106,7 +110,7 @@ static ExtendPlan make_plan(int B, int64_t T, int64_t max_kv_len, int Hq, int Hk
     p.pack = B <= kPackMax;
     p.tiles_cap = static_cast<int>(est + B);  // (packing only lowers the number of tiles)
     p.slots = kWgSlots / Hkv > 0 ? kWgSlots / Hkv : 1;
-    const int64_t by_rule = static_cast<int64_t>(p.slots) * kRounds + 1;                  // sum of (parts - 1) over the tiles
+    const int64_t by_rule = static_cast<int64_t>(p.slots) * rounds + 1;                  // sum of (parts - 1) over the tiles
     // (the key range of a shared tile holds the own keys of every member: of up to mt requests)
     const int64_t longest = p.pack ? max_kv_len * (B < mt ? (B > 0 ? B : 1) : mt) : max_kv_len;
     const int64_t per_tile = (longest / kKT) / kMinChunkTiles > 1 ? (longest / kKT) / kMinChunkTiles : 1;
@@ -207,7 +211,7 @@ struct TileDesc {
 __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
     const int32_t* __restrict__ prefix_len, const int32_t* __restrict__ ext_len, const int32_t* __restrict__ ext_offsets,
     const int32_t* __restrict__ slot_offsets, const int32_t* __restrict__ slot_idx, int B, int G, int mt, int tiles_cap,
-    int items_cap, int parts_cap, int merge_cap, int slots, int pack, int tile_parts, int32_t* __restrict__ hdr,
+    int items_cap, int parts_cap, int merge_cap, int slot_items, int pack, int tile_parts, int32_t* __restrict__ hdr,
     int32_t* __restrict__ order, int4* __restrict__ tile_tab, int4* __restrict__ tile_aux, int4* __restrict__ member_tab,
     int4* __restrict__ item_tab, int32_t* __restrict__ merge_tiles) {
     __shared__ int s_w[3][kPlanThreads / 64 + 1];
@@ -218,6 +222,10 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
     __shared__ int s_order[kSortMax];             // position in the list -> request
     __shared__ int s_e0[kSortMax], s_so[kSortMax]; // first extend token and first slot-list entry of the request
     __shared__ int s_tpos[kTileLds];  // tile -> (list position << 12 | tile of the position)
+    static_assert(kTileLds >= 3 * kSortMax, "the grouping borrows s_tpos");
+    int* const s_first = s_tpos;               // first and middle slot of the request's prefix, the first request with
+    int* const s_mid = s_tpos + kSortMax;      // the same prefix (before the tiles are laid out)
+    int* const s_ldr = s_tpos + 2 * kSortMax;
     // packing (B <= kPackMax): per list position ...
     __shared__ int s_gid[kPackMax];     // its group (run of positions with the same prefix)
     __shared__ int s_R[kPackMax];       // first row of its left-over rows among the group's, -1: not packed
@@ -249,8 +257,30 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
             s_e0[r] = ext_offsets[r];
             s_so[r] = so;
             s_grp[r] = P > 0 ? slot_idx[so + P - 1] : -1 - r;
+            s_first[r] = P > 0 ? slot_idx[so] : 0;
+            s_mid[r] = P > 0 ? slot_idx[so + P / 2] : 0;
+            s_ldr[r] = r;
         }
         __syncthreads();
+        // Requests share their whole prefix if it has the same length and the same slots: the group is named by its
+        // first request.  Slot lists that name the tokens of one prefix tree are equal as soon as their last slots
+        // are; the length, the first and the middle slot are compared as well, so that lists of other origin that
+        // merely end in the same slot stay apart.
+        {
+            const int tpr = max(1, kPlanThreads / B);
+            const int r = tid / tpr, q_first = tid % tpr;
+            if (r < B) {
+                const int grp = s_grp[r], P = s_P[r], first = s_first[r], mid = s_mid[r];
+                int lead = r;
+#pragma unroll 4
+                for (int q = q_first; q < r; q += tpr)
+                    if (s_grp[q] == grp && s_P[q] == P && s_first[q] == first && s_mid[q] == mid) lead = min(lead, q);
+                if (lead < r) atomicMin(&s_ldr[r], lead);
+            }
+            __syncthreads();
+            for (int q = tid; q < B; q += kPlanThreads) s_grp[q] = s_ldr[q];  // (>= 0; a lone request names itself)
+            __syncthreads();
+        }
         if (pack && B <= kPackMax) {
             // groups of requests that share the first part of their prefixes (see above); four threads per request
             constexpr int kProbes = 12;
@@ -352,9 +382,15 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
                         cut = s_lead[q] == lead ? min(cut, theirs) : cut;
                     }
                     cut = min4(cut);
-                    if (sub == 0) {
+                    // (lists of one prefix tree agree on [0, cut) once they agree at cut - 1; for lists of other origin
+                    // three more places are compared, and a request that differs there stays on its own)
+                    const int32_t* a = slot_idx + s_so[r];
+                    const int32_t* b = slot_idx + s_so[lead];
+                    const int at = sub == 0 ? 0 : sub == 1 ? cut / 3 : sub == 2 ? (2 * cut) / 3 : cut - 1;
+                    const bool agree = or4((cut > 0 && a[at] != b[at]) ? 1 : 0) == 0;
+                    if (sub == 0 && agree) {
                         s_cut[r] = cut;
-                        s_grp[r] = -1 - B - lead;  // (no slot and no lone request has this key)
+                        s_grp[r] = -1 - lead;  // (no whole-prefix group has a negative name)
                     }
                 }
                 __syncthreads();
@@ -405,6 +441,7 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
     const bool in_lds = staged && tiles_cap <= kTileLds;
     const bool packing = in_lds && pack && B <= kPackMax;
     int n_tiles;
+    bool tiles_over;  // more row tiles than the launch was sized for: ext_len on the device exceeds the host's T
     if (in_lds) {
         // one thread per list position (B <= kPlanThreads here)
         const bool on = tid < B;
@@ -459,6 +496,7 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
         block_scan<1>(v, total, s_w);
         if (on) s_gkey[tid] = v[0];  // (s_gkey is free again: the first tile of the position)
         __syncthreads();
+        tiles_over = total[0] > tiles_cap;
         n_tiles = min(total[0], tiles_cap);
         for (int t = tid; t < n_tiles; t += kPlanThreads) {
             int lo = 0, hi = B;  // the last position whose first tile is <= t
@@ -487,6 +525,7 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
             if (tid == 0) s_carry += total[0];
             __syncthreads();
         }
+        tiles_over = s_carry > tiles_cap;
         n_tiles = min(s_carry, tiles_cap);
     }
     // what tile t is
@@ -569,9 +608,9 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
     }
     // parts of a tile: its cost over the target cost of an item, rounded up from a quarter past a whole number (an item
     // of 1.5 targets at the end of the list is a tail of its own); never below kMinChunkTiles key tiles per part.
-    // Summed over the tiles, parts - 1 stays below W / target = slots * kRounds (a tile of cost c adds at most
+    // Summed over the tiles, parts - 1 stays below W / target = slot_items = slots * rounds (a tile of cost c adds at most
     // c / target - 1/4), which is what the capacities are sized for.
-    const float target = fmaxf(static_cast<float>(W) / static_cast<float>(slots * kRounds), 1.f);
+    const float target = fmaxf(static_cast<float>(W) / static_cast<float>(slot_items), 1.f);
     auto parts_of = [&](int K) {
         int n = static_cast<int>(static_cast<float>(K + kItemOverhead) / target + 0.75f);
         n = min(min(n, K / kMinChunkTiles), tile_parts);
@@ -590,8 +629,10 @@ __global__ __launch_bounds__(kPlanThreads) void extend_plan_kernel(
     block_scan<3>(base3, total3, s_w);
     int item0 = base3[0], part0 = base3[1], merge0 = base3[2];
     const int n_items = total3[0], n_merge = total3[2];
-    // (by the bounds the capacities were sized from this cannot happen; an empty list makes it visible: no output)
-    const bool overflow = n_items > items_cap || total3[1] > parts_cap || n_merge > merge_cap;
+    // The capacities follow from the host's T and max_kv_len: a batch on the device that is larger than they say does
+    // not fit.  Nothing is computed then (an empty list: no output row is written) and hdr[3] says so, which
+    // pa_extend_status reports.
+    const bool overflow = tiles_over || n_items > items_cap || total3[1] > parts_cap || n_merge > merge_cap;
     for (int t = t_lo; t < t_hi && !overflow; ++t) {
         const TileDesc d = tile_desc(t);
         const int K = (d.kv_end - d.kv_lo + kKT - 1) / kKT;
@@ -707,8 +748,8 @@ template <int D, int NW, int RB>
 __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     const __hip_bfloat16* __restrict__ q_ext, const __hip_bfloat16* __restrict__ k_ext,
     const __hip_bfloat16* __restrict__ v_ext, const __hip_bfloat16* __restrict__ pool,
-    const int32_t* __restrict__ slot_idx, int Hq, int Hkv, int page_size, int page_shift, int num_slots,
-    int fast_ok, float scale_log2e, __hip_bfloat16* __restrict__ out, const int32_t* __restrict__ hdr,
+    const int32_t* __restrict__ slot_idx, int Hq, int Hkv, int page_size, int page_shift, unsigned page_magic,
+    int page_mshift, int num_slots, int fast_ok, float scale_log2e, __hip_bfloat16* __restrict__ out, const int32_t* __restrict__ hdr,
     const int4* __restrict__ item_tab, const int4* __restrict__ member_tab, float* __restrict__ part_o,
     float* __restrict__ part_ml, unsigned long long* __restrict__ clk) {
     constexpr int WR = 32 * RB;              // packed query rows per wave (RB blocks of 32)
@@ -892,7 +933,8 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     auto ld_voff = [&](int u) __attribute__((always_inline)) { return opaque(ld_voff0) ^ ((D == 128 ? 16u : 32u) * u); };
     // The next tile's loads, general: every lane takes its row from the pool (through the slot prefetched for it) or
     // from the extend tensors, by position; rows past the end of the key range repeat the last valid row (finite
-    // values that the mask zeroes).  Page sizes are powers of two (checked on the host).
+    // values that the mask zeroes).  The page of a slot: a shift where the page size is a power of two
+    // (page_shift >= 0), otherwise the exact quotient by a multiplication (see page_divider).
     auto issue = [&](int p0, int ring) __attribute__((always_inline)) {
         const unsigned sk = __builtin_amdgcn_readfirstlane(smem_addr + ring * STAGEB);  // wave-uniform (goes to M0)
         if (shared)
@@ -903,8 +945,9 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
             const int p = min(p0 + blk * RPB + ld_rowl, kv_hi - 1);
             bool ext = p >= P;
             const unsigned sl = static_cast<unsigned>(min(max(sl_next[u], 0), num_slots - 1));  // never outside the pool
-            const size_t pool_off = static_cast<size_t>(sl >> page_shift) * page_stride +
-                                    (sl & static_cast<unsigned>(page_size - 1)) * static_cast<unsigned>(ROWB);
+            const unsigned pg = page_shift >= 0 ? sl >> page_shift : __umulhi(sl, page_magic) >> page_mshift;
+            const size_t pool_off = static_cast<size_t>(pg) * page_stride +
+                                    (sl - pg * static_cast<unsigned>(page_size)) * static_cast<unsigned>(ROWB);
             int64_t xrow = p - P;  // extend token, counted from the first one of the request of this item
             if (shared && ext) {
                 // the member whose extend tokens hold key p, and that token relative to e0
@@ -1279,6 +1322,26 @@ __global__ __launch_bounds__(256) void extend_merge_kernel(const int32_t* __rest
     }
 }
 
+// How the kernel divides a slot id (< 2^31) by the page size d.  A power of two: *shift = log2 d.  Otherwise
+// *shift = -1 and slot / d = umulhi(slot, *magic) >> *mshift exactly: with l = ceil(log2 d), k = 31 + l and
+// magic = floor(2^k / d) + 1 (< 2^32 since 2^l < 2 d), the error magic * d - 2^k is at most d <= 2^l = 2^(k - 31),
+// which keeps the quotient exact for every numerator below 2^31; mshift = k - 32.
+static void page_divider(int d, int* shift, unsigned* magic, int* mshift) {
+    *shift = -1;
+    *magic = 0;
+    *mshift = 0;
+    if ((d & (d - 1)) == 0) {
+        *shift = 0;
+        while ((1 << *shift) < d) ++*shift;
+        return;
+    }
+    int l = 0;
+    while ((int64_t{1} << l) < d) ++l;
+    const int k = 31 + l;
+    *magic = static_cast<unsigned>((static_cast<unsigned __int128>(1) << k) / static_cast<unsigned>(d) + 1);
+    *mshift = k - 32;
+}
+
 template <int D, int NW, int RB>
 static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_ext, const void* v_ext,
                          const void* kv_pool, const int32_t* slot_idx, const int32_t* ext_len, const int32_t* ext_offsets,
@@ -1288,11 +1351,9 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
                          unsigned long long* clk, hipStream_t stream) {
     // the K/V ring, and behind it the table of a shared tile's members (4 ints each, one int more) and 2 ints per wave
     constexpr size_t lds_bytes = static_cast<size_t>(kStages) * 2 * kKT * D * 2 + (4 * 32 * RB * NW + 1 + 2 * NW) * sizeof(int);
-    int page_shift = -1;
-    if ((page_size & (page_size - 1)) == 0) {
-        page_shift = 0;
-        while ((1 << page_shift) < page_size) ++page_shift;
-    }
+    int page_shift = -1, page_mshift = 0;
+    unsigned page_magic = 0;
+    page_divider(page_size, &page_shift, &page_magic, &page_mshift);
     const dim3 grid(static_cast<unsigned>(p.items_cap) * Hkv);
     // The hand-scheduled tile addresses K/V rows with 32-bit byte offsets and 24-bit multiplies: it needs a
     // power-of-two page size, a pool below 4 GB, and extend tensors below 4 GB.
@@ -1306,7 +1367,8 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
         hipLaunchKernelGGL((extend_bf16_kernel<D, NW, RB>), grid, dim3(NW * 64), lds_bytes, stream,
                            static_cast<const __hip_bfloat16*>(q_ext), static_cast<const __hip_bfloat16*>(k_ext),
                            static_cast<const __hip_bfloat16*>(v_ext), static_cast<const __hip_bfloat16*>(kv_pool), slot_idx,
-                           Hq, Hkv, page_size, page_shift, static_cast<int>(num_slots), fast_ok, scale_log2e,
+                           Hq, Hkv, page_size, page_shift, page_magic, page_mshift, static_cast<int>(num_slots), fast_ok,
+                           scale_log2e,
                            static_cast<__hip_bfloat16*>(out), hdr, item_tab, member_tab, part_o, part_ml, clk);
     }
     if (p.parts_cap > 0) {  // whether any tile was split is known on the device only: unsplit tiles leave at once
@@ -1320,6 +1382,26 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
 }
 
 }  // namespace pa
+
+// Process-wide switch: 0 = every request gets row tiles of its own (no grouping by equal slots).
+static std::atomic<int> g_row_sharing{1};
+extern "C" int pa_extend_set_row_sharing(int on) {
+    g_row_sharing.store(on != 0);
+    return PA_OK;
+}
+
+// Whether the last bf16 launch that used this workspace found room for its work list.
+extern "C" int pa_extend_status(const void* workspace, void* stream) {
+    PA_REQUIRE(workspace != nullptr, "pa_extend_status: workspace is NULL");
+    int32_t hdr[4] = {0, 0, 0, 0};
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    PA_HIP(hipMemcpyAsync(hdr, workspace, sizeof hdr, hipMemcpyDeviceToHost, s));
+    PA_HIP(hipStreamSynchronize(s));
+    if (hdr[3] != 0)
+        return pa::fail(PA_EOVERFLOW, "pa_extend_attention: the batch on the device is larger than the T and max_kv_len "
+                                      "the call was given; its work list did not fit and no output was written");
+    return PA_OK;
+}
 
 size_t pa_extend_workspace_bytes_bf16(int B, int64_t T, int64_t max_kv_len, int Hq, int Hkv, int D) {
     return pa::make_plan(B, T, max_kv_len, Hq, Hkv, D).total;
@@ -1335,7 +1417,8 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
     PA_REQUIRE(scale > 0.f && scale < INFINITY, "pa_extend_attention: scale must be positive and finite");
     PA_REQUIRE(num_slots <= INT32_MAX, "pa_extend_attention: num_slots exceeds the int32 range of slot ids");
     PA_REQUIRE(static_cast<int64_t>(page_size) * Hkv * D * 4 < (int64_t{1} << 31), "pa_extend_attention: a page of %d tokens x %d heads is too large", page_size, Hkv);
-    const ExtendPlan p = make_plan(B, T, max_kv_len, Hq, Hkv, D);
+    ExtendPlan p = make_plan(B, T, max_kv_len, Hq, Hkv, D);  // (sized for shared row tiles whether or not they are on)
+    if (!g_row_sharing.load()) p.pack = 0;
     if (workspace_bytes < p.total || workspace == nullptr)
         return fail(PA_ENOMEM, "pa_extend_attention: workspace of %zu bytes given, %zu needed", workspace_bytes, p.total);
     PA_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255u) == 0, "pa_extend_attention: workspace must be 256-byte aligned");
@@ -1356,7 +1439,7 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
     {
         ProfScope prof(kProfPlan, stream);
         hipLaunchKernelGGL(extend_plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, prefix_len, ext_len, ext_offsets, slot_offsets, slot_idx, B,
-                           G, 32 * p.rb * p.nw, p.tiles_cap, p.items_cap, p.parts_cap, p.merge_cap, p.slots, p.pack, p.tile_parts, hdr, order,
+                           G, 32 * p.rb * p.nw, p.tiles_cap, p.items_cap, p.parts_cap, p.merge_cap, p.slots * p.rounds, p.pack, p.tile_parts, hdr, order,
                            tile_tab, tile_aux, member_tab, item_tab, merge_tiles);
     }
     if (D == 64)

@@ -98,3 +98,15 @@ def test_size_queries_and_errors(pa):
     assert lib.pa_calib_copy(None, None, 1024, None) == -1
     lib.pa_calib_mfma.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.POINTER(C.c_int64), C.c_void_p]
     assert lib.pa_calib_mfma(None, 1 << 16, 16, None, None) == -1
+
+
+def test_status_and_switch_calls_check_their_arguments(pa):
+    """The two support calls beside pa_extend_attention refuse bad arguments before any GPU call, and pool sizes
+    accept page sizes that are not powers of two."""
+    import torch
+    lib = C.CDLL(pa.LIB_PATH)
+    lib.pa_extend_status.argtypes = [C.c_void_p, C.c_void_p]
+    assert lib.pa_extend_status(None, None) == -1
+    assert lib.pa_extend_set_row_sharing(0) == 0 and lib.pa_extend_set_row_sharing(1) == 0
+    assert pa.kv_pool_bytes(36864, 4, 128, torch.bfloat16, 12) == 36864 * 2 * 4 * 128 * 2
+    assert pa.kv_pool_bytes(36864, 4, 128, torch.bfloat16, 48) == 36864 * 2 * 4 * 128 * 2

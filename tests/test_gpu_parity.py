@@ -259,13 +259,17 @@ def _random_case(rng, B, Hq, Hkv, D, p_hi, e_hi, dtype, page, nslots):
     ("bf16", 4, 4, 64, 16, 300, 200, 4),     # G = 1, D = 64
     ("bf16", 16, 2, 128, 1, 200, 33, 4),     # G = 8, page size 1
     ("bf16", 8, 8, 128, 16, 5000, 10, 3),    # long prefix, short extend: split path
+    ("bf16", 8, 2, 128, 12, 700, 90, 6),     # page sizes that are not powers of two: the page of a slot by division
+    ("bf16", 16, 4, 128, 48, 3000, 40, 5),
+    ("bf16", 4, 2, 64, 24, 400, 150, 4),
+    ("f32", 4, 2, 64, 3, 150, 40, 5),
 ])
 def test_extend_random_shapes(pa, gpu_device, dtype, Hq, Hkv, D, page, p_hi, e_hi, B):
     """Ragged prefixes and extends including prefix_len = 0 and ext_len = 0 requests."""
     import oracle
     say(f"[case] extend_random {dtype} Hq={Hq} Hkv={Hkv} D={D} page={page} p_hi={p_hi} e_hi={e_hi}")
     rng = np.random.default_rng(11)
-    nslots = 16384
+    nslots = 16384 if 16384 % page == 0 else 18432  # (= 2^11 x 9: divisible by 3, 12, 24, 48)
     c = _random_case(rng, B, Hq, Hkv, D, p_hi, e_hi, dtype, page, nslots)
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
     dev = gpu_device
@@ -385,6 +389,126 @@ def test_extend_slot_permutation_invariance(pa, gpu_device):
     assert torch.equal(out1.view(torch.int16), out2.view(torch.int16))
 
 
+@pytest.mark.parametrize("page", [12, 48])
+def test_whole_path_with_a_page_size_that_is_no_power_of_two(pa, gpu_device, page):
+    """Tool-use-shaped batch on a pool of 12- or 48-token pages: tree, match, attention (whole tiles, shared tiles of
+    left-over rows, split key ranges) and append all address the pool by dividing by the page size; every element against
+    the oracle and the appended rows bit-exact."""
+    say(f"[case] page size {page}")
+    wl = W.tool_use(7, B=10, sys_len=900, n_tools=3, tool_lo=50, tool_hi=400, ext_lo=5, ext_hi=200, Hq=16, Hkv=4,
+                    num_slots=36864, page_size=page)
+    g, o = GpuSide(wl, gpu_device), OracleSide(wl)
+    pl, si, out = g.step()
+    torch.cuda.synchronize()
+    pl_ref, si_ref = o.match()
+    assert_match_equal(wl, pl, si, pl_ref, si_ref)
+    err = np.abs(out_to_f64(out) - o.extend(pl_ref, si_ref)).max()
+    say(f"  max abs err {err:.3e}")
+    assert err <= TOL[wl.dtype]
+    o.append()
+    allslots = np.concatenate([wl.pool_slots, wl.new_slots])
+    gk, gv = pa.gather_kv(g.pool, torch.from_numpy(allslots).to(gpu_device), Hkv=wl.Hkv, D=wl.D, dtype=g.tdtype, **g.kw)
+    np.testing.assert_array_equal(gk.view(torch.int16).cpu().numpy(), o.pool_k[allslots].view(np.int16))
+    np.testing.assert_array_equal(gv.view(torch.int16).cpu().numpy(), o.pool_v[allslots].view(np.int16))
+
+
+def _hand_built_lists(rng, kind, nslots, page):
+    """Five requests whose slot lists were NOT read off one prefix tree: they end in the same slot (and, by kind, also
+    have the same length, first and middle slot) but differ elsewhere."""
+    B, P0 = 5, 640
+    base = rng.permutation(nslots)[:P0].astype(np.int32)
+    lists = []
+    for r in range(B):
+        if kind == "unequal_length":       # same last slot, different lengths: tails of one list
+            lst = base[r * 17:].copy()
+        elif kind == "differs_early":      # same length and last slot, other slots before the middle
+            lst = base.copy()
+            lst[1 + r:200 + r] = rng.permutation(nslots)[:199].astype(np.int32)
+            lst[0] = base[r]                # (and a first slot of its own)
+        else:                              # "differs_between_probes": equal at every place a planner could cheaply look
+            lst = base.copy()
+            if r:
+                lst[3 + r] = base[400 + r]
+                lst[500 + r] = base[40 + r]
+        lists.append(lst)
+    return lists
+
+
+@pytest.mark.parametrize("kind,sharing", [("unequal_length", True), ("differs_early", True),
+                                          ("differs_between_probes", False), ("unequal_length", False)])
+def test_extend_slot_lists_that_do_not_come_from_one_tree(pa, gpu_device, kind, sharing):
+    """Slot lists built by hand.  Lists that end in the same slot but differ in length or in their early slots must
+    not be taken for a shared prefix (every element against the oracle with row sharing on); lists that agree at every
+    place the grouping looks at and differ in between are what pa_extend_set_row_sharing(0) is for."""
+    import oracle
+    say(f"[case] hand-built slot lists: {kind}, row sharing {'on' if sharing else 'off'}")
+    rng = np.random.default_rng(31)
+    Hq, Hkv, D, page, nslots = 8, 2, 128, 16, 8192
+    lists = _hand_built_lists(rng, kind, nslots, page)
+    B = len(lists)
+    P = np.array([len(x) for x in lists], np.int32)
+    E = rng.integers(3, 30, B).astype(np.int32)   # a few rows each: left-over rows only, the ones that get packed
+    off = np.zeros(B + 1, np.int32)
+    off[1:] = np.cumsum(P + E)
+    si = np.full(off[-1], -1, np.int32)
+    for r in range(B):
+        si[off[r]:off[r] + P[r]] = lists[r]
+    eo = np.zeros(B + 1, np.int32)
+    eo[1:] = np.cumsum(E)
+    T = int(eo[-1])
+    ss = np.random.SeedSequence(5).spawn(5)
+    mk = lambda s_, n, h: W._normal(s_, n * h * D, "bf16").reshape(n, h, D)
+    backed = np.arange(nslots, dtype=np.int32)
+    q, k, v, pk, pv = mk(ss[0], T, Hq), mk(ss[1], T, Hkv), mk(ss[2], T, Hkv), mk(ss[3], nslots, Hkv), mk(ss[4], nslots, Hkv)
+    dev = gpu_device
+    pool = torch.zeros(pa.kv_pool_bytes(nslots, Hkv, D, torch.bfloat16, page), dtype=torch.uint8, device=dev)
+    kw = dict(page_size=page, num_slots=nslots)
+    pa.append_kv(pool, torch.from_numpy(backed).to(dev), to_torch(pk, "bf16", dev), to_torch(pv, "bf16", dev), **kw)
+    tt = lambda a: torch.from_numpy(a).to(dev)
+    scale = 1.0 / np.sqrt(D)
+    pa.extend_set_row_sharing(sharing)
+    try:
+        out = pa.extend_attention(to_torch(q, "bf16", dev), to_torch(k, "bf16", dev), to_torch(v, "bf16", dev), pool, tt(si),
+                                  tt(off), tt(P), tt(E), tt(eo), scale, max_kv_len=int((P + E).max()), **kw)
+        torch.cuda.synchronize()
+    finally:
+        pa.extend_set_row_sharing(True)
+    opk, opv = oracle.new_pool(nslots, Hkv, D, "bf16")
+    oracle.append_kv(opk, opv, backed, pk, pv, "bf16")
+    ref = oracle.extend_attention(q, k, v, opk, opv, si, off, P, E, eo, scale, "bf16")
+    err = np.abs(out_to_f64(out) - ref).max()
+    say(f"  max abs err {err:.3e}")
+    assert err <= TOL["bf16"]
+
+
+def test_extend_reports_a_batch_larger_than_the_host_sizes(pa, gpu_device):
+    """pa_extend_attention sizes its launch from the host values T and max_kv_len.  Given a T smaller than what ext_len
+    on the device adds up to, the work list does not fit: no output row is written, and pa_extend_status says so
+    (PA_EOVERFLOW); after a proper call on the same workspace it reports success again."""
+    import ctypes as C
+    wl = W.small_variant("agent_tree", 2)
+    g = GpuSide(wl, gpu_device)
+    pl, si = g.match()
+    nbytes = pa.extend_workspace_bytes(wl.B, wl.T, g.max_kv_len, wl.Hq, wl.Hkv, wl.D, g.tdtype)
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device=gpu_device)
+    out = torch.full_like(g.q, 7.0)
+    lib = pa._lib
+    T_lie = 64  # the device-side ext_len adds up to wl.T, far more row tiles than 64 tokens make
+    assert wl.T * (wl.Hq // wl.Hkv) // 128 > T_lie * (wl.Hq // wl.Hkv) // 128 + wl.B + 1
+    rc = lib.pa_extend_attention(pa._ptr(g.q), pa._ptr(g.k), pa._ptr(g.v), pa._ptr(g.pool), pa._ptr(si), pa._ptr(g.offsets),
+                                 pa._ptr(pl), pa._ptr(g.ext_len), pa._ptr(g.ext_offsets), wl.B, T_lie, g.max_kv_len, wl.Hq,
+                                 wl.Hkv, wl.D, wl.page_size, wl.num_slots, pa.BF16, float(wl.scale), pa._ptr(out), pa._ptr(ws),
+                                 nbytes, pa._stream(None))
+    assert rc == 0  # the call itself cannot know: it never waits for the device
+    with pytest.raises(pa.PrefixAttnError) as e:
+        pa.extend_status(ws)
+    assert e.value.code == -5
+    assert bool((out == 7.0).all())  # nothing was written
+    g.extend(pl, si, workspace=ws, out=out)
+    pa.extend_status(ws)
+    assert torch.isfinite(out.float()).all() and not bool((out == 7.0).all())
+
+
 # ------------------------------------------------------------------------------------ full configs
 
 @pytest.fixture(scope="module")
@@ -411,24 +535,80 @@ def test_full_config_match_bit_exact(pa, gpu_device, full_cache, name):
     np.testing.assert_array_equal(pl_ref, wl.designed_prefix_len)
 
 
+def _pairs_for_partial_check(wl, frac, seed=1):
+    """(request, query head) pairs whose every row is compared when the oracle cannot do the whole batch: all heads of
+    the longest and the shortest request, of requests that share their whole prefix with another one (their left-over
+    rows sit in shared row tiles), then random pairs up to `frac` of all pairs."""
+    rng = np.random.default_rng(seed)
+    want = int(np.ceil(frac * wl.B * wl.Hq))
+    chosen, seen = [], set()
+
+    def add(r, h):
+        if (r, h) not in seen:
+            seen.add((r, h))
+            chosen.append((r, h))
+
+    for r in (int(np.argmax(wl.ext_len)), int(np.argmin(wl.ext_len))):
+        for h in range(wl.Hq):
+            add(r, h)
+    key = {}
+    for r in range(wl.B):
+        lo, P = int(wl.offsets[r]), int(wl.designed_prefix_len[r])
+        key.setdefault((P, int(wl.designed_slots[lo + P - 1]) if P else -1 - r), []).append(r)
+    sharers = [r for rs in key.values() if len(rs) > 1 for r in rs]
+    for r in sharers[:max(2, want // (2 * wl.Hq))]:
+        for h in range(wl.Hq):
+            add(r, h)
+    while len(chosen) < want:
+        add(int(rng.integers(0, wl.B)), int(rng.integers(0, wl.Hq)))
+    return chosen
+
+
 @pytest.mark.parametrize("name", FULL)
-def test_full_config_extend_sampled_rows(pa, gpu_device, full_cache, name):
-    """Full sizes, in the launch configuration the benchmark times: sampled output rows against the oracle,
-    plus a property that holds at any size (every output element lies inside the range of the visible V)."""
+def test_full_config_extend_every_element(pa, gpu_device, full_cache, name):
+    """Full sizes, in the launch configuration the benchmark times.  Every output element against the oracle; on
+    agent_tree, whose oracle run would take a minute, every row of a quarter of the (request, head) pairs: all heads of
+    the longest and shortest requests and of requests whose left-over rows are packed into shared tiles, the rest drawn
+    at random.  The error is reported for rows in full 128-row tiles and for left-over rows apart (the latter are the
+    ones that shared tiles hold), next to what the work list says about tiles, items and merged tiles.  Plus a property
+    that holds at any size: every output element lies inside the range of the visible V."""
     say(f"[case] full extend {name}")
     wl, g, o = _full(name, gpu_device, full_cache)
     pl, si = g.match()
-    out = g.extend(pl, si)
+    nbytes = pa.extend_workspace_bytes(wl.B, wl.T, g.max_kv_len, wl.Hq, wl.Hkv, wl.D, g.tdtype)
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device=gpu_device)
+    out = g.extend(pl, si, workspace=ws)
     torch.cuda.synchronize()
+    pa.extend_status(ws)
+    n_tiles, n_items, n_merge, overflow = ws[:16].view(torch.int32).tolist()
+    assert overflow == 0 and n_items >= n_tiles >= 1
     assert torch.isfinite(out.float()).all()
     pl_ref, si_ref = o.match()
-    rows = sample_rows(wl, 192 if name != "agent_tree" else 384, seed=1)
-    ref = o.extend(pl_ref, si_ref, rows=rows)
-    outn = out_to_f64(out)
-    got = np.stack([outn[wl.ext_offsets[r] + i, h] for r, i, h in rows])
-    err = np.abs(got - ref).max()
-    say(f"  max abs err over {len(rows)} rows: {err:.3e}")
-    assert err <= TOL[wl.dtype]
+    G = wl.Hq // wl.Hkv
+    if name == "agent_tree":
+        pairs = _pairs_for_partial_check(wl, 0.25)
+        rows = np.concatenate([np.stack([np.full(wl.ext_len[r], r), np.arange(wl.ext_len[r]), np.full(wl.ext_len[r], h)], 1)
+                               for r, h in pairs]).astype(np.int32)
+        ref = o.extend(pl_ref, si_ref, rows=rows)
+        flat = torch.from_numpy(wl.ext_offsets[rows[:, 0]].astype(np.int64) + rows[:, 1]).to(gpu_device)
+        got = out_to_f64(out[flat, torch.from_numpy(rows[:, 2].astype(np.int64)).to(gpu_device)])
+        covered = f"{len(pairs)} of {wl.B * wl.Hq} (request, head) pairs, {len(rows)} rows"
+    else:
+        ref = o.extend(pl_ref, si_ref).reshape(wl.T * wl.Hq, wl.D)
+        got = out_to_f64(out).reshape(wl.T * wl.Hq, wl.D)
+        r_of = np.repeat(np.arange(wl.B), wl.ext_len)
+        i_of = np.arange(wl.T) - wl.ext_offsets[r_of]
+        rows = np.stack([np.repeat(r_of, wl.Hq), np.repeat(i_of, wl.Hq), np.tile(np.arange(wl.Hq), wl.T)], 1)
+        covered = f"all {len(rows)} rows"
+    err_rows = np.abs(got - ref).max(axis=1)
+    rho = rows[:, 1].astype(np.int64) * G + rows[:, 2] % G
+    n_rows = wl.ext_len[rows[:, 0]].astype(np.int64) * G
+    leftover = rho >= (n_rows // 128) * 128
+    e_full = float(err_rows[~leftover].max()) if (~leftover).any() else 0.0
+    e_left = float(err_rows[leftover].max()) if leftover.any() else 0.0
+    say(f"  {covered}: max abs err {err_rows.max():.3e} (rows of full tiles {e_full:.3e}, left-over rows {e_left:.3e}); "
+        f"work list: {n_tiles} row tiles, {n_items} items, {n_merge} tiles merged from parts")
+    assert err_rows.max() <= TOL[wl.dtype]
     # softmax weights are a convex combination: |out| can never exceed the largest |V| in the inputs
     vmax = max(float(np.abs(W.bf16_bits_to_f32(wl.pool_v)).max()), float(np.abs(W.bf16_bits_to_f32(wl.v_ext)).max()))
     assert float(out.float().abs().max()) <= vmax * (1 + 2 ** -7)
