@@ -33,6 +33,7 @@
 #include <hip/hip_bf16.h>
 
 #include <atomic>
+#include <cstdlib>
 #include <type_traits>
 
 #include "common.h"
@@ -58,7 +59,6 @@ constexpr int kKT = 64;                  // key tokens per tile
 constexpr int kStages = 2;               // LDS ring: one tile being read, one being filled
 constexpr int kWgSlots = 512;            // workgroups resident at once: two on each of the 256 compute units
 constexpr int kRounds = 3;               // the plan aims at about this many work items per workgroup slot
-constexpr int kRoundsStatic = 1;         // ... with the library's own scratch buffer as workspace (fewer partial results)
 constexpr int kMinChunkTiles = 8;        // never split below this many key tiles (512 keys) per part
 constexpr int kItemOverhead = 4;         // fixed cost of a work item, in key tiles (its prologue and epilogue)
 constexpr int kMaxParts = 64;            // parts of one row tile at most
@@ -770,6 +770,13 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     const int g = blockIdx.x % Hkv;
     const int item = blockIdx.x / Hkv;
     if (item >= hdr[1]) return;
+#ifdef PA_PROBE_DETAIL
+    // (build option for experiments: where a workgroup's cycles go - clk[2..7] = cycles in runs of assembly tiles, tiles
+    // done there, cycles in general tiles, their number, cycles before the key loop, cycles after it)
+    const long long probe_t0 = clk ? clock64() : 0;
+    long long probe_fast = 0, probe_gen = 0, probe_gen_issue = 0, probe_gen_math = 0;
+    int probe_nfast = 0, probe_ngen = 0;
+#endif
     const int4 rec0 = item_tab[3 * static_cast<size_t>(item)], rec1 = item_tab[3 * static_cast<size_t>(item) + 1];
     const int4 rec2 = item_tab[3 * static_cast<size_t>(item) + 2];
     const int slot_off = rec2.x;
@@ -1010,24 +1017,45 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
         const unsigned off = static_cast<unsigned>(mb) * (32 * ROWB);
         const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         f32x16 sacc[RB];
-        // S^T = K Q^T: each K fragment read from LDS feeds RB MFMAs
+        // S^T = K Q^T: each K fragment read from LDS feeds RB MFMAs.  All fragments of the block are asked for before
+        // the first product, so that their LDS round trips overlap instead of following one another.
+        // (Written as assembly: the compiler, short of registers, otherwise reads one fragment at a time into the same four
+        // registers, eight LDS round trips in a row.  Nothing else of this wave's is in flight on the LDS counter here:
+        // the compiler's own LDS reads are awaited before they are used, and one wait for all eight follows.)
+        bf16x8 kf[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) asm volatile("ds_read_b128 %0, %1" : "=v"(kf[s]) : "v"(k_rd[s] + off));
+        if constexpr (KS == 8)
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]), "+v"(kf[4]), "+v"(kf[5]), "+v"(kf[6]), "+v"(kf[7]));
+        else
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]));
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            const bf16x8 kf = *(const __attribute__((address_space(3))) bf16x8*)(lds + (k_rd[s] + off));
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
-                sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qreg[rb][s], s == 0 ? zero16 : sacc[rb], 0, 0, 0);
+                sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qreg[rb][s], s == 0 ? zero16 : sacc[rb], 0, 0, 0);
         }
         const int pb0 = p0 + 32 * mb;
         uint32_t pb[RB][8];
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
             // the keys a row must not see (only where the block crosses a visibility limit)
+            // (register i of the lane holds the key at offset 8 (i / 4) + i % 4 from the lane's first key of the block:
+            // compared, without branches, against the row's limits counted from that key)
             if (need_mask && pb0 + 32 > blk_vis_min[rb]) {
+                const int first = pb0 + 4 * hh;
+                const int lim_end = vis_end[rb] - first;
+                if (!shared) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int p = pb0 + 8 * (i / 4) + 4 * hh + (i % 4);
-                    if (p >= vis_end[rb] || (p >= P && p < vis_lo[rb])) sacc[rb][i] = -INFINITY;
+                    for (int i = 0; i < 16; ++i) sacc[rb][i] = (8 * (i / 4) + (i % 4) < lim_end) ? sacc[rb][i] : -INFINITY;
+                } else {
+                    const int lim_p = P - first, lim_lo = vis_lo[rb] - first;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int o = 8 * (i / 4) + (i % 4);
+                        const bool hide = (o >= lim_end) | ((o >= lim_p) & (o < lim_lo));
+                        sacc[rb][i] = hide ? -INFINITY : sacc[rb][i];
+                    }
                 }
             }
             // row maximum of the block, in every lane of the row
@@ -1086,10 +1114,17 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     // One tile, general: any mix of prefix and extend rows, masks, ragged ends, any page size.  from = 1: the first
     // key block is already accumulated; issue_next = false: the next tile's loads are already in flight.
     auto tile_general = [&](int p0, int ring, int from, bool issue_next) __attribute__((always_inline)) {
+#ifdef PA_PROBE_DETAIL
+        const long long probe_i0 = clk ? clock64() : 0;
+#endif
         if (issue_next && p0 + kKT < kv_hi) {
             issue(p0 + kKT, ring ^ 1);  // the next tile flies during this tile's arithmetic
             load_slots(p0 + 2 * kKT);
         }
+#ifdef PA_PROBE_DETAIL
+        const long long probe_i1 = clk ? clock64() : 0;
+        probe_gen_issue += probe_i1 - probe_i0;
+#endif
         const bool not_ours = shared && p0 >= P && (p0 >= s_wave_own[2 * wave + 1] || p0 + kKT <= s_wave_own[2 * wave]);
         if (wave_on && p0 <= P + wave_i_last && !not_ours) {
             bool need_mask = false;
@@ -1098,6 +1133,9 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
 #pragma unroll 1
             for (int mb = from; mb < 2; ++mb) general_block(p0, mb, need_mask);
         }
+#ifdef PA_PROBE_DETAIL
+        if (clk) probe_gen_math += clock64() - probe_i1;
+#endif
     };
     // 0: the tile at p0 takes the general code; 1 / 2: the hand-scheduled one, the next tile lying wholly in the
     // prefix / wholly in the extend tokens (its rows clamp to the last valid key).  Uniform over the wave.
@@ -1165,6 +1203,9 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
                 while (tile_kind(p_end) == kind);
                 const int p_start = p0, ring_start = ring;
                 int st = 0;
+#ifdef PA_PROBE_DETAIL
+                const long long probe_r0 = clk ? clock64() : 0;
+#endif
                 const bf16x16 q01 = __builtin_shufflevector(qreg[0][0], qreg[0][1], 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
                 const bf16x16 q23 = __builtin_shufflevector(qreg[0][2], qreg[0][3], 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
                 const bf16x16 q45 = __builtin_shufflevector(qreg[0][4], qreg[0][5], 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
@@ -1196,6 +1237,12 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
                     fast_run_ext_d128(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
                                       k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
                                       uni_ptr(kx_g), uni_ptr(vx_g), c, c2);
+#ifdef PA_PROBE_DETAIL
+                if (clk) {
+                    probe_fast += clock64() - probe_r0;
+                    probe_nfast += (p0 - p_start) / kKT;
+                }
+#endif
                 if (((p0 - p_start) / kKT) & 1) move_read_addresses(ring_start);
                 // (the run fetched slot ids from the common list only: where the tile they are for holds a member's own
                 // prefix keys they are fetched again, from that member's list.  That tile is the next one, or, if the
@@ -1211,9 +1258,21 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
                 fast_allowed = false;
             }
         }
+#ifdef PA_PROBE_DETAIL
+        const long long probe_g0 = clk ? clock64() : 0;
+#endif
         tile_general(p0, ring, from, issue_next);
         next_tile();
+#ifdef PA_PROBE_DETAIL
+        if (clk) {
+            probe_gen += clock64() - probe_g0;
+            ++probe_ngen;
+        }
+#endif
     }
+#ifdef PA_PROBE_DETAIL
+    const long long probe_t1 = clk ? clock64() : 0;
+#endif
 
     if (clk && blockIdx.x % 997 == 7 && tid == 0) {
         atomicAdd(clk, static_cast<unsigned long long>(clock64() - clk_c0));
@@ -1252,6 +1311,18 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
             }
         }
     }
+#ifdef PA_PROBE_DETAIL
+    if (clk && blockIdx.x % 997 == 7 && tid == 0) {
+        atomicAdd(clk + 2, static_cast<unsigned long long>(probe_fast));
+        atomicAdd(clk + 3, static_cast<unsigned long long>(probe_nfast));
+        atomicAdd(clk + 4, static_cast<unsigned long long>(probe_gen));
+        atomicAdd(clk + 5, static_cast<unsigned long long>(probe_ngen));
+        atomicAdd(clk + 6, static_cast<unsigned long long>(clk_c0 - probe_t0));
+        atomicAdd(clk + 7, static_cast<unsigned long long>(clock64() - probe_t1));
+        atomicAdd(clk + 8, static_cast<unsigned long long>(probe_gen_issue));
+        atomicAdd(clk + 9, static_cast<unsigned long long>(probe_gen_math));
+    }
+#endif
 }
 
 // Merge of the parts of a split tile: out = sum_s 2^(m_s - m) O_s / sum_s 2^(m_s - m) l_s over the parts s.
@@ -1355,6 +1426,16 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
     unsigned page_magic = 0;
     page_divider(page_size, &page_shift, &page_magic, &page_mshift);
     const dim3 grid(static_cast<unsigned>(p.items_cap) * Hkv);
+#ifdef PA_PROBE_DETAIL
+    // (experiments: more LDS per workgroup than it uses, so that only one fits a compute unit)
+    const char* pad_env = getenv("PA_PROBE_LDS_PAD");
+    const size_t lds_pad = pad_env ? static_cast<size_t>(atol(pad_env)) : 0;
+    if (lds_pad)
+        PA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&extend_bf16_kernel<D, NW, RB>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes + lds_pad)));
+#else
+    constexpr size_t lds_pad = 0;
+#endif
     // The hand-scheduled tile addresses K/V rows with 32-bit byte offsets and 24-bit multiplies: it needs a
     // power-of-two page size, a pool below 4 GB, and extend tensors below 4 GB.
     const int64_t rowb = static_cast<int64_t>(D) * 2;
@@ -1364,7 +1445,7 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
                         num_slots / page_size < (1 << 24) && T_total < (1 << 24) && T_total * Hkv * rowb < (int64_t{1} << 32);
     {
         ProfScope prof(kProfExtend, stream);
-        hipLaunchKernelGGL((extend_bf16_kernel<D, NW, RB>), grid, dim3(NW * 64), lds_bytes, stream,
+        hipLaunchKernelGGL((extend_bf16_kernel<D, NW, RB>), grid, dim3(NW * 64), lds_bytes + lds_pad, stream,
                            static_cast<const __hip_bfloat16*>(q_ext), static_cast<const __hip_bfloat16*>(k_ext),
                            static_cast<const __hip_bfloat16*>(v_ext), static_cast<const __hip_bfloat16*>(kv_pool), slot_idx,
                            Hq, Hkv, page_size, page_shift, page_magic, page_mshift, static_cast<int>(num_slots), fast_ok,
@@ -1407,21 +1488,13 @@ size_t pa_extend_workspace_bytes_bf16(int B, int64_t T, int64_t max_kv_len, int 
     return pa::make_plan(B, T, max_kv_len, Hq, Hkv, D).total;
 }
 
-// Called by pa_extend_attention after argument validation.
-int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v_ext, const void* kv_pool,
-                             const int32_t* slot_idx, const int32_t* slot_offsets, const int32_t* prefix_len,
-                             const int32_t* ext_len, const int32_t* ext_offsets, int B, int64_t T, int64_t max_kv_len,
-                             int Hq, int Hkv, int D, int page_size, int64_t num_slots, float scale, void* out,
-                             void* workspace, size_t workspace_bytes, hipStream_t stream) {
+// The work of a bf16 call once its plan and its workspace are settled.
+static int run_extend_bf16(pa::ExtendPlan p, const void* q_ext, const void* k_ext, const void* v_ext, const void* kv_pool,
+                           const int32_t* slot_idx, const int32_t* slot_offsets, const int32_t* prefix_len,
+                           const int32_t* ext_len, const int32_t* ext_offsets, int B, int64_t T, int Hq, int Hkv, int D,
+                           int page_size, int64_t num_slots, float scale, void* out, void* workspace, hipStream_t stream) {
     using namespace pa;
-    PA_REQUIRE(scale > 0.f && scale < INFINITY, "pa_extend_attention: scale must be positive and finite");
-    PA_REQUIRE(num_slots <= INT32_MAX, "pa_extend_attention: num_slots exceeds the int32 range of slot ids");
-    PA_REQUIRE(static_cast<int64_t>(page_size) * Hkv * D * 4 < (int64_t{1} << 31), "pa_extend_attention: a page of %d tokens x %d heads is too large", page_size, Hkv);
-    ExtendPlan p = make_plan(B, T, max_kv_len, Hq, Hkv, D);  // (sized for shared row tiles whether or not they are on)
     if (!g_row_sharing.load()) p.pack = 0;
-    if (workspace_bytes < p.total || workspace == nullptr)
-        return fail(PA_ENOMEM, "pa_extend_attention: workspace of %zu bytes given, %zu needed", workspace_bytes, p.total);
-    PA_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255u) == 0, "pa_extend_attention: workspace must be 256-byte aligned");
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     int32_t* hdr = reinterpret_cast<int32_t*>(ws);
     int32_t* order = reinterpret_cast<int32_t*>(ws + p.off_order);
@@ -1450,4 +1523,27 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
                               scale_log2e, out, hdr, tile_tab, tile_aux, member_tab, item_tab, merge_tiles, part_o, part_ml, clk, stream);
     PA_HIP(hipGetLastError());
     return PA_OK;
+}
+
+static int check_bf16_args(float scale, int64_t num_slots, int page_size, int Hkv, int D) {
+    PA_REQUIRE(scale > 0.f && scale < INFINITY, "pa_extend_attention: scale must be positive and finite");
+    PA_REQUIRE(num_slots <= INT32_MAX, "pa_extend_attention: num_slots exceeds the int32 range of slot ids");
+    PA_REQUIRE(static_cast<int64_t>(page_size) * Hkv * D * 4 < (int64_t{1} << 31), "pa_extend_attention: a page of %d tokens x %d heads is too large", page_size, Hkv);
+    return PA_OK;
+}
+
+// Called by pa_extend_attention after argument validation.
+int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v_ext, const void* kv_pool,
+                             const int32_t* slot_idx, const int32_t* slot_offsets, const int32_t* prefix_len,
+                             const int32_t* ext_len, const int32_t* ext_offsets, int B, int64_t T, int64_t max_kv_len,
+                             int Hq, int Hkv, int D, int page_size, int64_t num_slots, float scale, void* out,
+                             void* workspace, size_t workspace_bytes, hipStream_t stream) {
+    using namespace pa;
+    if (const int rc = check_bf16_args(scale, num_slots, page_size, Hkv, D)) return rc;
+    const ExtendPlan p = make_plan(B, T, max_kv_len, Hq, Hkv, D);  // (sized for shared row tiles whether or not they are on)
+    if (workspace_bytes < p.total || workspace == nullptr)
+        return fail(PA_ENOMEM, "pa_extend_attention: workspace of %zu bytes given, %zu needed", workspace_bytes, p.total);
+    PA_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255u) == 0, "pa_extend_attention: workspace must be 256-byte aligned");
+    return run_extend_bf16(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, B, T, Hq,
+                           Hkv, D, page_size, num_slots, scale, out, workspace, stream);
 }

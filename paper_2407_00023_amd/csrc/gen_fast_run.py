@@ -28,17 +28,16 @@ KS, NB = 8, 4            # k-slices of QK^T, head-dim blocks of O^T
 ROWB, TILEB, STAGEB = 256, 16384, 32768
 UPW, RPB = 4, 4          # 1 KB load blocks per wave and tensor, rows per block
 
-PD = 3                   # LDS fragments in flight ahead of their MFMA
-NBUF = PD + 1            # fragment buffers per operand kind
-PRIO = False             # raise the wave's issue priority around its MFMAs
+NFR = 8                  # fragment buffers (K and V^T fragments share them: the two kinds are read in different phases)
+PD = 5                   # LDS fragments in flight ahead of their MFMA
+PAIRWAIT, DEFER_SUM, M0_FIRST, FAST_SLOTS, SETTLE = True, True, True, True, False   # (switches for experiments)
 
 # ---- vector registers (everything from v44 up belongs to the assembly) ----
 ACC = [192 + 16 * b for b in range(NB)]
 Q = [160 + 4 * s for s in range(KS)]
 SC0, SC1 = 144, 128
 PB0, PB1 = 120, 112
-KF = [96 + 4 * i for i in range(4)]
-VF = [80 + 4 * i for i in range(4)]
+FR = [80 + 4 * i for i in range(NFR)]
 KRD = [72 + s for s in range(8)]
 VRD = [64 + i for i in range(8)]   # index b * 2 + h2
 SLN = [60, 61, 62, 63]
@@ -71,6 +70,7 @@ class Stream:
         self.lines = []
         self.lds = []      # ids of LDS reads in flight, oldest first
         self.next_id = 0
+        self.tail = []     # code placed behind the loop (rarely taken paths)
 
     def emit(self, text):
         self.lines.append(text)
@@ -91,7 +91,13 @@ class Stream:
 
 
 def tile(st, ext, ring, uid):
-    """One tile that sits in ring slot `ring`; the next tile is loaded into the other slot."""
+    """One tile that sits in ring slot `ring`; the next tile is loaded into the other slot.
+
+    Every instruction costs its wave an issue slot (four cycles, more for a few), whatever unit executes it, and a
+    wave runs two of its four phases at that limit: the schedule below is written for few instructions.  LDS
+    reads are awaited two fragments at a time; where the hardware wants wait states between two instructions (a write
+    of M0 and the load that uses it, a transcendental and the use of its result, the last MFMA of a score block and
+    the first ALU read of it - eleven issue slots) other work stands there instead of s_nop."""
     e = st.emit
     here, there = ring * STAGEB, (ring ^ 1) * STAGEB
     last = {}   # fragment number (0..15 K, 16..31 V) -> id of its last LDS read
@@ -99,29 +105,36 @@ def tile(st, ext, ring, uid):
     def read_frag(f):
         if f >= 32:
             return
+        buf = FR[f % NFR]
         if f < 16:   # K fragment: key block f // 8, k-slice f % 8
             blk, sl = divmod(f, 8)
             off = here + blk * 32 * ROWB
             o = f" offset:{off}" if off else ""
-            last[f] = st.lds_read(f"ds_read_b128 {v(KF[f % NBUF], 4)}, {v(KRD[sl])}{o}")
+            last[f] = st.lds_read(f"ds_read_b128 {v(buf, 4)}, {v(KRD[sl])}{o}")
         else:        # V^T fragment: key block g // 8, 16-key group (g % 8) // 4, head-dim block g % 4
             g = f - 16
             blk, j = divmod(g, 8)
             cs, b = divmod(j, NB)
             off = here + blk * 32 * ROWB + cs * 16 * ROWB
             o = f" offset:{off}" if off else ""
-            st.lds_read(f"ds_read_b64_tr_b16 {v(VF[g % NBUF], 2)}, {v(VRD[2 * b])}{o}")
-            last[f] = st.lds_read(f"ds_read_b64_tr_b16 {v(VF[g % NBUF] + 2, 2)}, {v(VRD[2 * b + 1])}{o}")
+            st.lds_read(f"ds_read_b64_tr_b16 {v(buf, 2)}, {v(VRD[2 * b])}{o}")
+            last[f] = st.lds_read(f"ds_read_b64_tr_b16 {v(buf + 2, 2)}, {v(VRD[2 * b + 1])}{o}")
+
+    def wait_pair(f):
+        """Before the MFMA of an even fragment: it and the next one have arrived."""
+        if not PAIRWAIT:
+            st.wait_lds(last[f])
+        elif f % 2 == 0:
+            st.wait_lds(last[f + 1])
 
     def mfma(dst, a, b, c):
-        if PRIO:
-            e("s_setprio 1")
         e(f"v_mfma_f32_32x32x16_bf16 {dst}, {a}, {b}, {c}")
-        if PRIO:
-            e("s_setprio 0")
 
     def load_piece(u, which):
         m0 = there + u * 1024 + (TILEB if which else 0)
+        # (M0 first: the address arithmetic that follows is the wait state the load needs after it)
+        if M0_FIRST:
+            e(f"s_add_u32 m0, {s(C_LDSW)}, {m0}" if m0 else f"s_mov_b32 m0, {s(C_LDSW)}")
         if which == 0:
             if ext:
                 # position of the row in the extend tokens, clamped to the last valid key; times the token stride
@@ -143,74 +156,118 @@ def tile(st, ext, ring, uid):
         else:
             e(f"v_xad_u32 {v(T[3])}, {v(VOFF0)}, {16 * u}, {v(ROWOFF)}")
             addr, base = T[3], BASE_V
-        e(f"s_add_u32 m0, {s(C_LDSW)}, {m0}" if m0 else f"s_mov_b32 m0, {s(C_LDSW)}")
-        e("s_nop 0")
+        if not M0_FIRST:
+            e(f"s_add_u32 m0, {s(C_LDSW)}, {m0}" if m0 else f"s_mov_b32 m0, {s(C_LDSW)}")
+            e("s_nop 0")
         e(f"global_load_lds_dwordx4 {v(addr)}, {s(base, 2)}")
 
-    def exp_piece(sc, pb, idx, f_next):
-        """Probabilities of elements 2 idx, 2 idx + 1 of a score block.  The LDS read of fragment f_next (or an
-        s_nop) separates the exponentials from the first use of their results."""
+    pending = []   # probability pair whose row-sum contribution is still to be added: [register]
+
+    def flush_sum():
+        if pending:
+            e(f"v_dot2c_f32_bf16 {v(LSUM)}, {ONES}, {v(pending.pop())}")
+
+    def exp_piece(sc, pb, idx):
+        """Probabilities of elements 2 idx, 2 idx + 1 of a score block.  The row-sum step of the piece before stands
+        between the exponentials and the first use of their results."""
         e(f"v_fma_f32 {v(T[4])}, {v(sc + 2 * idx)}, {s(C_SCALE)}, {v(NEGM)}")
         e(f"v_fma_f32 {v(T[5])}, {v(sc + 2 * idx + 1)}, {s(C_SCALE)}, {v(NEGM)}")
         e(f"v_exp_f32 {v(T[4])}, {v(T[4])}")
         e(f"v_exp_f32 {v(T[5])}, {v(T[5])}")
-        if f_next < 32:
-            read_frag(f_next)
+        if pending:
+            flush_sum()
         else:
             e("s_nop 0")
         e(f"v_cvt_pk_bf16_f32 {v(pb + idx)}, {v(T[4])}, {v(T[5])}")
-        e(f"v_dot2c_f32_bf16 {v(LSUM)}, {ONES}, {v(pb + idx)}")
+        pending.append(pb + idx)
+        if not DEFER_SUM:
+            flush_sum()
 
-    def settle():
-        e("s_nop 7")
-        e("s_nop 3")
+    def end_of_sums(f):
+        """The last row-sum step of a key block, and then three instructions before anything but another such step
+        reads the sum (the result of a dot-product instruction reaches other ALU instructions three issue slots
+        late, and the hardware does not wait for it): the LDS reads this MFMA slot (fragment f) still owes and the
+        wait that the next MFMA needs anyway."""
+        flush_sum()
+        n0 = len(st.lines)
+        read_frag(f + PD)
+        st.wait_lds(last[f + 2])
+        while len(st.lines) - n0 < 3:
+            e("s_nop 0")
+
+    def slot_ids():
+        """Slot ids of this lane's four rows in the tile after the next one (rows outside the prefix repeat the last
+        prefix slot).  Usually that tile lies wholly in the prefix: one address, four loads at fixed distances."""
+        e(f"s_add_u32 {s(S_T[3])}, {s(P0)}, 128")
+        e(f"s_add_u32 {s(S_T[2])}, {s(P0)}, 191")
+        e(f"s_cmp_le_i32 {s(S_T[2])}, {s(C_P1)}")
+        e(f"s_cbranch_scc0 Lslow{ring}{uid}" if FAST_SLOTS else f"s_branch Lslow{ring}{uid}")
+        e(f"v_add_lshl_u32 {v(T[6])}, {s(S_T[3])}, {v(ROWI)}, 2")
+        for u in range(UPW):
+            o = f" offset:{4 * RPB * u}" if u else ""
+            e(f"global_load_dword {v(SLN[u])}, {v(T[6])}, {s(SLOTS, 2)}{o}")
+        e(f"Lback{ring}{uid}:")
+        t = st.tail
+        t.append(f"Lslow{ring}{uid}:")
+        for u in range(UPW):
+            t.append(f"s_add_u32 {s(S_T[2])}, {s(S_T[3])}, {RPB * u}")
+            t.append(f"v_add_u32 {v(T[6])}, {s(S_T[2])}, {v(ROWI)}")
+            t.append(f"v_min_i32 {v(T[6])}, {s(C_P1)}, {v(T[6])}")
+            t.append(f"v_lshlrev_b32 {v(T[6])}, 2, {v(T[6])}")
+            t.append(f"global_load_dword {v(SLN[u])}, {v(T[6])}, {s(SLOTS, 2)}")
+        t.append(f"s_branch Lback{ring}{uid}")
 
     for f in range(PD):
         read_frag(f)
-    # ---- phase A ----
+    # ---- phase A: S0 = K(block 0) Q^T | the next tile's loads ----
     for sl in range(KS):
-        st.wait_lds(last[sl])
-        mfma(v(SC0, 16), v(KF[sl % NBUF], 4), v(Q[sl], 4), v(SC0, 16) if sl else "0")
+        wait_pair(sl)
+        mfma(v(SC0, 16), v(FR[sl % NFR], 4), v(Q[sl], 4), v(SC0, 16) if sl else "0")
         read_frag(sl + PD)
         load_piece(sl // 2, sl % 2)
-    # ---- phase B ----
+    # ---- phase B: S1 = K(block 1) Q^T | slot ids of the tile after next, probabilities of block 0 ----
     e(f"v_mov_b32 {v(LSUM)}, 0")
     for sl in range(KS):
         f = KS + sl
-        st.wait_lds(last[f])
-        mfma(v(SC1, 16), v(KF[f % NBUF], 4), v(Q[sl], 4), v(SC1, 16) if sl else "0")
-        if not ext and sl < UPW:
-            # slot id of this lane's row in the tile after the next one (rows outside the prefix repeat the last prefix slot)
-            e(f"s_add_u32 {s(S_T[3])}, {s(P0)}, {128 + RPB * sl}")
-            e(f"v_add_u32 {v(T[6])}, {s(S_T[3])}, {v(ROWI)}")
-            e(f"v_min_i32 {v(T[6])}, {s(C_P1)}, {v(T[6])}")
-            e(f"v_lshlrev_b32 {v(T[6])}, 2, {v(T[6])}")
-            e(f"global_load_dword {v(SLN[sl])}, {v(T[6])}, {s(SLOTS, 2)}")
-        if sl == 0:
-            settle()   # S0 was last written by the MFMA before this slot's
-        exp_piece(SC0, PB0, sl, f + PD)
+        wait_pair(f)
+        mfma(v(SC1, 16), v(FR[f % NFR], 4), v(Q[sl], 4), v(SC1, 16) if sl else "0")
+        if sl < KS - 1:
+            read_frag(f + PD)
+        if sl == 0 and not ext:
+            slot_ids()   # (also the distance block 0's scores need from the MFMA that wrote them last)
+        elif sl == 0:
+            e("s_nop 7")
+        if sl == 0 and SETTLE:
+            e("s_nop 7")
+            e("s_nop 3")
+        exp_piece(SC0, PB0, sl)
+    end_of_sums(2 * KS - 1)
     e(f"v_cmp_lt_u32 vcc, {LIMIT}, {v(LSUM)}")
     e(f"s_cbranch_vccnz Lover1{uid}")
     e(f"v_add_f32 {v(L)}, {v(L)}, {v(LSUM)}")
     e(f"v_mov_b32 {v(LSUM)}, 0")
-    # ---- phase C ----
+    # ---- phase C: O += V(block 0) P0 | probabilities of block 1 (its scores were last written thirteen issue slots ago) ----
     for j in range(8):
         f = 16 + j
-        st.wait_lds(last[f])
+        wait_pair(f)
         cs, b = divmod(j, NB)
-        mfma(v(ACC[b], 16), v(VF[j % NBUF], 4), v(PB0 + 4 * cs, 4), v(ACC[b], 16))
-        if j == 0:
-            settle()   # S1 was last written by the MFMA before this slot's
-        exp_piece(SC1, PB1, j, f + PD)
+        mfma(v(ACC[b], 16), v(FR[f % NFR], 4), v(PB0 + 4 * cs, 4), v(ACC[b], 16))
+        if j < 7:
+            read_frag(f + PD)
+        if j == 0 and SETTLE:
+            e("s_nop 7")
+            e("s_nop 3")
+        exp_piece(SC1, PB1, j)
+    end_of_sums(23)
     e(f"v_cmp_lt_u32 vcc, {LIMIT}, {v(LSUM)}")
     e(f"s_cbranch_vccnz Lover2{uid}")
     e(f"v_add_f32 {v(L)}, {v(L)}, {v(LSUM)}")
-    # ---- phase D ----
+    # ---- phase D: O += V(block 1) P1 ----
     for j in range(8):
         f = 24 + j
-        st.wait_lds(last[f])
+        wait_pair(f)
         cs, b = divmod(j, NB)
-        mfma(v(ACC[b], 16), v(VF[(8 + j) % NBUF], 4), v(PB1 + 4 * cs, 4), v(ACC[b], 16))
+        mfma(v(ACC[b], 16), v(FR[f % NFR], 4), v(PB1 + 4 * cs, 4), v(ACC[b], 16))
         read_frag(f + PD)
     assert not st.lds, st.lds
     # ---- this wave's part of the next tile has landed, and so has everyone else's ----
@@ -247,6 +304,8 @@ def gen(ext):
     tile(st, ext, 1, uid)
     e(f"s_cbranch_scc1 Lring0{uid}")
     e(f"s_branch Ldone{uid}")
+    for ln in st.tail:
+        e(ln)
     e(f"Lover1{uid}:")
     e(f"s_mov_b32 {s(STATUS)}, 1")
     e(f"s_branch Ldone{uid}")
