@@ -305,6 +305,25 @@ int pa_extend_attention(const void* q_ext, const void* k_ext, const void* v_ext,
                         int dtype, float scale, void* out, void* workspace, size_t workspace_bytes,
                         void* stream);
 
+/* pa_extend_attention for callers that cannot allocate device memory - code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc - and so cannot supply a workspace: the same computation with the same
+ * arguments (minus workspace and workspace_bytes), its work list and partial results kept in a buffer of
+ * PA_STATIC_SCRATCH_BYTES that is part of the library's code object (every GPU the library runs on holds its copy from
+ * the first use until the process ends).  The call allocates nothing and frees nothing.  To fit that buffer the
+ * launch aims at one work item per workgroup slot instead of three, so long key ranges are cut into fewer parts
+ * (results agree with pa_extend_attention within the tolerance of the dtype, bit for bit where no row tile is split);
+ * a batch whose plan still does not fit is refused with PA_ENOMEM and a message that names both sizes, and nothing
+ * is launched.  All calls on one GPU share that GPU's buffer: calls that overlap in time on one GPU - on different
+ * streams or from different threads - race, and the caller must order them.  Nothing in the buffer has to be zero
+ * beforehand (each call writes every word it later reads).  The very first call on a device looks the buffer's
+ * address up (hipGetSymbolAddress); make it once outside any stream capture.  PA_F32 needs no workspace and simply runs. */
+#define PA_STATIC_SCRATCH_BYTES (80u << 20)
+int pa_extend_attention_static(const void* q_ext, const void* k_ext, const void* v_ext, const void* kv_pool,
+                               const int32_t* slot_idx, const int32_t* slot_offsets, const int32_t* prefix_len,
+                               const int32_t* ext_len, const int32_t* ext_offsets, int B, int64_t T,
+                               int64_t max_kv_len, int Hq, int Hkv, int D, int page_size, int64_t num_slots,
+                               int dtype, float scale, void* out, void* stream);
+
 /* Whether the most recent bf16 pa_extend_attention launch that used `workspace` (device pointer) could lay out its
  * work.  The launch is sized from the host values T and max_kv_len; if ext_len on the device adds up to more
  * row tiles than T allows, or the key ranges to more parts than max_kv_len allows, the kernels compute nothing, write

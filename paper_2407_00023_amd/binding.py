@@ -59,6 +59,7 @@ _SIGS = {
     "pa_extend_workspace_bytes": (_sz, [_i, _i64, _i64, _i, _i, _i, _i]),
     "pa_match_prefixes": (_i, [_vp, _vp, _vp, _i, _vp, _vp, _vp]),
     "pa_extend_attention": (_i, [_vp] * 9 + [_i, _i64, _i64, _i, _i, _i, _i, _i64, _i, _f, _vp, _vp, _sz, _vp]),
+    "pa_extend_attention_static": (_i, [_vp] * 9 + [_i, _i64, _i64, _i, _i, _i, _i, _i64, _i, _f, _vp, _vp]),
     "pa_extend_status": (_i, [_vp, _vp]),
     "pa_extend_set_row_sharing": (_i, [_i]),
     "pa_append_kv": (_i, [_vp, _vp, _vp, _vp, _i64, _i, _i, _i, _i64, _i, _vp]),
@@ -364,6 +365,22 @@ def extend_attention(q_ext: torch.Tensor, k_ext: torch.Tensor, v_ext: torch.Tens
                                     _ptr(slot_offsets), _ptr(prefix_len), _ptr(ext_len), _ptr(ext_offsets), B, T,
                                     max_kv_len, Hq, Hkv, D, page_size, num_slots, dt, float(scale), _ptr(out),
                                     _ptr(workspace), wbytes, _stream(stream)), "pa_extend_attention")
+    return out
+
+
+def extend_attention_static(q_ext: torch.Tensor, k_ext: torch.Tensor, v_ext: torch.Tensor, kv_pool: torch.Tensor,
+                            slot_idx: torch.Tensor, slot_offsets: torch.Tensor, prefix_len: torch.Tensor,
+                            ext_len: torch.Tensor, ext_offsets: torch.Tensor, scale: float, *, page_size: int,
+                            num_slots: int, max_kv_len: int, out: torch.Tensor, stream=None) -> torch.Tensor:
+    """pa_extend_attention_static: as extend_attention, with the library's own scratch buffer as workspace; `out` is
+    the caller's (nothing is allocated here either)."""
+    T, Hq, D = q_ext.shape
+    Hkv = k_ext.shape[1]
+    B = prefix_len.numel()
+    _check(_lib.pa_extend_attention_static(_ptr(q_ext), _ptr(k_ext), _ptr(v_ext), _ptr(kv_pool), _ptr(slot_idx),
+                                           _ptr(slot_offsets), _ptr(prefix_len), _ptr(ext_len), _ptr(ext_offsets), B, T,
+                                           max_kv_len, Hq, Hkv, D, page_size, num_slots, _DTYPES[q_ext.dtype], float(scale),
+                                           _ptr(out), _stream(stream)), "pa_extend_attention_static")
     return out
 
 

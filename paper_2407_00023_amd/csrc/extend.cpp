@@ -20,6 +20,12 @@ extern "C" size_t pa_extend_workspace_bytes(int B, int64_t T, int64_t max_kv_len
     return 0;
 }
 
+int pa_extend_attention_bf16_static(const void* q_ext, const void* k_ext, const void* v_ext, const void* kv_pool,
+                                    const int32_t* slot_idx, const int32_t* slot_offsets, const int32_t* prefix_len,
+                                    const int32_t* ext_len, const int32_t* ext_offsets, int B, int64_t T,
+                                    int64_t max_kv_len, int Hq, int Hkv, int D, int page_size, int64_t num_slots,
+                                    float scale, void* out, hipStream_t stream);
+
 // What both entry points ask of their arguments.  *nothing_to_do: an empty batch (no pointer is looked at then).
 static int check_extend_args(const void* q_ext, const void* k_ext, const void* v_ext, const void* kv_pool,
                              const int32_t* slot_offsets, const int32_t* prefix_len, const int32_t* ext_len,
@@ -62,4 +68,22 @@ extern "C" int pa_extend_attention(const void* q_ext, const void* k_ext, const v
     return pa_extend_attention_bf16(q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len,
                                     ext_offsets, B, T, max_kv_len, Hq, Hkv, D, page_size, num_slots, scale, out,
                                     workspace, workspace_bytes, s);
+}
+
+extern "C" int pa_extend_attention_static(const void* q_ext, const void* k_ext, const void* v_ext, const void* kv_pool,
+                                          const int32_t* slot_idx, const int32_t* slot_offsets, const int32_t* prefix_len,
+                                          const int32_t* ext_len, const int32_t* ext_offsets, int B, int64_t T,
+                                          int64_t max_kv_len, int Hq, int Hkv, int D, int page_size, int64_t num_slots,
+                                          int dtype, float scale, void* out, void* stream) {
+    bool nothing = false;
+    if (const int rc = check_extend_args(q_ext, k_ext, v_ext, kv_pool, slot_offsets, prefix_len, ext_len, ext_offsets, B, T,
+                                         max_kv_len, Hq, Hkv, D, page_size, num_slots, dtype, out, &nothing))
+        return rc;
+    if (nothing) return PA_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dtype == PA_F32)  // (the fp32 kernel uses no workspace at all)
+        return pa_extend_attention_f32(q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len,
+                                       ext_offsets, B, T, Hq, Hkv, D, page_size, num_slots, scale, out, s);
+    return pa_extend_attention_bf16_static(q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len,
+                                           ext_offsets, B, T, max_kv_len, Hq, Hkv, D, page_size, num_slots, scale, out, s);
 }

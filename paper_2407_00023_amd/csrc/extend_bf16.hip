@@ -34,6 +34,7 @@
 
 #include <atomic>
 #include <cstdlib>
+#include <mutex>
 #include <type_traits>
 
 #include "common.h"
@@ -59,6 +60,7 @@ constexpr int kKT = 64;                  // key tokens per tile
 constexpr int kStages = 2;               // LDS ring: one tile being read, one being filled
 constexpr int kWgSlots = 512;            // workgroups resident at once: two on each of the 256 compute units
 constexpr int kRounds = 3;               // the plan aims at about this many work items per workgroup slot
+constexpr int kRoundsStatic = 1;         // ... with the library's own scratch buffer as workspace (fewer partial results)
 constexpr int kMinChunkTiles = 8;        // never split below this many key tiles (512 keys) per part
 constexpr int kItemOverhead = 4;         // fixed cost of a work item, in key tiles (its prologue and epilogue)
 constexpr int kMaxParts = 64;            // parts of one row tile at most
@@ -1546,4 +1548,52 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
     PA_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255u) == 0, "pa_extend_attention: workspace must be 256-byte aligned");
     return run_extend_bf16(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, B, T, Hq,
                            Hkv, D, page_size, num_slots, scale, out, workspace, stream);
+}
+
+// ---------------------------------------------------------------------------------------
+// The variant for callers that cannot allocate: its workspace is a buffer that is part of the library's code object.
+// Every GPU that loads the library holds its own copy of the array at its own address; in host code the array's name
+// is only a handle for hipGetSymbolAddress, never a device address.
+// ---------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[PA_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, looked up once per device.
+int scratch_of_current_device(void** out) {
+    int dev = -1;
+    PA_HIP(hipGetDevice(&dev));
+    PA_REQUIRE(dev >= 0 && dev < kMaxDevices, "pa_extend_attention_static: device ordinal %d not supported", dev);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* ptr = nullptr;
+        PA_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        PA_REQUIRE(ptr != nullptr && (reinterpret_cast<uintptr_t>(ptr) & 255u) == 0, "pa_extend_attention_static: bad scratch address");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return PA_OK;
+}
+}  // namespace
+
+// Called by pa_extend_attention_static after argument validation.
+int pa_extend_attention_bf16_static(const void* q_ext, const void* k_ext, const void* v_ext, const void* kv_pool,
+                                    const int32_t* slot_idx, const int32_t* slot_offsets, const int32_t* prefix_len,
+                                    const int32_t* ext_len, const int32_t* ext_offsets, int B, int64_t T,
+                                    int64_t max_kv_len, int Hq, int Hkv, int D, int page_size, int64_t num_slots,
+                                    float scale, void* out, hipStream_t stream) {
+    using namespace pa;
+    if (const int rc = check_bf16_args(scale, num_slots, page_size, Hkv, D)) return rc;
+    // (one work item per workgroup slot is aimed at instead of three: a third of the partial results at most)
+    const ExtendPlan p = make_plan(B, T, max_kv_len, Hq, Hkv, D, kRoundsStatic);
+    if (p.total > PA_STATIC_SCRATCH_BYTES)
+        return fail(PA_ENOMEM, "pa_extend_attention_static: this batch needs %zu bytes of workspace, the library's own buffer holds %zu; "
+                               "use pa_extend_attention with a workspace of the caller's", p.total, static_cast<size_t>(PA_STATIC_SCRATCH_BYTES));
+    void* ws = nullptr;
+    if (const int rc = scratch_of_current_device(&ws)) return rc;
+    return run_extend_bf16(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, B, T, Hq,
+                           Hkv, D, page_size, num_slots, scale, out, ws, stream);
 }
