@@ -101,17 +101,18 @@ static inline size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
 // the end of the list finer still evens the finish further and was measured to gain nothing: while every slot is
 // busy the chip is at its power limit, and the extra parts cost a merge.)  The bounds below follow from that rule
 // (see extend_plan_kernel).
-static ExtendPlan make_plan(int B, int64_t T, int64_t max_kv_len, int Hq, int Hkv, int D, int rounds = kRounds) {
+static ExtendPlan make_plan(int B, int64_t T, int64_t max_kv_len, int Hq, int Hkv, int D, int rounds = kRounds, int nw = 4) {
     ExtendPlan p{};
     p.rounds = rounds;
     const int G = Hq / Hkv;
-    p.nw = 4;
+    p.nw = nw;
     p.rb = 1;
     const int mt = 32 * p.rb * p.nw;
     const int64_t est = (T * G + mt - 1) / mt;
     p.pack = B <= kPackMax;
     p.tiles_cap = static_cast<int>(est + B);  // (packing only lowers the number of tiles)
-    p.slots = kWgSlots / Hkv > 0 ? kWgSlots / Hkv : 1;
+    const int wg_slots = nw == 8 ? kWgSlots / 2 : kWgSlots;  // (workgroups of eight waves: one on a compute unit)
+    p.slots = wg_slots / Hkv > 0 ? wg_slots / Hkv : 1;
     const int64_t by_rule = static_cast<int64_t>(p.slots) * rounds + 1;                  // sum of (parts - 1) over the tiles
     // (the key range of a shared tile holds the own keys of every member: of up to mt requests)
     const int64_t longest = p.pack ? max_kv_len * (B < mt ? (B > 0 ? B : 1) : mt) : max_kv_len;
@@ -747,7 +748,7 @@ __device__ __forceinline__ unsigned lds_address(const void* p) {
 }
 
 template <int D, int NW, int RB>
-__global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
+__global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf16_kernel(
     const __hip_bfloat16* __restrict__ q_ext, const __hip_bfloat16* __restrict__ k_ext,
     const __hip_bfloat16* __restrict__ v_ext, const __hip_bfloat16* __restrict__ pool,
     const int32_t* __restrict__ slot_idx, int Hq, int Hkv, int page_size, int page_shift, unsigned page_magic,
@@ -1142,7 +1143,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
     // 0: the tile at p0 takes the general code; 1 / 2: the hand-scheduled one, the next tile lying wholly in the
     // prefix / wholly in the extend tokens (its rows clamp to the last valid key).  Uniform over the wave.
     auto tile_kind = [&](int p0) __attribute__((always_inline)) -> int {
-        if (!(fast_ok && D == 128 && RB == 1 && NW == 4 && (smem_addr & 255u) == 0)) return 0;
+        if (!(fast_ok && D == 128 && RB == 1 && (NW == 4 || NW == 8) && (smem_addr & 255u) == 0)) return 0;
         bool no_mask = true;
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) no_mask &= p0 + kKT <= blk_vis_min[rb];
@@ -1197,7 +1198,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) have_m &= m_run[rb] != -INFINITY;
         if (kind != 0 && __all(have_m)) {
-            if constexpr (D == 128 && RB == 1 && NW == 4) {
+            if constexpr (D == 128 && RB == 1 && (NW == 4 || NW == 8)) {
                 // A run of steady-state tiles against the running maximum as it stands: scores never move it in there
                 // (a row's probabilities may reach 2^40 instead), the output accumulators are touched by MFMAs only.
                 int p_end = p0;
@@ -1223,7 +1224,8 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
                     const uint64_t lo = static_cast<uint32_t>(uni(static_cast<int>(a))), hi = static_cast<uint32_t>(uni(static_cast<int>(a >> 32)));
                     return reinterpret_cast<const void*>(lo | (hi << 32));
                 };
-                const i32x8 c = {uni(page_shift), uni(page_size - 1), uni(static_cast<int>(page_stride)), uni(num_slots - 1),
+                // (fast_ok == 2: the pool is too large for 32-bit byte offsets; rows are then counted in units of 256 bytes)
+                const i32x8 c = {uni(page_shift), uni(page_size - 1), uni(static_cast<int>(fast_ok == 2 ? page_stride / ROWB : page_stride)), uni(num_slots - 1),
                                  uni(P - 1), uni(static_cast<int>(x_stride)), uni(kv_hi - 1 - P),
                                  uni(static_cast<int>(smem_addr) + wave * (UPW * 1024))};
                 const i32x4 c2 = {uni(128), uni(192), uni(P), uni(__float_as_int(scale_log2e))};
@@ -1231,14 +1233,33 @@ __global__ __launch_bounds__(NW * 64, RB == 1 ? 2 : 1) void extend_bf16_kernel(
                 ring = uni(ring);
                 p_end = uni(p_end);
                 const int row_in_tile = wave * (UPW * RPB) + ld_rowl;
-                if (kind == 1)
-                    fast_run_pool_d128(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
-                                       k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
-                                       uni_ptr(pool_g), uni_ptr(pool_g + v_off32), c, c2);
-                else
-                    fast_run_ext_d128(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
-                                      k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
-                                      uni_ptr(kx_g), uni_ptr(vx_g), c, c2);
+                if constexpr (NW == 4) {
+                    if (kind == 1 && fast_ok == 2)
+                        fast_run_pool64_d128(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
+                                             k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
+                                             uni_ptr(pool_g), uni_ptr(pool_g + v_off32), c, c2);
+                    else if (kind == 1)
+                        fast_run_pool_d128(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
+                                           k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
+                                           uni_ptr(pool_g), uni_ptr(pool_g + v_off32), c, c2);
+                    else
+                        fast_run_ext_d128(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
+                                          k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
+                                          uni_ptr(kx_g), uni_ptr(vx_g), c, c2);
+                } else {
+                    if (kind == 1 && fast_ok == 2)
+                        fast_run_pool64_d128_w8(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
+                                                k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
+                                                uni_ptr(pool_g), uni_ptr(pool_g + v_off32), c, c2);
+                    else if (kind == 1)
+                        fast_run_pool_d128_w8(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
+                                              k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
+                                              uni_ptr(pool_g), uni_ptr(pool_g + v_off32), c, c2);
+                    else
+                        fast_run_ext_d128_w8(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
+                                             k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
+                                             uni_ptr(kx_g), uni_ptr(vx_g), c, c2);
+                }
 #ifdef PA_PROBE_DETAIL
                 if (clk) {
                     probe_fast += clock64() - probe_r0;
@@ -1438,13 +1459,19 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
 #else
     constexpr size_t lds_pad = 0;
 #endif
-    // The hand-scheduled tile addresses K/V rows with 32-bit byte offsets and 24-bit multiplies: it needs a
-    // power-of-two page size, a pool below 4 GB, and extend tensors below 4 GB.
+    // The hand-scheduled tiles multiply in 24 bits and take a power-of-two page size.  They address pool rows by
+    // 32-bit byte offsets where the pool is below 4 GB (1); by row numbers in units of 256 bytes, the byte address
+    // formed in 64 bits, where it is larger (2: D = 128, a pool base aligned to 256 bytes, up to 64 GB).  The extend
+    // tensors are addressed by 32-bit byte offsets in either case.
     const int64_t rowb = static_cast<int64_t>(D) * 2;
     const int64_t pool_bytes = num_slots * 2 * Hkv * rowb;
     const int64_t page_bytes = static_cast<int64_t>(page_size) * 2 * Hkv * rowb;
-    const int fast_ok = page_shift >= 0 && pool_bytes < (int64_t{1} << 32) && page_bytes < (1 << 24) &&
-                        num_slots / page_size < (1 << 24) && T_total < (1 << 24) && T_total * Hkv * rowb < (int64_t{1} << 32);
+    const bool common_ok = page_shift >= 0 && num_slots / page_size < (1 << 24) && T_total < (1 << 24) &&
+                           T_total * Hkv * rowb < (int64_t{1} << 32);
+    const bool ok32 = common_ok && pool_bytes < (int64_t{1} << 32) && page_bytes < (1 << 24);
+    const bool ok64 = common_ok && rowb == 256 && (reinterpret_cast<uintptr_t>(kv_pool) & 255u) == 0 &&
+                      page_bytes / rowb < (1 << 24) && pool_bytes / rowb < (int64_t{1} << 28);
+    const int fast_ok = ok32 ? 1 : ok64 ? 2 : 0;
     {
         ProfScope prof(kProfExtend, stream);
         hipLaunchKernelGGL((extend_bf16_kernel<D, NW, RB>), grid, dim3(NW * 64), lds_bytes + lds_pad, stream,
@@ -1486,8 +1513,21 @@ extern "C" int pa_extend_status(const void* workspace, void* stream) {
     return PA_OK;
 }
 
+// Waves per workgroup for a batch: eight (row tiles of 256 packed rows; a K/V tile then serves twice the rows and a
+// wave issues half the loads per tile) where requests bring many rows, four (finer row tiles, two workgroups on a
+// compute unit) otherwise.
+static int waves_for(int B, int64_t T, int Hq, int Hkv, int D) {
+#ifdef PA_PROBE_DETAIL
+    if (const char* e = getenv("PA_PROBE_NW")) return atoi(e) == 8 && D == 128 ? 8 : 4;
+#endif
+    (void)B; (void)T; (void)Hq; (void)Hkv; (void)D;
+    return 4;
+}
+
 size_t pa_extend_workspace_bytes_bf16(int B, int64_t T, int64_t max_kv_len, int Hq, int Hkv, int D) {
-    return pa::make_plan(B, T, max_kv_len, Hq, Hkv, D).total;
+    const size_t a = pa::make_plan(B, T, max_kv_len, Hq, Hkv, D, pa::kRounds, 4).total;
+    const size_t b = D == 128 ? pa::make_plan(B, T, max_kv_len, Hq, Hkv, D, pa::kRounds, 8).total : 0;
+    return a > b ? a : b;
 }
 
 // The work of a bf16 call once its plan and its workspace are settled.
@@ -1520,6 +1560,9 @@ static int run_extend_bf16(pa::ExtendPlan p, const void* q_ext, const void* k_ex
     if (D == 64)
         launch_extend<64, 4, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots, T,
                              scale_log2e, out, hdr, tile_tab, tile_aux, member_tab, item_tab, merge_tiles, part_o, part_ml, clk, stream);
+    else if (p.nw == 8)
+        launch_extend<128, 8, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots, T,
+                              scale_log2e, out, hdr, tile_tab, tile_aux, member_tab, item_tab, merge_tiles, part_o, part_ml, clk, stream);
     else
         launch_extend<128, 4, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots, T,
                               scale_log2e, out, hdr, tile_tab, tile_aux, member_tab, item_tab, merge_tiles, part_o, part_ml, clk, stream);
@@ -1542,7 +1585,7 @@ int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v
                              void* workspace, size_t workspace_bytes, hipStream_t stream) {
     using namespace pa;
     if (const int rc = check_bf16_args(scale, num_slots, page_size, Hkv, D)) return rc;
-    const ExtendPlan p = make_plan(B, T, max_kv_len, Hq, Hkv, D);  // (sized for shared row tiles whether or not they are on)
+    const ExtendPlan p = make_plan(B, T, max_kv_len, Hq, Hkv, D, kRounds, waves_for(B, T, Hq, Hkv, D));  // (sized for shared row tiles whether or not they are on)
     if (workspace_bytes < p.total || workspace == nullptr)
         return fail(PA_ENOMEM, "pa_extend_attention: workspace of %zu bytes given, %zu needed", workspace_bytes, p.total);
     PA_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255u) == 0, "pa_extend_attention: workspace must be 256-byte aligned");
@@ -1588,7 +1631,7 @@ int pa_extend_attention_bf16_static(const void* q_ext, const void* k_ext, const 
     using namespace pa;
     if (const int rc = check_bf16_args(scale, num_slots, page_size, Hkv, D)) return rc;
     // (one work item per workgroup slot is aimed at instead of three: a third of the partial results at most)
-    const ExtendPlan p = make_plan(B, T, max_kv_len, Hq, Hkv, D, kRoundsStatic);
+    const ExtendPlan p = make_plan(B, T, max_kv_len, Hq, Hkv, D, kRoundsStatic, waves_for(B, T, Hq, Hkv, D));
     if (p.total > PA_STATIC_SCRATCH_BYTES)
         return fail(PA_ENOMEM, "pa_extend_attention_static: this batch needs %zu bytes of workspace, the library's own buffer holds %zu; "
                                "use pa_extend_attention with a workspace of the caller's", p.total, static_cast<size_t>(PA_STATIC_SCRATCH_BYTES));

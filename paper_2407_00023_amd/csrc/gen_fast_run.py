@@ -90,7 +90,7 @@ class Stream:
         self.lds = self.lds[len(self.lds) - after:] if after else []
 
 
-def tile(st, ext, ring, uid):
+def tile(st, kind, ring, uid, upw):
     """One tile that sits in ring slot `ring`; the next tile is loaded into the other slot.
 
     Every instruction costs its wave an issue slot (four cycles, more for a few), whatever unit executes it, and a
@@ -99,6 +99,7 @@ def tile(st, ext, ring, uid):
     of M0 and the load that uses it, a transcendental and the use of its result, the last MFMA of a score block and
     the first ALU read of it - eleven issue slots) other work stands there instead of s_nop."""
     e = st.emit
+    ext, wide = kind == "ext", kind == "pool64"
     here, there = ring * STAGEB, (ring ^ 1) * STAGEB
     last = {}   # fragment number (0..15 K, 16..31 V) -> id of its last LDS read
 
@@ -143,6 +144,15 @@ def tile(st, ext, ring, uid):
                 e(f"v_add_u32 {v(T[0])}, {s(S_T[2])}, {v(ROWI)}")
                 e(f"v_min_i32 {v(T[0])}, {s(C_EXTMAX)}, {v(T[0])}")
                 e(f"v_mul_u32_u24 {v(ROWOFF)}, {s(C_XSTRIDE)}, {v(T[0])}")
+            elif wide:
+                # slot id (never outside the pool) -> page, offset in the page -> number of the K row from the head's
+                # first, in rows of 256 bytes, then in units of 16 bytes (the 64-bit shift-and-add shifts by 4 at most;
+                # below 2^32 for pools of up to 64 GB).  (T[0], T[1]) = (that number, 0) is its 64-bit operand.
+                e(f"v_med3_i32 {v(T[0])}, {v(SLN[u])}, 0, {s(C_NSLOT1)}")
+                e(f"v_lshrrev_b32 {v(T[6])}, {s(C_SHIFT)}, {v(T[0])}")
+                e(f"v_and_b32 {v(T[0])}, {s(C_MASK)}, {v(T[0])}")
+                e(f"v_mad_u32_u24 {v(T[0])}, {v(T[6])}, {s(C_PSTRIDE)}, {v(T[0])}")
+                e(f"v_lshlrev_b32 {v(T[0])}, 4, {v(T[0])}")
             else:
                 # slot id (never outside the pool) -> page, offset in the page -> byte offset of the K row
                 e(f"v_med3_i32 {v(T[0])}, {v(SLN[u])}, 0, {s(C_NSLOT1)}")
@@ -151,15 +161,28 @@ def tile(st, ext, ring, uid):
                 e(f"v_lshlrev_b32 {v(T[0])}, 8, {v(T[0])}")
                 e(f"v_mad_u32_u24 {v(ROWOFF)}, {v(T[1])}, {s(C_PSTRIDE)}, {v(T[0])}")
             x = [0, 64, s(C_128), s(C_192)][u]
-            e(f"v_xad_u32 {v(T[2])}, {v(KOFF0)}, {x}, {v(ROWOFF)}")
+            if wide:
+                # (the bases are 256-byte aligned: adding the offset inside the row never carries)
+                e(f"v_lshl_add_u64 {v(T[2], 2)}, {v(T[0], 2)}, 4, {s(BASE_K, 2)}")
+                e(f"v_xad_u32 {v(T[2])}, {v(KOFF0)}, {x}, {v(T[2])}")
+            else:
+                e(f"v_xad_u32 {v(T[2])}, {v(KOFF0)}, {x}, {v(ROWOFF)}")
             addr, base = T[2], BASE_K
         else:
-            e(f"v_xad_u32 {v(T[3])}, {v(VOFF0)}, {16 * u}, {v(ROWOFF)}")
-            addr, base = T[3], BASE_V
+            if wide:
+                e(f"v_lshl_add_u64 {v(T[4], 2)}, {v(T[0], 2)}, 4, {s(BASE_V, 2)}")
+                e(f"v_xad_u32 {v(T[4])}, {v(VOFF0)}, {16 * u}, {v(T[4])}")
+                addr, base = T[4], BASE_V
+            else:
+                e(f"v_xad_u32 {v(T[3])}, {v(VOFF0)}, {16 * u}, {v(ROWOFF)}")
+                addr, base = T[3], BASE_V
         if not M0_FIRST:
             e(f"s_add_u32 m0, {s(C_LDSW)}, {m0}" if m0 else f"s_mov_b32 m0, {s(C_LDSW)}")
             e("s_nop 0")
-        e(f"global_load_lds_dwordx4 {v(addr)}, {s(base, 2)}")
+        if wide:
+            e(f"global_load_lds_dwordx4 {v(addr, 2)}, off")
+        else:
+            e(f"global_load_lds_dwordx4 {v(addr)}, {s(base, 2)}")
 
     pending = []   # probability pair whose row-sum contribution is still to be added: [register]
 
@@ -203,13 +226,13 @@ def tile(st, ext, ring, uid):
         e(f"s_cmp_le_i32 {s(S_T[2])}, {s(C_P1)}")
         e(f"s_cbranch_scc0 Lslow{ring}{uid}" if FAST_SLOTS else f"s_branch Lslow{ring}{uid}")
         e(f"v_add_lshl_u32 {v(T[6])}, {s(S_T[3])}, {v(ROWI)}, 2")
-        for u in range(UPW):
+        for u in range(upw):
             o = f" offset:{4 * RPB * u}" if u else ""
             e(f"global_load_dword {v(SLN[u])}, {v(T[6])}, {s(SLOTS, 2)}{o}")
         e(f"Lback{ring}{uid}:")
         t = st.tail
         t.append(f"Lslow{ring}{uid}:")
-        for u in range(UPW):
+        for u in range(upw):
             t.append(f"s_add_u32 {s(S_T[2])}, {s(S_T[3])}, {RPB * u}")
             t.append(f"v_add_u32 {v(T[6])}, {s(S_T[2])}, {v(ROWI)}")
             t.append(f"v_min_i32 {v(T[6])}, {s(C_P1)}, {v(T[6])}")
@@ -219,12 +242,15 @@ def tile(st, ext, ring, uid):
 
     for f in range(PD):
         read_frag(f)
+    if wide:
+        e(f"v_mov_b32 {v(T[1])}, 0")
     # ---- phase A: S0 = K(block 0) Q^T | the next tile's loads ----
     for sl in range(KS):
         wait_pair(sl)
         mfma(v(SC0, 16), v(FR[sl % NFR], 4), v(Q[sl], 4), v(SC0, 16) if sl else "0")
         read_frag(sl + PD)
-        load_piece(sl // 2, sl % 2)
+        if sl < 2 * upw:
+            load_piece(sl // 2, sl % 2)
     # ---- phase B: S1 = K(block 1) Q^T | slot ids of the tile after next, probabilities of block 0 ----
     e(f"v_mov_b32 {v(LSUM)}, 0")
     for sl in range(KS):
@@ -278,7 +304,7 @@ def tile(st, ext, ring, uid):
     e(f"s_cmp_lt_i32 {s(P0)}, {s(PEND)}")
 
 
-def gen(ext):
+def gen(kind, upw):
     st = Stream()
     e = st.emit
     uid = "%="
@@ -298,10 +324,10 @@ def gen(ext):
     e(f"s_cbranch_scc0 Lring1{uid}")
     # the loop body is written out for both ring slots: every LDS offset is an immediate
     e(f"Lring0{uid}:")
-    tile(st, ext, 0, uid)
+    tile(st, kind, 0, uid, upw)
     e(f"s_cbranch_scc0 Ldone{uid}")
     e(f"Lring1{uid}:")
-    tile(st, ext, 1, uid)
+    tile(st, kind, 1, uid, upw)
     e(f"s_cbranch_scc1 Lring0{uid}")
     e(f"s_branch Ldone{uid}")
     for ln in st.tail:
@@ -316,22 +342,24 @@ def gen(ext):
     return st.lines
 
 
-def emit(name, ext):
-    lines = gen(ext)
+def emit(name, kind, upw=UPW):
+    lines = gen(kind, upw)
+    ext = kind == "ext"
     body = "\n".join(f'        "{ln}\\n\\t"' for ln in lines)
     clob = [f"v{i}" for i in range(FIRST_V, 53)] + [f"v{i}" for i in range(64, 160)] + [f"s{i}" for i in S_T] + ["vcc", "scc", "memory"]
     clobbers = ", ".join(f'"{c}"' for c in clob)
+    sln = ", ".join(f'"+{{v{SLN[u]}}}"(sl_next[{u}])' for u in range(upw))
     return f'''
-// {'next tile in the extend tokens' if ext else 'next tile in the prefix (pool rows through slot ids)'}
+// {'next tile in the extend tokens' if ext else 'next tile in the prefix (pool rows through slot ids' + (', 64-bit addresses' if kind == 'pool64' else '') + ')'}; a wave loads {upw} blocks of a tile
 __device__ __forceinline__ void {name}(f32x16& acc0, f32x16& acc1, f32x16& acc2, f32x16& acc3, const bf16x32& q_lo,
-                                       const bf16x32& q_hi, float& l_run, float neg_m, int32_t (&sl_next)[4],
+                                       const bf16x32& q_hi, float& l_run, float neg_m, int32_t (&sl_next)[{upw}],
                                        unsigned k_rd0, unsigned v_rd0, unsigned ld_koff0, unsigned ld_voff0, int row_in_tile,
                                        int& p0, int& ring, int& status, int p_end, const void* slots, const void* base_k,
                                        const void* base_v, const i32x8& c, const i32x4& c2) {{
     asm volatile(
 {body}
         : "+{{v[192:207]}}"(acc0), "+{{v[208:223]}}"(acc1), "+{{v[224:239]}}"(acc2), "+{{v[240:255]}}"(acc3), "+{{v59}}"(l_run),
-          "+{{v60}}"(sl_next[0]), "+{{v61}}"(sl_next[1]), "+{{v62}}"(sl_next[2]), "+{{v63}}"(sl_next[3]), "+{{s40}}"(p0),
+          {sln}, "+{{s40}}"(p0),
           "+{{s41}}"(ring), "={{s42}}"(status)
         : "{{v[160:175]}}"(q_lo), "{{v[176:191]}}"(q_hi), "{{v58}}"(neg_m), "{{v54}}"(k_rd0), "{{v53}}"(v_rd0), "{{v57}}"(ld_koff0),
           "{{v56}}"(ld_voff0), "{{v55}}"(row_in_tile), "{{s43}}"(p_end), "{{s[44:45]}}"(slots), "{{s[46:47]}}"(base_k),
@@ -341,8 +369,9 @@ __device__ __forceinline__ void {name}(f32x16& acc0, f32x16& acc1, f32x16& acc2,
 '''
 
 
-HEADER = '''// GENERATED by gen_fast_run.py - do not edit.  Runs of steady-state tiles of extend_bf16_kernel<128, 4, 1> as
-// gfx950 assembly with fixed registers; the generator describes the schedule.
+HEADER = '''// GENERATED by gen_fast_run.py - do not edit.  Runs of steady-state tiles of extend_bf16_kernel<128, 4, 1> (a wave
+// loads four 1 KB blocks of a K or V tile) and extend_bf16_kernel<128, 8, 1> (the _w8 functions: two blocks) as gfx950
+// assembly with fixed registers; the generator describes the schedule.
 //
 // Operands: acc0..3 output accumulators (head-dim blocks 0..3); q_lo / q_hi the eight query fragments (k-slices 0..3,
 // 4..7); l_run this lane's share of the row sum; neg_m minus the running maximum; sl_next the pool
@@ -351,15 +380,17 @@ HEADER = '''// GENERATED by gen_fast_run.py - do not edit.  Runs of steady-state
 // ld_koff0 / ld_voff0 byte offsets inside a K / V row of this lane's 16 bytes of load block 0; row_in_tile the row of
 // the tile this lane loads in block 0; p0 first key of the tile (advanced by 64 per tile done); ring its ring slot;
 // status 0 = ran to p_end, 1 / 2 = the tile at p0 outgrew the running maximum in key block 0 / 1 (see the kernel);
-// slots the request's slot ids; base_k / base_v where K / V rows are fetched from; c = {page shift, page mask, page
-// stride in bytes, num_slots - 1, P - 1, extend token stride in bytes, kv_hi - 1 - P, LDS address of this wave's load
+// slots the request's slot ids; base_k / base_v where K / V rows are fetched from (pool64: 256-byte aligned); c = {page
+// shift, page mask, page stride in bytes (pool64: in rows of 256 bytes), num_slots - 1, P - 1, extend token stride in bytes, kv_hi - 1 - P, LDS address of this wave's load
 // block 0 in ring slot 0}; c2 = {128, 192, P, bits of scale * log2(e)}.
 '''
 
 
 def main():
     here = os.path.dirname(os.path.abspath(__file__))
-    text = HEADER + emit("fast_run_pool_d128", False) + emit("fast_run_ext_d128", True)
+    text = (HEADER + emit("fast_run_pool_d128", "pool") + emit("fast_run_pool64_d128", "pool64") + emit("fast_run_ext_d128", "ext") +
+            emit("fast_run_pool_d128_w8", "pool", 2) + emit("fast_run_pool64_d128_w8", "pool64", 2) +
+            emit("fast_run_ext_d128_w8", "ext", 2))
     path = os.path.join(here, "fast_run_d128.inc")
     old = open(path).read() if os.path.exists(path) else None
     if old != text:

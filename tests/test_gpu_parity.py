@@ -509,6 +509,33 @@ def test_extend_reports_a_batch_larger_than_the_host_sizes(pa, gpu_device):
     assert torch.isfinite(out.float()).all() and not bool((out == 7.0).all())
 
 
+def test_extend_pool_beyond_4_gib(pa, gpu_device):
+    """A KV pool of 6.4 GB (1.5 M slots x 8 KV heads x 128 x bf16 x K and V): pool rows lie on either side of the 4 GiB line, so
+    byte offsets no longer fit 32 bits - the assembly runs address rows in units of 256 bytes and form the address in
+    64 bits, the general tile and append / gather compute in 64 bits throughout.  Every element against the oracle, and
+    the appended rows bit-exact."""
+    say("[case] pool beyond 4 GiB")
+    wl = W.tool_use(21, B=8, sys_len=1300, n_tools=3, tool_lo=100, tool_hi=500, ext_lo=20, ext_hi=160, num_slots=1_572_864)
+    row_bytes = 2 * wl.Hkv * wl.D * 2
+    page_off = (wl.pool_slots.astype(np.int64) // wl.page_size) * wl.page_size * row_bytes
+    assert (page_off < 2 ** 32).sum() > 100 and (page_off >= 2 ** 32).sum() > 100
+    g, o = GpuSide(wl, gpu_device), OracleSide(wl)
+    pl, si, out = g.step()
+    torch.cuda.synchronize()
+    pl_ref, si_ref = o.match()
+    assert_match_equal(wl, pl, si, pl_ref, si_ref)
+    err = np.abs(out_to_f64(out) - o.extend(pl_ref, si_ref)).max()
+    say(f"  max abs err {err:.3e}")
+    assert err <= TOL[wl.dtype]
+    o.append()
+    allslots = np.concatenate([wl.pool_slots, wl.new_slots])
+    gk, gv = pa.gather_kv(g.pool, torch.from_numpy(allslots).to(gpu_device), Hkv=wl.Hkv, D=wl.D, dtype=g.tdtype, **g.kw)
+    np.testing.assert_array_equal(gk.view(torch.int16).cpu().numpy(), o.pool_k[allslots].view(np.int16))
+    np.testing.assert_array_equal(gv.view(torch.int16).cpu().numpy(), o.pool_v[allslots].view(np.int16))
+    del g
+    torch.cuda.empty_cache()
+
+
 # ------------------------------------------------------------------------------------ full configs
 
 @pytest.fixture(scope="module")
