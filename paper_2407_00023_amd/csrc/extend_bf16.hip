@@ -777,8 +777,8 @@ __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf
     // (build option for experiments: where a workgroup's cycles go - clk[2..7] = cycles in runs of assembly tiles, tiles
     // done there, cycles in general tiles, their number, cycles before the key loop, cycles after it)
     const long long probe_t0 = clk ? clock64() : 0;
-    long long probe_fast = 0, probe_gen = 0, probe_gen_issue = 0, probe_gen_math = 0;
-    int probe_nfast = 0, probe_ngen = 0;
+    long long probe_fast = 0, probe_gen = 0, probe_gen_issue = 0, probe_gen_math = 0, probe_single = 0;
+    int probe_nfast = 0, probe_ngen = 0, probe_nsingle = 0;
 #endif
     const int4 rec0 = item_tab[3 * static_cast<size_t>(item)], rec1 = item_tab[3 * static_cast<size_t>(item) + 1];
     const int4 rec2 = item_tab[3 * static_cast<size_t>(item) + 2];
@@ -1187,28 +1187,66 @@ __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf
         ring ^= 1;
         p0 += kKT;
     };
+    // Tiles in assembly (D = 128; one statement, see fast_run_d128.inc).  A run: consecutive tiles that need no mask
+    // and whose successors lie wholly in the prefix (mode 1, or 3 for pools of 4 GB and more) or wholly in the extend
+    // tokens (2); it issues its tiles' loads itself.  A single tile: arithmetic only, with the keys a row must not see
+    // hidden if there are any (5, else 4), the next tile's loads issued from here by the general code - for the tiles
+    // that no run takes because of what their successor is (prefix and extend rows mixed) or because they touch the
+    // causal diagonal; not in shared tiles (a second visibility bound).  Neither before the running maximum exists.
+    auto single_tile_ok = [&](int p0) __attribute__((always_inline)) -> bool {
+        return fast_ok && D == 128 && RB == 1 && NW == 4 && (smem_addr & 255u) == 0 && !shared && wave_on && p0 <= P + wave_i_last;
+    };
+    // The assembly tiles want a running maximum to start from, and any lower bound of the true one will do as long as it
+    // is not 2^40 short (then the tile is handed to the general code, as always): the largest score of the first 32 keys,
+    // where every row of the wave sees all of them.  The first tile then runs in assembly like the others (its first
+    // key block is multiplied twice) instead of in the general code, which establishes the maximum otherwise.
+    if constexpr (D == 128 && RB == 1 && NW == 4) {
+        // (also in shared tiles: the keys of the common prefix are visible to every row)
+        if (fast_ok && (smem_addr & 255u) == 0 && wave_on && kv_lo <= P + wave_i_last && kv_lo + 32 <= blk_vis_min[0] && kv_lo + 32 <= kv_hi) {
+            const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            bf16x8 kf[KS];
+#pragma unroll
+            for (int s = 0; s < KS; ++s) asm volatile("ds_read_b128 %0, %1" : "=v"(kf[s]) : "v"(k_rd[s]));
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[0]), "+v"(kf[1]), "+v"(kf[2]), "+v"(kf[3]), "+v"(kf[4]), "+v"(kf[5]), "+v"(kf[6]), "+v"(kf[7]));
+            f32x16 sacc = zero16;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qreg[0][s], sacc, 0, 0, 0);
+            float mx = fmaxf(sacc[0], sacc[1]);
+#pragma unroll
+            for (int i = 2; i < 16; ++i) mx = fmaxf(mx, sacc[i]);
+            m_run[0] = row_max(mx) * scale_log2e;
+        }
+    }
     bool fast_allowed = true;
     while (p0 < kv_hi) {
         p0 = __builtin_amdgcn_readfirstlane(p0);  // wave-uniform, said so to the compiler
         ring = __builtin_amdgcn_readfirstlane(ring);
         int from = 0;
         bool issue_next = true;
-        const int kind = fast_allowed ? tile_kind(p0) : 0;
         bool have_m = true;  // every row has a finite running maximum
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) have_m &= m_run[rb] != -INFINITY;
-        if (kind != 0 && __all(have_m)) {
+        int mode = 0, kind = 0;
+        if (fast_allowed && __all(have_m)) {
+            kind = tile_kind(p0);
+            mode = kind == 1 ? (fast_ok == 2 ? 3 : 1) : kind == 2 ? 2 : single_tile_ok(p0) ? (p0 + kKT > blk_vis_min[0] ? 5 : 4) : 0;
+        }
+        if (mode != 0) {
             if constexpr (D == 128 && RB == 1 && (NW == 4 || NW == 8)) {
-                // A run of steady-state tiles against the running maximum as it stands: scores never move it in there
-                // (a row's probabilities may reach 2^40 instead), the output accumulators are touched by MFMAs only.
-                int p_end = p0;
-                do p_end += kKT;
-                while (tile_kind(p_end) == kind);
-                const int p_start = p0, ring_start = ring;
-                int st = 0;
+                // Against the running maximum as it stands: scores never move it in there (a row's probabilities may
+                // reach 2^40 instead), the output accumulators are touched by MFMAs only.
+                int p_end = p0 + kKT;
+                if (mode <= 3) {
+                    while (tile_kind(p_end) == kind) p_end += kKT;
+                } else if (p0 + kKT < kv_hi) {
+                    issue(p0 + kKT, ring ^ 1);
+                    load_slots(p0 + 2 * kKT);
+                }
 #ifdef PA_PROBE_DETAIL
                 const long long probe_r0 = clk ? clock64() : 0;
 #endif
+                const int p_start = p0, ring_start = ring;
+                int st = 0;
                 const bf16x16 q01 = __builtin_shufflevector(qreg[0][0], qreg[0][1], 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
                 const bf16x16 q23 = __builtin_shufflevector(qreg[0][2], qreg[0][3], 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
                 const bf16x16 q45 = __builtin_shufflevector(qreg[0][4], qreg[0][5], 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
@@ -1224,8 +1262,8 @@ __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf
                     const uint64_t lo = static_cast<uint32_t>(uni(static_cast<int>(a))), hi = static_cast<uint32_t>(uni(static_cast<int>(a >> 32)));
                     return reinterpret_cast<const void*>(lo | (hi << 32));
                 };
-                // (fast_ok == 2: the pool is too large for 32-bit byte offsets; rows are then counted in units of 256 bytes)
-                const i32x8 c = {uni(page_shift), uni(page_size - 1), uni(static_cast<int>(fast_ok == 2 ? page_stride / ROWB : page_stride)), uni(num_slots - 1),
+                // (mode 3: the pool is too large for 32-bit byte offsets; rows are then counted in units of 256 bytes)
+                const i32x8 c = {uni(page_shift), uni(page_size - 1), uni(static_cast<int>(mode == 3 ? page_stride / ROWB : page_stride)), uni(num_slots - 1),
                                  uni(P - 1), uni(static_cast<int>(x_stride)), uni(kv_hi - 1 - P),
                                  uni(static_cast<int>(smem_addr) + wave * (UPW * 1024))};
                 const i32x4 c2 = {uni(128), uni(192), uni(P), uni(__float_as_int(scale_log2e))};
@@ -1233,44 +1271,33 @@ __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf
                 ring = uni(ring);
                 p_end = uni(p_end);
                 const int row_in_tile = wave * (UPW * RPB) + ld_rowl;
-                if constexpr (NW == 4) {
-                    if (kind == 1 && fast_ok == 2)
-                        fast_run_pool64_d128(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
-                                             k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
-                                             uni_ptr(pool_g), uni_ptr(pool_g + v_off32), c, c2);
-                    else if (kind == 1)
-                        fast_run_pool_d128(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
-                                           k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
-                                           uni_ptr(pool_g), uni_ptr(pool_g + v_off32), c, c2);
-                    else
-                        fast_run_ext_d128(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
-                                          k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
-                                          uni_ptr(kx_g), uni_ptr(vx_g), c, c2);
-                } else {
-                    if (kind == 1 && fast_ok == 2)
-                        fast_run_pool64_d128_w8(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
-                                                k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
-                                                uni_ptr(pool_g), uni_ptr(pool_g + v_off32), c, c2);
-                    else if (kind == 1)
-                        fast_run_pool_d128_w8(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
-                                              k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
-                                              uni_ptr(pool_g), uni_ptr(pool_g + v_off32), c, c2);
-                    else
-                        fast_run_ext_d128_w8(oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
-                                             k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
-                                             uni_ptr(kx_g), uni_ptr(vx_g), c, c2);
-                }
+                const void* base_k = mode == 2 ? static_cast<const void*>(kx_g) : static_cast<const void*>(pool_g);
+                const void* base_v = mode == 2 ? static_cast<const void*>(vx_g) : static_cast<const void*>(pool_g + v_off32);
+                const int lim = vis_end[0] - p0 - 4 * hh;
+                if constexpr (NW == 4)
+                    fast_tiles_d128(uni(mode), oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
+                                    k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
+                                    uni_ptr(base_k), uni_ptr(base_v), lim, c, c2);
+                else
+                    fast_tiles_d128_w8(uni(mode), oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
+                                       k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
+                                       uni_ptr(base_k), uni_ptr(base_v), lim, c, c2);
 #ifdef PA_PROBE_DETAIL
                 if (clk) {
-                    probe_fast += clock64() - probe_r0;
-                    probe_nfast += (p0 - p_start) / kKT;
+                    if (mode <= 3) {
+                        probe_fast += clock64() - probe_r0;
+                        probe_nfast += (p0 - p_start) / kKT;
+                    } else {
+                        probe_single += clock64() - probe_r0;
+                        probe_nsingle += (p0 - p_start) / kKT;
+                    }
                 }
 #endif
                 if (((p0 - p_start) / kKT) & 1) move_read_addresses(ring_start);
-                // (the run fetched slot ids from the common list only: where the tile they are for holds a member's own
+                // (a run fetched slot ids from the common list only: where the tile they are for holds a member's own
                 // prefix keys they are fetched again, from that member's list.  That tile is the next one, or, if the
                 // run was left inside a tile - the next one's loads are in flight then - the one after it.)
-                if (has_own_prefix()) {
+                if (mode <= 3 && has_own_prefix()) {
                     const int pn = p0 + (st == 0 ? kKT : 2 * kKT);
                     if (pn + kKT > P) load_slots(pn);
                 }
@@ -1344,6 +1371,8 @@ __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf
         atomicAdd(clk + 7, static_cast<unsigned long long>(clock64() - probe_t1));
         atomicAdd(clk + 8, static_cast<unsigned long long>(probe_gen_issue));
         atomicAdd(clk + 9, static_cast<unsigned long long>(probe_gen_math));
+        atomicAdd(clk + 10, static_cast<unsigned long long>(probe_single));
+        atomicAdd(clk + 11, static_cast<unsigned long long>(probe_nsingle));
     }
 #endif
 }

@@ -44,6 +44,8 @@ SLN = [60, 61, 62, 63]
 L, NEGM, KOFF0, VOFF0, ROWI, KRD0, VRD0 = 59, 58, 57, 56, 55, 54, 53
 T = [46, 47, 48, 49, 50, 51, 52]
 LSUM, ROWOFF = 45, 44
+LIM0, LIM1, NEGINF = T[0], T[1], T[6]   # masked single tiles (they issue no loads: the T registers are free)
+MASKS = [72, 74]                        # ... and two scalar register pairs for their comparisons
 FIRST_V = 44
 # ---- scalar registers ----
 P0, RING, STATUS, PEND = 40, 41, 42, 43
@@ -100,6 +102,7 @@ def tile(st, kind, ring, uid, upw):
     the first ALU read of it - eleven issue slots) other work stands there instead of s_nop."""
     e = st.emit
     ext, wide = kind == "ext", kind == "pool64"
+    noload, masked = kind in ("plain", "masked"), kind == "masked"   # (single tiles: the kernel issues the next tile's loads itself)
     here, there = ring * STAGEB, (ring ^ 1) * STAGEB
     last = {}   # fragment number (0..15 K, 16..31 V) -> id of its last LDS read
 
@@ -190,11 +193,20 @@ def tile(st, kind, ring, uid, upw):
         if pending:
             e(f"v_dot2c_f32_bf16 {v(LSUM)}, {ONES}, {v(pending.pop())}")
 
-    def exp_piece(sc, pb, idx):
+    def exp_piece(sc, pb, idx, lim=None):
         """Probabilities of elements 2 idx, 2 idx + 1 of a score block.  The row-sum step of the piece before stands
-        between the exponentials and the first use of their results."""
+        between the exponentials and the first use of their results.  Masked tiles: register i of a lane holds the key
+        at offset 8 (i / 4) + i % 4 from the lane's first key of the block, visible if that is below the lane's limit;
+        the exponent of a hidden key becomes -inf (two comparisons ahead of the two selections, so that their results
+        have reached the scalar registers)."""
+        if masked:
+            for k, i in enumerate((2 * idx, 2 * idx + 1)):
+                e(f"v_cmp_gt_i32 {s(MASKS[k], 2)}, {v(lim)}, {8 * (i // 4) + i % 4}")
         e(f"v_fma_f32 {v(T[4])}, {v(sc + 2 * idx)}, {s(C_SCALE)}, {v(NEGM)}")
         e(f"v_fma_f32 {v(T[5])}, {v(sc + 2 * idx + 1)}, {s(C_SCALE)}, {v(NEGM)}")
+        if masked:
+            e(f"v_cndmask_b32 {v(T[4])}, {v(NEGINF)}, {v(T[4])}, {s(MASKS[0], 2)}")
+            e(f"v_cndmask_b32 {v(T[5])}, {v(NEGINF)}, {v(T[5])}, {s(MASKS[1], 2)}")
         e(f"v_exp_f32 {v(T[4])}, {v(T[4])}")
         e(f"v_exp_f32 {v(T[5])}, {v(T[5])}")
         if pending:
@@ -249,7 +261,7 @@ def tile(st, kind, ring, uid, upw):
         wait_pair(sl)
         mfma(v(SC0, 16), v(FR[sl % NFR], 4), v(Q[sl], 4), v(SC0, 16) if sl else "0")
         read_frag(sl + PD)
-        if sl < 2 * upw:
+        if sl < 2 * upw and not noload:
             load_piece(sl // 2, sl % 2)
     # ---- phase B: S1 = K(block 1) Q^T | slot ids of the tile after next, probabilities of block 0 ----
     e(f"v_mov_b32 {v(LSUM)}, 0")
@@ -259,17 +271,20 @@ def tile(st, kind, ring, uid, upw):
         mfma(v(SC1, 16), v(FR[f % NFR], 4), v(Q[sl], 4), v(SC1, 16) if sl else "0")
         if sl < KS - 1:
             read_frag(f + PD)
-        if sl == 0 and not ext:
+        if sl == 0 and not ext and not noload:
             slot_ids()   # (also the distance block 0's scores need from the MFMA that wrote them last)
         elif sl == 0:
+            if masked:
+                e(f"v_subrev_u32 {v(LIM1)}, 32, {v(LIM0)}")
+                e(f"v_mov_b32 {v(NEGINF)}, 0xff800000")
             e("s_nop 7")
         if sl == 0 and SETTLE:
             e("s_nop 7")
             e("s_nop 3")
-        exp_piece(SC0, PB0, sl)
+        exp_piece(SC0, PB0, sl, LIM0)
     end_of_sums(2 * KS - 1)
     e(f"v_cmp_lt_u32 vcc, {LIMIT}, {v(LSUM)}")
-    e(f"s_cbranch_vccnz Lover1{uid}")
+    e(f"s_cbranch_vccnz Lover1{st.kind_end}")
     e(f"v_add_f32 {v(L)}, {v(L)}, {v(LSUM)}")
     e(f"v_mov_b32 {v(LSUM)}, 0")
     # ---- phase C: O += V(block 0) P0 | probabilities of block 1 (its scores were last written thirteen issue slots ago) ----
@@ -283,10 +298,10 @@ def tile(st, kind, ring, uid, upw):
         if j == 0 and SETTLE:
             e("s_nop 7")
             e("s_nop 3")
-        exp_piece(SC1, PB1, j)
+        exp_piece(SC1, PB1, j, LIM1)
     end_of_sums(23)
     e(f"v_cmp_lt_u32 vcc, {LIMIT}, {v(LSUM)}")
-    e(f"s_cbranch_vccnz Lover2{uid}")
+    e(f"s_cbranch_vccnz Lover2{st.kind_end}")
     e(f"v_add_f32 {v(L)}, {v(L)}, {v(LSUM)}")
     # ---- phase D: O += V(block 1) P1 ----
     for j in range(8):
@@ -304,10 +319,16 @@ def tile(st, kind, ring, uid, upw):
     e(f"s_cmp_lt_i32 {s(P0)}, {s(PEND)}")
 
 
-def gen(kind, upw):
+KINDS = ["pool", "ext", "pool64", "plain", "masked"]   # mode operand = 1 + index
+MODE = 50                                                # scalar register of the mode operand
+
+
+def gen(upw):
+    """All kinds of run in one statement (one set of register constraints for the compiler to meet), chosen by the mode
+    operand.  Labels of a kind carry its name; Lover1 / Lover2 / Ldone are common."""
     st = Stream()
     e = st.emit
-    uid = "%="
+    end = "%="
     # ---- entry: LDS read addresses in ring slot 0 (the operands give those of the slot that holds the tile at P0) ----
     e(f"s_lshl_b32 {s(S_T[0])}, {s(RING)}, 15")
     e(f"v_subrev_u32 {v(KRD[0])}, {s(S_T[0])}, {v(KRD0)}")
@@ -320,58 +341,71 @@ def gen(kind, upw):
         e(f"v_xor_b32 {v(VRD[2 * b + 1])}, 32, {v(VRD[2 * b])}")
         e(f"v_add_u32 {v(VRD[2 * b + 1])}, 0x800, {v(VRD[2 * b + 1])}")
     e(f"s_mov_b32 {s(STATUS)}, 0")
-    e(f"s_cmp_eq_u32 {s(RING)}, 0")
-    e(f"s_cbranch_scc0 Lring1{uid}")
-    # the loop body is written out for both ring slots: every LDS offset is an immediate
-    e(f"Lring0{uid}:")
-    tile(st, kind, 0, uid, upw)
-    e(f"s_cbranch_scc0 Ldone{uid}")
-    e(f"Lring1{uid}:")
-    tile(st, kind, 1, uid, upw)
-    e(f"s_cbranch_scc1 Lring0{uid}")
-    e(f"s_branch Ldone{uid}")
+    for i, kind in enumerate(KINDS[1:], start=2):
+        e(f"s_cmp_eq_u32 {s(MODE)}, {i}")
+        e(f"s_cbranch_scc1 Lkind_{kind}{end}")
+    for kind in KINDS:
+        uid = f"_{kind}{end}"
+        e(f"Lkind{uid}:")
+        e(f"s_cmp_eq_u32 {s(RING)}, 0")
+        e(f"s_cbranch_scc0 Lring1{uid}")
+        # the loop body is written out for both ring slots: every LDS offset is an immediate
+        e(f"Lring0{uid}:")
+        st.kind_end = end
+        tile(st, kind, 0, uid, upw)
+        e(f"s_cbranch_scc0 Ldone{end}")
+        e(f"Lring1{uid}:")
+        tile(st, kind, 1, uid, upw)
+        e(f"s_cbranch_scc1 Lring0{uid}")
+        e(f"s_branch Ldone{end}")
     for ln in st.tail:
         e(ln)
-    e(f"Lover1{uid}:")
+    e(f"Lover1{end}:")
     e(f"s_mov_b32 {s(STATUS)}, 1")
-    e(f"s_branch Ldone{uid}")
-    e(f"Lover2{uid}:")
+    e(f"s_branch Ldone{end}")
+    e(f"Lover2{end}:")
     e(f"s_mov_b32 {s(STATUS)}, 2")               # the sum of block 0 is in L already
-    e(f"Ldone{uid}:")
+    e(f"Ldone{end}:")
     e("s_waitcnt vmcnt(0) lgkmcnt(0)")           # prefetched fragments and slot ids of a run that was left early
     return st.lines
 
 
-def emit(name, kind, upw=UPW):
-    lines = gen(kind, upw)
-    ext = kind == "ext"
+def emit(name, upw):
+    lines = gen(upw)
     body = "\n".join(f'        "{ln}\\n\\t"' for ln in lines)
-    clob = [f"v{i}" for i in range(FIRST_V, 53)] + [f"v{i}" for i in range(64, 160)] + [f"s{i}" for i in S_T] + ["vcc", "scc", "memory"]
+    clob = ([f"v{i}" for i in range(FIRST_V, 53) if i != LIM0] + [f"v{i}" for i in range(64, 160)] + [f"s{i}" for i in S_T] +
+            [f"s{i}" for i in range(MASKS[0], MASKS[1] + 2)] + ["vcc", "scc", "memory"])
     clobbers = ", ".join(f'"{c}"' for c in clob)
     sln = ", ".join(f'"+{{v{SLN[u]}}}"(sl_next[{u}])' for u in range(upw))
     return f'''
-// {'next tile in the extend tokens' if ext else 'next tile in the prefix (pool rows through slot ids' + (', 64-bit addresses' if kind == 'pool64' else '') + ')'}; a wave loads {upw} blocks of a tile
-__device__ __forceinline__ void {name}(f32x16& acc0, f32x16& acc1, f32x16& acc2, f32x16& acc3, const bf16x32& q_lo,
+// a wave loads {upw} blocks of a tile
+__device__ __forceinline__ void {name}(int mode, f32x16& acc0, f32x16& acc1, f32x16& acc2, f32x16& acc3, const bf16x32& q_lo,
                                        const bf16x32& q_hi, float& l_run, float neg_m, int32_t (&sl_next)[{upw}],
                                        unsigned k_rd0, unsigned v_rd0, unsigned ld_koff0, unsigned ld_voff0, int row_in_tile,
                                        int& p0, int& ring, int& status, int p_end, const void* slots, const void* base_k,
-                                       const void* base_v, const i32x8& c, const i32x4& c2) {{
+                                       const void* base_v, int lim, const i32x8& c, const i32x4& c2) {{
     asm volatile(
 {body}
         : "+{{v[192:207]}}"(acc0), "+{{v[208:223]}}"(acc1), "+{{v[224:239]}}"(acc2), "+{{v[240:255]}}"(acc3), "+{{v59}}"(l_run),
           {sln}, "+{{s40}}"(p0),
-          "+{{s41}}"(ring), "={{s42}}"(status)
+          "+{{s41}}"(ring), "={{s42}}"(status), "+{{v{LIM0}}}"(lim)
         : "{{v[160:175]}}"(q_lo), "{{v[176:191]}}"(q_hi), "{{v58}}"(neg_m), "{{v54}}"(k_rd0), "{{v53}}"(v_rd0), "{{v57}}"(ld_koff0),
           "{{v56}}"(ld_voff0), "{{v55}}"(row_in_tile), "{{s43}}"(p_end), "{{s[44:45]}}"(slots), "{{s[46:47]}}"(base_k),
-          "{{s[48:49]}}"(base_v), "{{s[52:59]}}"(c), "{{s[60:63]}}"(c2)
+          "{{s[48:49]}}"(base_v), "{{s[52:59]}}"(c), "{{s[60:63]}}"(c2), "{{s{MODE}}}"(mode)
         : {clobbers});
 }}
 '''
 
 
-HEADER = '''// GENERATED by gen_fast_run.py - do not edit.  Runs of steady-state tiles of extend_bf16_kernel<128, 4, 1> (a wave
-// loads four 1 KB blocks of a K or V tile) and extend_bf16_kernel<128, 8, 1> (the _w8 functions: two blocks) as gfx950
-// assembly with fixed registers; the generator describes the schedule.
+HEADER = '''// GENERATED by gen_fast_run.py - do not edit.  Tiles of extend_bf16_kernel<128, 4, 1> (a wave loads four 1 KB blocks of
+// a K or V tile) and extend_bf16_kernel<128, 8, 1> (_w8: two blocks) as gfx950 assembly with fixed registers; the
+// generator describes the schedule.  One statement per kernel holds every kind of tile, so that the compiler meets one
+// set of register constraints; the mode operand chooses:
+//   1  a run of tiles, the NEXT tile of each wholly in the prefix (its rows come from the pool through slot ids)
+//   2  a run of tiles, the next tile wholly in the extend tokens
+//   3  as 1 for pools of 4 GB and more (pool rows addressed in 64 bits; base_k / base_v 256-byte aligned)
+//   4  one tile, arithmetic only (the caller has issued the next tile's loads)
+//   5  as 4 with keys hidden from rows: lim = how many keys of the tile, counted from the lane's first, its row sees
 //
 // Operands: acc0..3 output accumulators (head-dim blocks 0..3); q_lo / q_hi the eight query fragments (k-slices 0..3,
 // 4..7); l_run this lane's share of the row sum; neg_m minus the running maximum; sl_next the pool
@@ -380,17 +414,16 @@ HEADER = '''// GENERATED by gen_fast_run.py - do not edit.  Runs of steady-state
 // ld_koff0 / ld_voff0 byte offsets inside a K / V row of this lane's 16 bytes of load block 0; row_in_tile the row of
 // the tile this lane loads in block 0; p0 first key of the tile (advanced by 64 per tile done); ring its ring slot;
 // status 0 = ran to p_end, 1 / 2 = the tile at p0 outgrew the running maximum in key block 0 / 1 (see the kernel);
-// slots the request's slot ids; base_k / base_v where K / V rows are fetched from (pool64: 256-byte aligned); c = {page
-// shift, page mask, page stride in bytes (pool64: in rows of 256 bytes), num_slots - 1, P - 1, extend token stride in bytes, kv_hi - 1 - P, LDS address of this wave's load
-// block 0 in ring slot 0}; c2 = {128, 192, P, bits of scale * log2(e)}.
+// slots the request's slot ids; base_k / base_v where K / V rows are fetched from; lim see mode 5 (scratch otherwise);
+// c = {page shift, page mask, page stride in bytes (mode 3: in rows of 256 bytes), num_slots - 1, P - 1, extend token
+// stride in bytes, kv_hi - 1 - P, LDS address of this wave's load block 0 in ring slot 0}; c2 = {128, 192, P, bits of
+// scale * log2(e)}.
 '''
 
 
 def main():
     here = os.path.dirname(os.path.abspath(__file__))
-    text = (HEADER + emit("fast_run_pool_d128", "pool") + emit("fast_run_pool64_d128", "pool64") + emit("fast_run_ext_d128", "ext") +
-            emit("fast_run_pool_d128_w8", "pool", 2) + emit("fast_run_pool64_d128_w8", "pool64", 2) +
-            emit("fast_run_ext_d128_w8", "ext", 2))
+    text = HEADER + emit("fast_tiles_d128", 4) + emit("fast_tiles_d128_w8", 2)
     path = os.path.join(here, "fast_run_d128.inc")
     old = open(path).read() if os.path.exists(path) else None
     if old != text:
