@@ -45,6 +45,7 @@ def lib():
         _lib.ora_trie_insert.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]
         _lib.ora_trie_insert.restype = C.c_int64
         _lib.ora_trie_match.argtypes = [C.c_void_p] * 3 + [C.c_int] + [C.c_void_p] * 2
+        _lib.ora_fp8_rows.argtypes = [C.c_void_p, C.c_int64, C.c_int] + [C.c_void_p] * 3
         _lib.ora_append_kv.argtypes = [C.c_void_p] * 5 + [C.c_int64, C.c_int, C.c_int, C.c_int]
         _lib.ora_extend_attention.argtypes = [C.c_void_p] * 10 + [C.c_int] * 5 + [C.c_double, C.c_void_p]
         _lib.ora_extend_attention_rows.argtypes = ([C.c_void_p] * 9 + [C.c_int] * 4 + [C.c_double, C.c_void_p,
@@ -110,8 +111,23 @@ def new_pool(num_slots: int, Hkv: int, D: int, dtype: str):
     return np.zeros((num_slots, Hkv, D), dt), np.zeros((num_slots, Hkv, D), dt)
 
 
+def fp8_rows(rows: np.ndarray):
+    """rows: bfloat16 bit patterns [..., D] -> (codes uint8 like rows, exps int8 [...], stored bfloat16 bit patterns like
+    rows): the fp8 form of KV rows (one power-of-two scale per row of D elements) and the values it stores."""
+    r = _vals(rows, "bf16")
+    D = r.shape[-1]
+    n = r.size // D
+    codes, exps, stored = np.zeros(r.shape, np.uint8), np.zeros(r.shape[:-1], np.int8), np.zeros(r.shape, np.uint16)
+    lib().ora_fp8_rows(_p(r), n, D, _p(codes), _p(exps), _p(stored))
+    return codes, exps, stored
+
+
 def append_kv(pool_k, pool_v, new_slots, k_ext, v_ext, dtype: str):
+    """dtype 'bf16_kv8': the pool holds the rows in their fp8 form; the oracle keeps the values that form stores (exactly
+    bfloat16) in its bfloat16 pool, so that attention over the pool needs no other change."""
     s = _i32(new_slots)
+    if dtype == "bf16_kv8":
+        k_ext, v_ext, dtype = fp8_rows(k_ext)[2], fp8_rows(v_ext)[2], "bf16"
     k, v = _vals(k_ext, dtype), _vals(v_ext, dtype)
     T, Hkv, D = k.shape
     assert v.shape == k.shape and len(s) == T and pool_k.shape[1:] == (Hkv, D)

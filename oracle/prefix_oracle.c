@@ -139,6 +139,68 @@ void ora_append_kv(void *pool_k, void *pool_v, const int32_t *new_slots, const v
     }
 }
 
+/* ------------------------------------------------------------------ fp8 KV rows */
+
+/*
+ * The fp8 form of the KV pool (a reading of this build, not of the paper, which stores no KV format: memory for KV
+ * bounds what stays cached, Sec. 3.3).  A row = the D elements of one (token, KV head, K or V).  It is stored as D
+ * codes in the 8-bit format with 4 exponent bits (bias 7), 3 mantissa bits, no infinities and largest value 448, and
+ * one exponent k per row: stored value = decode(code) * 2^k.  k is the smallest integer with max|row| * 2^-k <= 448
+ * (0 for a row of zeros, kept within [-100, 120]); code = x * 2^-k rounded to the nearest representable value, ties to
+ * the one with an even mantissa.  Every stored value is exactly a bfloat16, so the pool that attention reads can be
+ * held, without loss, as the bfloat16 rows this function returns.
+ */
+static double e4m3_value(int code) { /* code 0..126 (sign apart); 127 would be NaN and is never produced */
+    int e = code >> 3, m = code & 7;
+    return e == 0 ? ldexp((double)m, -9) : ldexp(1.0 + m / 8.0, e - 7);
+}
+
+static int e4m3_nearest(double a) { /* 0 <= a <= 448 */
+    /* the two neighbours of a among the 127 non-negative values, then nearest, ties to even */
+    int lo = 0, hi = 126;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) / 2;
+        if (e4m3_value(mid) <= a) lo = mid; else hi = mid;
+    }
+    if (e4m3_value(hi) <= a) return hi;
+    double dl = a - e4m3_value(lo), dh = e4m3_value(hi) - a;
+    if (dl < dh) return lo;
+    if (dh < dl) return hi;
+    return (lo & 1) ? hi : lo;
+}
+
+/* rows: n rows of D bfloat16 bit patterns.  codes (n * D bytes, sign in bit 7), exps (n) and stored (n * D bfloat16
+ * bit patterns of the stored values) may each be NULL. */
+void ora_fp8_rows(const uint16_t *rows, int64_t n, int D, uint8_t *codes, int8_t *exps, uint16_t *stored) {
+    for (int64_t r = 0; r < n; ++r) {
+        double amax = 0.0;
+        for (int d = 0; d < D; ++d) {
+            double x = fabs(load_val(rows, r * D + d, 1));
+            if (x > amax) amax = x;
+        }
+        int k = 0;
+        if (amax > 0.0) {
+            int e;
+            double m = frexp(amax / 448.0, &e); /* amax / 448 = m * 2^e, 0.5 <= m < 1 */
+            k = (m == 0.5) ? e - 1 : e;
+            if (k < -100) k = -100;
+            if (k > 120) k = 120;
+        }
+        if (exps) exps[r] = (int8_t)k;
+        for (int d = 0; d < D; ++d) {
+            double x = load_val(rows, r * D + d, 1);
+            int code = e4m3_nearest(ldexp(fabs(x), -k));
+            if (codes) codes[r * D + d] = (uint8_t)(code | (signbit(x) ? 0x80 : 0));
+            if (stored) {
+                float f = (float)(ldexp(e4m3_value(code), k) * (signbit(x) ? -1.0 : 1.0)); /* exact */
+                uint32_t u;
+                memcpy(&u, &f, 4);
+                stored[r * D + d] = (uint16_t)(u >> 16); /* the low 16 bits are zero: at most 4 significant bits */
+            }
+        }
+    }
+}
+
 /* ------------------------------------------------------------------ extend attention */
 
 /* one output row: request r, extend row i, query head h -> out[D] */
