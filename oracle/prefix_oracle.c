@@ -146,9 +146,10 @@ void ora_append_kv(void *pool_k, void *pool_v, const int32_t *new_slots, const v
  * bounds what stays cached, Sec. 3.3).  A row = the D elements of one (token, KV head, K or V).  It is stored as D
  * codes in the 8-bit format with 4 exponent bits (bias 7), 3 mantissa bits, no infinities and largest value 448, and
  * one exponent k per row: stored value = decode(code) * 2^k.  k is the smallest integer with max|row| * 2^-k <= 448
- * (0 for a row of zeros, kept within [-100, 120]); code = x * 2^-k rounded to the nearest representable value, ties to
- * the one with an even mantissa.  Every stored value is exactly a bfloat16, so the pool that attention reads can be
- * held, without loss, as the bfloat16 rows this function returns.
+ * (0 for a row of zeros, kept within [-100, 119]); code = x * 2^-k rounded to the nearest representable value, ties to
+ * the one with an even mantissa, and what still exceeds 448 (only where k was cut at 119: values within a factor 1.14
+ * of the largest bfloat16) becomes 448.  Every stored value is exactly a finite bfloat16, so the pool that attention
+ * reads can be held, without loss, as the bfloat16 rows this function returns.
  */
 static double e4m3_value(int code) { /* code 0..126 (sign apart); 127 would be NaN and is never produced */
     int e = code >> 3, m = code & 7;
@@ -184,12 +185,13 @@ void ora_fp8_rows(const uint16_t *rows, int64_t n, int D, uint8_t *codes, int8_t
             double m = frexp(amax / 448.0, &e); /* amax / 448 = m * 2^e, 0.5 <= m < 1 */
             k = (m == 0.5) ? e - 1 : e;
             if (k < -100) k = -100;
-            if (k > 120) k = 120;
+            if (k > 119) k = 119;
         }
         if (exps) exps[r] = (int8_t)k;
         for (int d = 0; d < D; ++d) {
             double x = load_val(rows, r * D + d, 1);
-            int code = e4m3_nearest(ldexp(fabs(x), -k));
+            double y = ldexp(fabs(x), -k);
+            int code = e4m3_nearest(y > 448.0 ? 448.0 : y);
             if (codes) codes[r * D + d] = (uint8_t)(code | (signbit(x) ? 0x80 : 0));
             if (stored) {
                 float f = (float)(ldexp(e4m3_value(code), k) * (signbit(x) ? -1.0 : 1.0)); /* exact */

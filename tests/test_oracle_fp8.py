@@ -92,3 +92,13 @@ def test_row_exponent_is_the_smallest_that_fits():
     zero = np.zeros((2, 64), np.uint16)
     codes, exps, stored = oracle.fp8_rows(zero)
     assert not codes.any() and not exps.any() and not stored.any()
+
+
+def test_the_largest_bfloat16_values_stay_finite():
+    """k stops at 119, so that 448 * 2^k is still a bfloat16; what exceeds 448 after scaling is stored as 448."""
+    big = np.array([[0x7F7F, 0xFF7F, 0x7F60, 0x7F00] + [0] * 60], np.uint16)   # +-max, 1.75 * 2^127, 2^127
+    codes, exps, stored = oracle.fp8_rows(big)
+    assert exps[0] == 119
+    assert list(codes[0, :4]) == [126, 126 | 0x80, 126, 120]
+    got = W.bf16_bits_to_f32(stored)[0, :4].astype(np.float64)
+    assert list(got) == [448 * 2.0 ** 119, -448 * 2.0 ** 119, 448 * 2.0 ** 119, 2.0 ** 127]
