@@ -11,7 +11,8 @@ value      extend (newly prefilled) tokens per second over the whole step, on --
 roofline   the extend-attention kernel against the roof that binds it for this workload:
            algorithmic bytes or flops per launch / average kernel time from HIP events
 configs    the same measurement, shorter, on each of the four bf16 configurations (tool use, long-document QA,
-           agent tree, video QA): step time, per-kernel times, both roofline fractions
+           agent tree, video QA): step time, per-kernel times, both roofline fractions; and on long-document QA
+           with the KV pool in its fp8 form (--kv-pool fp8 makes that the headline's pool)
 cpu_baseline  the CPU oracle, as it stands, on a bounded sample of the headline workload
 """
 import argparse
@@ -28,6 +29,7 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 BF16_CONFIGS = ["tool_use", "long_doc_qa", "agent_tree", "video_qa"]
+FP8_POOL_CONFIGS = ["long_doc_qa"]   # measured once more with the KV pool held in 8 bits per element
 
 # HBM bytes per launch of the extend-attention kernel, measured with rocprofv3 --pmc in runs of their own (a counter
 # run cannot share a process with the timed one): FETCH_SIZE x the factor that the same counter shows for append_kv, a
@@ -50,6 +52,8 @@ def algorithmic_work(wl, prefix_len):
     E = wl.ext_len.astype(np.int64)
     T = int(E.sum())
     kv_bytes = int(P.sum()) * wl.Hkv * wl.D * el * 2
+    if wl.dtype == "bf16_kv8":   # a pool row is D one-byte codes and one exponent byte
+        kv_bytes = int(P.sum()) * wl.Hkv * (wl.D + 1) * 2
     slot_bytes = 4 * int(P.sum())
     io_bytes = T * (2 * wl.Hq * wl.D * el + 2 * wl.Hkv * wl.D * el)
     flops = 4 * wl.D * wl.Hq * int((E * P + E * (E + 1) // 2).sum())
@@ -203,8 +207,10 @@ def extras(pa, g, wl, prefix_len, slot_idx, out, ws, main_k, nbytes):
     return ex
 
 
-def measure(name, steps, warmup, args, with_extras):
+def measure(name, steps, warmup, args, with_extras, kv_pool="bf16"):
     """All GPU measurements of one workload.  -> (result dict, the workload)."""
+    import dataclasses
+
     import torch
 
     from paper_2407_00023_amd import binding as pa
@@ -213,6 +219,8 @@ def measure(name, steps, warmup, args, with_extras):
 
     dev = torch.device("cuda:0")
     wl = W.CONFIGS[name]()
+    if kv_pool == "fp8" and wl.dtype == "bf16":
+        wl = dataclasses.replace(wl, dtype="bf16_kv8")
     g = ResidentWorkload(wl, dev)
     tdt = g.tdtype
     # every buffer of the step is allocated once, outside the timed region
@@ -285,7 +293,7 @@ def measure(name, steps, warmup, args, with_extras):
             kern[kname] = {"avg_us": ms / n * 1e3, "launches_per_step": n / steps}
     shader_mhz = 0.0
     hdr = None
-    if wl.dtype == "bf16":
+    if wl.dtype != "f32":
         pa.extend_status(ws)  # (raises if the work list of the launches above did not fit)
         hdr = ws[:16].view(torch.int32).tolist()
         # a few more steps with the clock probe in the kernel, kept out of the times above
@@ -312,7 +320,7 @@ def measure(name, steps, warmup, args, with_extras):
         else:
             roofline = {"bound": "alu" if wl.dtype == "f32" else "mfma", "achieved": tfs, "peak": peak_f, "unit": "TFLOP/s",
                         "frac": tfs / peak_f}
-        traffic = MEASURED_TRAFFIC_BYTES.get(name)
+        traffic = MEASURED_TRAFFIC_BYTES.get(name + ("_fp8_pool" if wl.dtype == "bf16_kv8" else ""))
         roofline.update({"traffic": traffic,
                          "traffic_source": f"profiles/extend_attention_{name}.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, runs of their own)" if traffic else None,
                          "kernel": main_k, "avg_kernel_us": kern[main_k]["avg_us"], "algorithmic_bytes": nbytes,
@@ -322,7 +330,7 @@ def measure(name, steps, warmup, args, with_extras):
             # read back by the merge kernel): not part of algorithmic_bytes, shown beside it
             roofline["workspace_bytes"] = workspace_traffic(wl, hdr)
             roofline["work_list"] = {"row_tiles": hdr[0], "items": hdr[1], "tiles_merged_from_parts": hdr[2]}
-        if shader_mhz > 0 and wl.dtype == "bf16":
+        if shader_mhz > 0 and wl.dtype != "f32":
             # the clock the kernel ran at (shader cycles against the 100 MHz constant counter, across the key loop of a
             # few workgroups), and the matrix peak at that clock: 2.5 PFLOP/s is quoted at 2,400 MHz
             roofline["shader_mhz"] = shader_mhz
@@ -330,8 +338,8 @@ def measure(name, steps, warmup, args, with_extras):
 
     res = {
         "value": wl.T / (ms_per_step * 1e-3), "ms_per_step": ms_per_step, "steps": steps, "warmup": warmup,
-        "dtype": wl.dtype,
-        "config": {"workload": name, "requests": wl.B, "extend_tokens": wl.T, "prompt_tokens": int(wl.offsets[-1]),
+        "dtype": "f32" if wl.dtype == "f32" else "bf16",
+        "config": {"workload": name, "kv_pool": "fp8 codes + one exponent byte per row" if wl.dtype == "bf16_kv8" else wl.dtype, "requests": wl.B, "extend_tokens": wl.T, "prompt_tokens": int(wl.offsets[-1]),
                    "Hq": wl.Hq, "Hkv": wl.Hkv, "D": wl.D, "page_size": wl.page_size, "num_slots": wl.num_slots,
                    "cached_sequences": wl.n_cached, "only": args.only or "whole path", "launch": mode},
         "prompt_tokens_per_s": int(wl.offsets[-1]) / (ms_per_step * 1e-3),
@@ -343,11 +351,13 @@ def measure(name, steps, warmup, args, with_extras):
     if "append_kv" in kern:
         el = 4 if wl.dtype == "f32" else 2
         app_bytes = 2 * (2 * wl.T * wl.Hkv * wl.D * el) + 4 * wl.T   # K and V rows read and written, slot ids read
+        if wl.dtype == "bf16_kv8":
+            app_bytes = 2 * wl.T * wl.Hkv * (wl.D * 2 + wl.D + 1) + 4 * wl.T   # bf16 rows read, codes and exponents written
         res["append_GBps"] = app_bytes / (kern["append_kv"]["avg_us"] * 1e-6) / 1e9
     if with_extras:
         res["extras"] = extras(pa, g, wl, prefix_len, slot_idx, out, ws, main_k, nbytes)
         ach = res["extras"].get("achievable")
-        if ach and roofline and wl.dtype == "bf16":
+        if ach and roofline and wl.dtype != "f32":
             # beside the fractions of the published peaks: of what a bare MFMA loop and a bare copy reach on this machine
             roofline["compute_frac_of_mfma_loop"] = roofline["compute_frac"] * MFMA_BF16_PEAK_TFLOPS / ach["mfma_bf16_TFLOPs"]
             roofline["hbm_frac_of_copy"] = roofline["hbm_frac"] * HBM_PEAK_GBS / ach["copy_GBps"]
@@ -359,7 +369,7 @@ def measure(name, steps, warmup, args, with_extras):
 def summary(res):
     """One line of the `configs` array: what the headline carries for its own workload, shortened."""
     r = res["roofline"] or {}
-    return {"workload": res["config"]["workload"], "requests": res["config"]["requests"],
+    return {"workload": res["config"]["workload"], "kv_pool": res["config"]["kv_pool"], "requests": res["config"]["requests"],
             "extend_tokens": res["config"]["extend_tokens"], "steps": res["steps"], "ms_per_step": res["ms_per_step"],
             "extend_tokens_per_s": res["value"], "match_reqs_per_s": res.get("match_reqs_per_s"),
             "kernel_us": {k: round(v["avg_us"], 2) for k, v in res["kernels"].items()},
@@ -375,6 +385,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="agent_tree", choices=["tiny_fp32", "tool_use", "long_doc_qa", "agent_tree", "video_qa", "programming", "tool_use_zipf", "decode"])
+    ap.add_argument("--kv-pool", default="bf16", choices=["bf16", "fp8"], help="fp8: the KV pool of a bf16 workload in 8 bits per element")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the cold-cache and the scaled-matcher measurements")
     ap.add_argument("--no-configs", action="store_true", help="measure --workload only, not the other bf16 configurations beside it")
@@ -389,7 +400,8 @@ def main():
     import torch
 
     assert torch.cuda.is_available(), "bench.py needs a GPU; there is no CPU fallback"
-    head, wl = measure(args.workload, args.steps, args.warmup, args, with_extras=not args.no_extras and not args.only)
+    head, wl = measure(args.workload, args.steps, args.warmup, args, with_extras=not args.no_extras and not args.only,
+                       kv_pool=args.kv_pool)
     res = {"metric": "extend_prefill_tokens_per_s", "value": head["value"], "unit": "tokens/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic"}
@@ -399,10 +411,16 @@ def main():
     if not args.no_configs and not args.only:
         rows = []
         for name in BF16_CONFIGS:
-            if name == args.workload:
+            if name == args.workload and args.kv_pool == "bf16":
                 rows.append(summary(head))
             else:
                 other, _ = measure(name, min(args.steps, 100), min(args.warmup, 10), args, with_extras=False)
+                rows.append(summary(other))
+        for name in FP8_POOL_CONFIGS:
+            if name == args.workload and args.kv_pool == "fp8":
+                rows.append(summary(head))
+            else:
+                other, _ = measure(name, min(args.steps, 100), min(args.warmup, 10), args, with_extras=False, kv_pool="fp8")
                 rows.append(summary(other))
         res["configs"] = rows
     if not args.no_cpu_baseline:

@@ -21,7 +21,8 @@
  *    B + 1 entries (offsets[0] = 0).
  *  - dtype: PA_F32 computes in fp32 throughout; PA_BF16 takes bf16 inputs, multiplies
  *    on the bf16 matrix cores with fp32 accumulation, keeps softmax in fp32, and
- *    writes bf16.
+ *    writes bf16.  PA_BF16_KV8 is PA_BF16 for every tensor and all arithmetic, with the
+ *    KV pool held in 8 bits per element (see "KV pool"): half the memory per cached token.
  *  - Supported shapes: D in {64, 128}; Hq a multiple of Hkv; page_size >= 1 dividing
  *    num_slots (any size, a power of two or not).  Tensor base pointers must be 16-byte aligned.
  */
@@ -44,6 +45,7 @@ extern "C" {
 
 #define PA_F32 0
 #define PA_BF16 1
+#define PA_BF16_KV8 2 /* as PA_BF16, with the KV pool held in 8 bits per element (see "KV pool" below) */
 
 typedef struct pa_tree pa_tree;
 
@@ -239,6 +241,18 @@ int pa_history_gpu_load(pa_history* h, int32_t gpu, int64_t now, double* L, doub
  * pa_extend_attention / pa_gather_kv read it.  The caller allocates
  * pa_kv_pool_bytes(...) bytes of device memory (16-byte aligned); contents of slots
  * never appended are never read for a request whose slot_idx does not name them.
+ *
+ * With PA_BF16_KV8 (Sec. 3.3: memory for KV decides what can stay cached; the paper fixes no
+ * storage format, this one is the library's) a row - the D elements of one token, KV head and
+ * K or V - is kept as D one-byte codes and one signed exponent byte k: the value stored is
+ * decode(code) * 2^k, the code being the 8-bit floating-point format with 4 exponent bits
+ * (bias 7), 3 mantissa bits, no infinities and largest value 448.  pa_append_kv chooses k as
+ * the smallest integer with max|row| * 2^-k <= 448 (0 for a row of zeros, kept within
+ * [-100, 119]) and rounds x * 2^-k to the nearest code, ties to the even mantissa, anything
+ * still above 448 to 448.  Every stored value is exactly a finite bf16; pa_gather_kv returns
+ * those values, and pa_extend_attention computes over them as PA_BF16 does over its pool.
+ * Rows given to pa_append_kv must be finite.  The pool takes num_slots * 2 * Hkv * (D + 1)
+ * bytes.
  * --------------------------------------------------------------------------------- */
 size_t pa_kv_pool_bytes(int64_t num_slots, int Hkv, int D, int dtype, int page_size);
 
@@ -280,7 +294,7 @@ int pa_match_prefixes(const pa_tree* tree, const int32_t* tokens, const int32_t*
  *     out[e0 + i, h, :] = sum_j softmax_j(scale * <q_ext[e0 + i, h, :], K_j[g, :]>) V_j[g, :]
  * with e0 = ext_offsets[r].
  *
- * q_ext        [T, Hq, D]   k_ext, v_ext  [T, Hkv, D]   out [T, Hq, D]   (dtype elements)
+ * q_ext        [T, Hq, D]   k_ext, v_ext  [T, Hkv, D]   out [T, Hq, D]   (dtype elements; bf16 with PA_BF16_KV8)
  * kv_pool      pool written by pa_append_kv with the same Hkv, D, dtype, page_size, num_slots
  * slot_idx, slot_offsets   as produced by pa_match_prefixes (slot_offsets = its offsets).  The bf16 path lets
  *                requests that share a prefix, or a first part of it, share row tiles, and finds them by comparing

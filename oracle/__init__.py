@@ -107,7 +107,7 @@ def match_prefixes(cached, tokens, offsets):
 
 def new_pool(num_slots: int, Hkv: int, D: int, dtype: str):
     """The oracle's own dense pool: K and V arrays [num_slots, Hkv, D], zero-filled."""
-    dt = np.float32 if dtype == "f32" else np.uint16
+    dt = np.float32 if dtype == "f32" else np.uint16   # ('bf16_kv8': the values the fp8 form stores, as bfloat16)
     return np.zeros((num_slots, Hkv, D), dt), np.zeros((num_slots, Hkv, D), dt)
 
 
@@ -139,6 +139,8 @@ def append_kv(pool_k, pool_v, new_slots, k_ext, v_ext, dtype: str):
 def extend_attention(q_ext, k_ext, v_ext, pool_k, pool_v, slot_idx, slot_offsets, prefix_len, ext_len,
                      ext_offsets, scale: float, dtype: str, rows=None) -> np.ndarray:
     """fp64 output [T, Hq, D]; with rows = int array [n,3] of (r, i, h): only those rows, [n, D]."""
+    if dtype == "bf16_kv8":   # the pool given here already holds the values its fp8 form stores (see append_kv)
+        dtype = "bf16"
     q, k, v = _vals(q_ext, dtype), _vals(k_ext, dtype), _vals(v_ext, dtype)
     T, Hq, D = q.shape
     Hkv = k.shape[1]

@@ -300,8 +300,17 @@ class History:
     __del__ = close
 
 
-def kv_pool_bytes(num_slots: int, Hkv: int, D: int, dtype: torch.dtype, page_size: int) -> int:
-    n = int(_lib.pa_kv_pool_bytes(num_slots, Hkv, D, _DTYPES[dtype], page_size))
+def _code(dtype: torch.dtype, kv8: bool) -> int:
+    """The library's dtype value; kv8 = bf16 tensors with the KV pool in its fp8 form (PA_BF16_KV8)."""
+    if kv8:
+        if dtype != torch.bfloat16:
+            raise TypeError("the fp8 KV pool goes with bfloat16 tensors")
+        return 2
+    return _DTYPES[dtype]
+
+
+def kv_pool_bytes(num_slots: int, Hkv: int, D: int, dtype: torch.dtype, page_size: int, kv8: bool = False) -> int:
+    n = int(_lib.pa_kv_pool_bytes(num_slots, Hkv, D, _code(dtype, kv8), page_size))
     if n == 0:
         raise ValueError("pa_kv_pool_bytes: invalid arguments")
     return n
@@ -335,11 +344,11 @@ def extend_attention(q_ext: torch.Tensor, k_ext: torch.Tensor, v_ext: torch.Tens
                      slot_idx: torch.Tensor, slot_offsets: torch.Tensor, prefix_len: torch.Tensor,
                      ext_len: torch.Tensor, ext_offsets: torch.Tensor, scale: float, *, page_size: int,
                      num_slots: int, max_kv_len: int, out: Optional[torch.Tensor] = None,
-                     workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                     workspace: Optional[torch.Tensor] = None, stream=None, kv8: bool = False) -> torch.Tensor:
     """q_ext [T,Hq,D], k_ext/v_ext [T,Hkv,D] -> out [T,Hq,D].  Asynchronous on the stream."""
     T, Hq, D = q_ext.shape
     Hkv = k_ext.shape[1]
-    dt = _DTYPES[q_ext.dtype]
+    dt = _code(q_ext.dtype, kv8)
     for name, t in (("q_ext", q_ext), ("k_ext", k_ext), ("v_ext", v_ext)):
         if not (t.is_cuda and t.is_contiguous() and t.dtype == q_ext.dtype):
             raise TypeError(f"{name} must be a contiguous CUDA tensor of dtype {q_ext.dtype}")
@@ -351,7 +360,7 @@ def extend_attention(q_ext: torch.Tensor, k_ext: torch.Tensor, v_ext: torch.Tens
     B = prefix_len.numel()
     if slot_offsets.numel() != B + 1 or ext_offsets.numel() != B + 1 or ext_len.numel() != B:
         raise ValueError("per-request arrays disagree on B")
-    if kv_pool.numel() * kv_pool.element_size() < kv_pool_bytes(num_slots, Hkv, D, q_ext.dtype, page_size):
+    if kv_pool.numel() * kv_pool.element_size() < kv_pool_bytes(num_slots, Hkv, D, q_ext.dtype, page_size, kv8):
         raise ValueError("kv_pool smaller than pa_kv_pool_bytes")
     if out is None:
         out = torch.empty_like(q_ext)
@@ -371,7 +380,7 @@ def extend_attention(q_ext: torch.Tensor, k_ext: torch.Tensor, v_ext: torch.Tens
 def extend_attention_static(q_ext: torch.Tensor, k_ext: torch.Tensor, v_ext: torch.Tensor, kv_pool: torch.Tensor,
                             slot_idx: torch.Tensor, slot_offsets: torch.Tensor, prefix_len: torch.Tensor,
                             ext_len: torch.Tensor, ext_offsets: torch.Tensor, scale: float, *, page_size: int,
-                            num_slots: int, max_kv_len: int, out: torch.Tensor, stream=None) -> torch.Tensor:
+                            num_slots: int, max_kv_len: int, out: torch.Tensor, stream=None, kv8: bool = False) -> torch.Tensor:
     """pa_extend_attention_static: as extend_attention, with the library's own scratch buffer as workspace; `out` is
     the caller's (nothing is allocated here either)."""
     T, Hq, D = q_ext.shape
@@ -379,7 +388,7 @@ def extend_attention_static(q_ext: torch.Tensor, k_ext: torch.Tensor, v_ext: tor
     B = prefix_len.numel()
     _check(_lib.pa_extend_attention_static(_ptr(q_ext), _ptr(k_ext), _ptr(v_ext), _ptr(kv_pool), _ptr(slot_idx),
                                            _ptr(slot_offsets), _ptr(prefix_len), _ptr(ext_len), _ptr(ext_offsets), B, T,
-                                           max_kv_len, Hq, Hkv, D, page_size, num_slots, _DTYPES[q_ext.dtype], float(scale),
+                                           max_kv_len, Hq, Hkv, D, page_size, num_slots, _code(q_ext.dtype, kv8), float(scale),
                                            _ptr(out), _stream(stream)), "pa_extend_attention_static")
     return out
 
@@ -396,27 +405,27 @@ def extend_set_row_sharing(on: bool) -> None:
 
 
 def append_kv(kv_pool: torch.Tensor, new_slots: torch.Tensor, k_ext: torch.Tensor, v_ext: torch.Tensor, *,
-              page_size: int, num_slots: int, stream=None) -> None:
+              page_size: int, num_slots: int, stream=None, kv8: bool = False) -> None:
     T, Hkv, D = k_ext.shape
     _dev_i32(new_slots, "new_slots")
     if new_slots.numel() != T or v_ext.shape != k_ext.shape or v_ext.dtype != k_ext.dtype:
         raise ValueError("append_kv: shape mismatch")
     if not (k_ext.is_cuda and v_ext.is_cuda and k_ext.is_contiguous() and v_ext.is_contiguous()):
         raise TypeError("k_ext / v_ext must be contiguous CUDA tensors")
-    if kv_pool.numel() * kv_pool.element_size() < kv_pool_bytes(num_slots, Hkv, D, k_ext.dtype, page_size):
+    if kv_pool.numel() * kv_pool.element_size() < kv_pool_bytes(num_slots, Hkv, D, k_ext.dtype, page_size, kv8):
         raise ValueError("kv_pool smaller than pa_kv_pool_bytes")
     _check(_lib.pa_append_kv(_ptr(kv_pool), _ptr(new_slots), _ptr(k_ext), _ptr(v_ext), T, Hkv, D, page_size,
-                             num_slots, _DTYPES[k_ext.dtype], _stream(stream)), "pa_append_kv")
+                             num_slots, _code(k_ext.dtype, kv8), _stream(stream)), "pa_append_kv")
 
 
 def gather_kv(kv_pool: torch.Tensor, slots: torch.Tensor, *, Hkv: int, D: int, dtype: torch.dtype, page_size: int,
-              num_slots: int, stream=None):
+              num_slots: int, stream=None, kv8: bool = False):
     """Test/debug helper: dense (k, v) [n, Hkv, D] of the given slots."""
     _dev_i32(slots, "slots")
     n = slots.numel()
     k = torch.empty((n, Hkv, D), dtype=dtype, device=slots.device)
     v = torch.empty_like(k)
-    _check(_lib.pa_gather_kv(_ptr(kv_pool), _ptr(slots), n, Hkv, D, page_size, num_slots, _DTYPES[dtype], _ptr(k),
+    _check(_lib.pa_gather_kv(_ptr(kv_pool), _ptr(slots), n, Hkv, D, page_size, num_slots, _code(dtype, kv8), _ptr(k),
                              _ptr(v), _stream(stream)), "pa_gather_kv")
     return k, v
 

@@ -8,7 +8,7 @@ int pa_extend_attention_f32(const void* q_ext, const void* k_ext, const void* v_
 int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v_ext, const void* kv_pool,
                              const int32_t* slot_idx, const int32_t* slot_offsets, const int32_t* prefix_len,
                              const int32_t* ext_len, const int32_t* ext_offsets, int B, int64_t T, int64_t max_kv_len,
-                             int Hq, int Hkv, int D, int page_size, int64_t num_slots, float scale, void* out,
+                             int Hq, int Hkv, int D, int page_size, int64_t num_slots, bool kv8, float scale, void* out,
                              void* workspace, size_t workspace_bytes, hipStream_t stream);
 size_t pa_extend_workspace_bytes_bf16(int B, int64_t T, int64_t max_kv_len, int Hq, int Hkv, int D);
 
@@ -16,7 +16,7 @@ extern "C" size_t pa_extend_workspace_bytes(int B, int64_t T, int64_t max_kv_len
     if (B < 0 || T < 0 || max_kv_len < 0 || !pa::shape_ok(Hq, Hkv, D)) return 0;
     if (T > INT32_MAX / (Hq / Hkv) - 256 || max_kv_len > INT32_MAX / 2) return 0;
     if (dtype == PA_F32) return 256;  // the fp32 kernel needs no scratch; a non-zero size keeps "0 = invalid"
-    if (dtype == PA_BF16) return pa_extend_workspace_bytes_bf16(B, T, max_kv_len, Hq, Hkv, D);
+    if (dtype == PA_BF16 || dtype == PA_BF16_KV8) return pa_extend_workspace_bytes_bf16(B, T, max_kv_len, Hq, Hkv, D);
     return 0;
 }
 
@@ -24,7 +24,7 @@ int pa_extend_attention_bf16_static(const void* q_ext, const void* k_ext, const 
                                     const int32_t* slot_idx, const int32_t* slot_offsets, const int32_t* prefix_len,
                                     const int32_t* ext_len, const int32_t* ext_offsets, int B, int64_t T,
                                     int64_t max_kv_len, int Hq, int Hkv, int D, int page_size, int64_t num_slots,
-                                    float scale, void* out, hipStream_t stream);
+                                    bool kv8, float scale, void* out, hipStream_t stream);
 
 // What both entry points ask of their arguments.  *nothing_to_do: an empty batch (no pointer is looked at then).
 static int check_extend_args(const void* q_ext, const void* k_ext, const void* v_ext, const void* kv_pool,
@@ -32,7 +32,7 @@ static int check_extend_args(const void* q_ext, const void* k_ext, const void* v
                              const int32_t* ext_offsets, int B, int64_t T, int64_t max_kv_len, int Hq, int Hkv, int D,
                              int page_size, int64_t num_slots, int dtype, const void* out, bool* nothing_to_do) {
     *nothing_to_do = false;
-    PA_REQUIRE(dtype == PA_F32 || dtype == PA_BF16, "pa_extend_attention: unknown dtype %d", dtype);
+    PA_REQUIRE(dtype == PA_F32 || dtype == PA_BF16 || dtype == PA_BF16_KV8, "pa_extend_attention: unknown dtype %d", dtype);
     PA_REQUIRE(pa::shape_ok(Hq, Hkv, D), "pa_extend_attention: unsupported shape Hq=%d Hkv=%d D=%d", Hq, Hkv, D);
     PA_REQUIRE(B >= 0 && T >= 0 && max_kv_len >= 0, "pa_extend_attention: negative size");
     PA_REQUIRE(T <= INT32_MAX / (Hq / Hkv) - 256 && max_kv_len <= INT32_MAX / 2, "pa_extend_attention: batch too large for 32-bit row indices");
@@ -66,8 +66,8 @@ extern "C" int pa_extend_attention(const void* q_ext, const void* k_ext, const v
         return pa_extend_attention_f32(q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len,
                                        ext_offsets, B, T, Hq, Hkv, D, page_size, num_slots, scale, out, s);
     return pa_extend_attention_bf16(q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len,
-                                    ext_offsets, B, T, max_kv_len, Hq, Hkv, D, page_size, num_slots, scale, out,
-                                    workspace, workspace_bytes, s);
+                                    ext_offsets, B, T, max_kv_len, Hq, Hkv, D, page_size, num_slots, dtype == PA_BF16_KV8, scale,
+                                    out, workspace, workspace_bytes, s);
 }
 
 extern "C" int pa_extend_attention_static(const void* q_ext, const void* k_ext, const void* v_ext, const void* kv_pool,
@@ -85,5 +85,6 @@ extern "C" int pa_extend_attention_static(const void* q_ext, const void* k_ext, 
         return pa_extend_attention_f32(q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len,
                                        ext_offsets, B, T, Hq, Hkv, D, page_size, num_slots, scale, out, s);
     return pa_extend_attention_bf16_static(q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len,
-                                           ext_offsets, B, T, max_kv_len, Hq, Hkv, D, page_size, num_slots, scale, out, s);
+                                           ext_offsets, B, T, max_kv_len, Hq, Hkv, D, page_size, num_slots,
+                                           dtype == PA_BF16_KV8, scale, out, s);
 }

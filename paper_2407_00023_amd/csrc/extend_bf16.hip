@@ -38,6 +38,7 @@
 #include <type_traits>
 
 #include "common.h"
+#include "fp8_rows.h"
 
 namespace pa {
 
@@ -743,14 +744,20 @@ __device__ __forceinline__ void load_to_lds_16(const void* g, unsigned lds_addr)
 __device__ __forceinline__ void load_to_lds_16(const void* base, unsigned off, unsigned lds_addr) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_addr) : "memory");
 }
+// One byte per lane: lane l of the wave writes the 32-bit word at lds_addr + 4 l (the byte in its low 8 bits).
+__device__ __forceinline__ void load_to_lds_1(const void* g, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_ubyte %0, off" ::"v"(g), "s"(lds_addr) : "memory");
+}
 __device__ __forceinline__ unsigned lds_address(const void* p) {
     return static_cast<unsigned>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const unsigned char*)(p)));
 }
 
-template <int D, int NW, int RB>
+// KV8: the pool holds one-byte codes and row exponents (fp8_rows.h) instead of bfloat16; its rows are decoded into the
+// bfloat16 tiles in LDS, and everything from there on is the same arithmetic.
+template <int D, int NW, int RB, bool KV8>
 __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf16_kernel(
     const __hip_bfloat16* __restrict__ q_ext, const __hip_bfloat16* __restrict__ k_ext,
-    const __hip_bfloat16* __restrict__ v_ext, const __hip_bfloat16* __restrict__ pool,
+    const __hip_bfloat16* __restrict__ v_ext, const __hip_bfloat16* __restrict__ pool, const signed char* __restrict__ pool_exp,
     const int32_t* __restrict__ slot_idx, int Hq, int Hkv, int page_size, int page_shift, unsigned page_magic,
     int page_mshift, int num_slots, int fast_ok, float scale_log2e, __hip_bfloat16* __restrict__ out, const int32_t* __restrict__ hdr,
     const int4* __restrict__ item_tab, const int4* __restrict__ member_tab, float* __restrict__ part_o,
@@ -777,7 +784,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf
     // (build option for experiments: where a workgroup's cycles go - clk[2..7] = cycles in runs of assembly tiles, tiles
     // done there, cycles in general tiles, their number, cycles before the key loop, cycles after it)
     const long long probe_t0 = clk ? clock64() : 0;
-    long long probe_fast = 0, probe_gen = 0, probe_gen_issue = 0, probe_gen_math = 0, probe_single = 0;
+    long long probe_fast = 0, probe_gen = 0, probe_gen_issue = 0, probe_gen_math = 0, probe_single = 0, probe_single_issue = 0, probe_landed = 0;
     int probe_nfast = 0, probe_ngen = 0, probe_nsingle = 0;
 #endif
     const int4 rec0 = item_tab[3 * static_cast<size_t>(item)], rec1 = item_tab[3 * static_cast<size_t>(item) + 1];
@@ -974,6 +981,94 @@ __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf
         }
     };
 
+    // ---- fp8 pool.  A pool row arrives as its D codes, in the first half of the LDS bytes its bfloat16 form will take
+    // (the lanes that would fetch the second half stay idle), and its exponent as one byte in a small staging area of
+    // the wave; rows of the extend tensors arrive as before.  Once the loads have landed, landed8() turns the codes
+    // into bfloat16 in place: the lanes of a row (one wave, in step) all read their 8 codes before any of them writes,
+    // and no other wave touches the row until the barrier that follows.
+    constexpr int EXPB = 256 * 2 * UPW;  // staging bytes per wave: one 32-bit word per lane, load block and tensor
+    constexpr int EX_OFF = (kStages * STAGEB + (4 * MT + 1 + 2 * NW) * static_cast<int>(sizeof(int)) + 255) & ~255;
+    const unsigned char* pool8_g = reinterpret_cast<const unsigned char*>(pool) + static_cast<size_t>(g) * page_size * D;
+    const size_t page_stride8 = static_cast<size_t>(2) * Hkv * page_size * D;
+    const size_t v_off8 = static_cast<size_t>(Hkv) * page_size * D;
+    const signed char* exp_g = pool_exp + static_cast<size_t>(g) * page_size;
+    const size_t exp_page = static_cast<size_t>(2) * Hkv * page_size, exp_v = static_cast<size_t>(Hkv) * page_size;
+    int raw_mask = 0;  // bit u: this lane's row of load block u is a pool row (codes to be decoded)
+    auto issue8 = [&](int p0, int ring) __attribute__((always_inline)) {
+        const unsigned sk = __builtin_amdgcn_readfirstlane(smem_addr + ring * STAGEB);
+        const unsigned ex = __builtin_amdgcn_readfirstlane(smem_addr + EX_OFF + wave * EXPB);
+        if (shared)
+            while (cur_member + 1 < n_members && s_mseg[cur_member + 1] <= p0) ++cur_member;
+        raw_mask = 0;
+#pragma unroll
+        for (int u = 0; u < UPW; ++u) {
+            const int blk = wave * UPW + u;
+            const int p = min(p0 + blk * RPB + ld_rowl, kv_hi - 1);
+            bool ext = p >= P;
+            const unsigned sl = static_cast<unsigned>(min(max(sl_next[u], 0), num_slots - 1));  // never outside the pool
+            const unsigned pg = page_shift >= 0 ? sl >> page_shift : __umulhi(sl, page_magic) >> page_mshift;
+            const unsigned o = sl - pg * static_cast<unsigned>(page_size);
+            int64_t xrow = p - P;
+            if (shared && ext) {
+                const int k = member_at(cur_member, p);
+                const int q = p - s_mseg[k], own = s_mown[k];
+                xrow = static_cast<int64_t>(s_mx0[k]) + (q - own);
+                ext = q >= own;
+            }
+            if (ext) {
+                const size_t off = static_cast<size_t>(xrow) * x_stride;
+                load_to_lds_16(kx_g + off + ld_koff(u), sk + blk * 1024);
+                load_to_lds_16(vx_g + off + ld_voff(u), sk + TILEB + blk * 1024);
+            } else {
+                raw_mask |= 1 << u;
+                if (ld_pos < CPR / 2) {
+                    const unsigned char* ka = pool8_g + static_cast<size_t>(pg) * page_stride8 + o * static_cast<unsigned>(D) + ld_pos * 16;
+                    load_to_lds_16(ka, sk + blk * 1024);
+                    load_to_lds_16(ka + v_off8, sk + TILEB + blk * 1024);
+                }
+                if (ld_pos == 0) {
+                    const signed char* ea = exp_g + static_cast<size_t>(pg) * exp_page + o;
+                    load_to_lds_1(ea, ex + (2 * u) * 256);
+                    load_to_lds_1(ea + exp_v, ex + (2 * u + 1) * 256);
+                }
+            }
+        }
+    };
+    // the tile in ring slot `ring` has landed (this wave's loads have been waited for): decode this wave's pool rows
+    auto landed8 = [&](int ring) __attribute__((always_inline)) {
+        unsigned char* const sk = smem + ring * STAGEB;
+        const int* const ex = reinterpret_cast<const int*>(smem + EX_OFF + wave * EXPB);
+        uint2 kraw[UPW], vraw[UPW];
+        int ke[UPW], ve[UPW];
+#pragma unroll
+        for (int u = 0; u < UPW; ++u) {
+            if ((raw_mask >> u) & 1) {
+                const unsigned char* row = sk + (wave * UPW + u) * 1024 + ld_rowl * ROWB;
+                kraw[u] = *reinterpret_cast<const uint2*>(row + (ld_koff(u) >> 1));
+                vraw[u] = *reinterpret_cast<const uint2*>(row + TILEB + (ld_voff(u) >> 1));
+                ke[u] = ex[(2 * u) * 64 + (lane & ~(CPR - 1))];
+                ve[u] = ex[(2 * u + 1) * 64 + (lane & ~(CPR - 1))];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UPW; ++u) {
+            if ((raw_mask >> u) & 1) {
+                unsigned char* dst = sk + (wave * UPW + u) * 1024 + lane * 16;
+                const float ks = fp8_scale(static_cast<int>(static_cast<signed char>(ke[u] & 0xFF)));
+                const float vs = fp8_scale(static_cast<int>(static_cast<signed char>(ve[u] & 0xFF)));
+                const uint2 ka = fp8_decode4(kraw[u].x, ks), kb = fp8_decode4(kraw[u].y, ks);
+                const uint2 va = fp8_decode4(vraw[u].x, vs), vb = fp8_decode4(vraw[u].y, vs);
+                *reinterpret_cast<uint4*>(dst) = make_uint4(ka.x, ka.y, kb.x, kb.y);
+                *reinterpret_cast<uint4*>(dst + TILEB) = make_uint4(va.x, va.y, vb.x, vb.y);
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the barrier that follows does not wait for LDS writes
+    };
+    auto issue_any = [&](int p0, int ring) __attribute__((always_inline)) {
+        if constexpr (KV8) issue8(p0, ring);
+        else issue(p0, ring);
+    };
+
     f32x16 oacc[RB][NB];
     float m_run[RB], l_run[RB];  // running maximum (scaled, log2 domain) and this lane's share of the sum
 #pragma unroll
@@ -1121,8 +1216,10 @@ __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf
         const long long probe_i0 = clk ? clock64() : 0;
 #endif
         if (issue_next && p0 + kKT < kv_hi) {
-            issue(p0 + kKT, ring ^ 1);  // the next tile flies during this tile's arithmetic
+            issue_any(p0 + kKT, ring ^ 1);  // the next tile flies during this tile's arithmetic
             load_slots(p0 + 2 * kKT);
+        } else if (issue_next) {
+            raw_mask = 0;  // (the last tile: nothing lands after it)
         }
 #ifdef PA_PROBE_DETAIL
         const long long probe_i1 = clk ? clock64() : 0;
@@ -1150,14 +1247,17 @@ __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf
         if (!(wave_on && p0 <= P + wave_i_last && no_mask)) return 0;
         const int first = min(p0 + kKT, kv_hi - 1), last = min(p0 + 2 * kKT - 1, kv_hi - 1);
         // (after the common keys of a shared tile come several requests' keys: never one run of extend tokens)
-        return last < P ? 1 : (first >= P && !shared) ? 2 : 0;
+        // (fp8 pool: fast_ok bit 0 allows runs over the extend tokens, bit 1 runs over the pool)
+        if (last < P) return !KV8 || (fast_ok & 2) ? 1 : 0;
+        return (first >= P && !shared && (!KV8 || (fast_ok & 1))) ? 2 : 0;
     };
 
     // ---- prologue: first tile into ring slot 0 ----
     load_slots(kv_lo);
-    issue(kv_lo, 0);
+    issue_any(kv_lo, 0);
     load_slots(kv_lo + kKT);
     wait_vm_all();
+    if constexpr (KV8) landed8(0);
     wg_barrier();
 
     // clock probe (benchmarks only): shader cycles and ticks of the constant 100 MHz counter across the key loop
@@ -1182,6 +1282,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf
     // finished; then on to the next tile
     auto next_tile = [&]() __attribute__((always_inline)) {
         wait_vm_all();
+        if constexpr (KV8) landed8(ring ^ 1);
         wg_barrier();
         move_read_addresses(ring);
         ring ^= 1;
@@ -1194,7 +1295,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf
     // that no run takes because of what their successor is (prefix and extend rows mixed) or because they touch the
     // causal diagonal; not in shared tiles (a second visibility bound).  Neither before the running maximum exists.
     auto single_tile_ok = [&](int p0) __attribute__((always_inline)) -> bool {
-        return fast_ok && D == 128 && RB == 1 && NW == 4 && (smem_addr & 255u) == 0 && !shared && wave_on && p0 <= P + wave_i_last;
+        return (fast_ok || KV8) && D == 128 && RB == 1 && NW == 4 && (smem_addr & 255u) == 0 && !shared && wave_on && p0 <= P + wave_i_last;
     };
     // The assembly tiles want a running maximum to start from, and any lower bound of the true one will do as long as it
     // is not 2^40 short (then the tile is handed to the general code, as always): the largest score of the first 32 keys,
@@ -1202,7 +1303,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf
     // key block is multiplied twice) instead of in the general code, which establishes the maximum otherwise.
     if constexpr (D == 128 && RB == 1 && NW == 4) {
         // (also in shared tiles: the keys of the common prefix are visible to every row)
-        if (fast_ok && (smem_addr & 255u) == 0 && wave_on && kv_lo <= P + wave_i_last && kv_lo + 32 <= blk_vis_min[0] && kv_lo + 32 <= kv_hi) {
+        if ((fast_ok || KV8) && (smem_addr & 255u) == 0 && wave_on && kv_lo <= P + wave_i_last && kv_lo + 32 <= blk_vis_min[0] && kv_lo + 32 <= kv_hi) {
             const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             bf16x8 kf[KS];
 #pragma unroll
@@ -1229,18 +1330,27 @@ __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf
         int mode = 0, kind = 0;
         if (fast_allowed && __all(have_m)) {
             kind = tile_kind(p0);
-            mode = kind == 1 ? (fast_ok == 2 ? 3 : 1) : kind == 2 ? 2 : single_tile_ok(p0) ? (p0 + kKT > blk_vis_min[0] ? 5 : 4) : 0;
+            mode = kind == 1 ? (KV8 ? 6 : fast_ok == 2 ? 3 : 1) : kind == 2 ? 2 : single_tile_ok(p0) ? (p0 + kKT > blk_vis_min[0] ? 5 : 4) : 0;
         }
         if (mode != 0) {
-            if constexpr (D == 128 && RB == 1 && (NW == 4 || NW == 8)) {
+            if constexpr (D == 128 && RB == 1 && (NW == 4 || (NW == 8 && !KV8))) {
                 // Against the running maximum as it stands: scores never move it in there (a row's probabilities may
                 // reach 2^40 instead), the output accumulators are touched by MFMAs only.
                 int p_end = p0 + kKT;
-                if (mode <= 3) {
+                if (mode <= 3 || mode == 6) {
                     while (tile_kind(p_end) == kind) p_end += kKT;
+                    raw_mask = 0;  // (fp8 pool: a run decodes what it loads itself)
                 } else if (p0 + kKT < kv_hi) {
-                    issue(p0 + kKT, ring ^ 1);
+#ifdef PA_PROBE_DETAIL
+                    const long long probe_s0 = clk ? clock64() : 0;
+#endif
+                    issue_any(p0 + kKT, ring ^ 1);
                     load_slots(p0 + 2 * kKT);
+#ifdef PA_PROBE_DETAIL
+                    if (clk) probe_single_issue += clock64() - probe_s0;
+#endif
+                } else {
+                    raw_mask = 0;
                 }
 #ifdef PA_PROBE_DETAIL
                 const long long probe_r0 = clk ? clock64() : 0;
@@ -1263,18 +1373,27 @@ __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf
                     return reinterpret_cast<const void*>(lo | (hi << 32));
                 };
                 // (mode 3: the pool is too large for 32-bit byte offsets; rows are then counted in units of 256 bytes)
-                const i32x8 c = {uni(page_shift), uni(page_size - 1), uni(static_cast<int>(mode == 3 ? page_stride / ROWB : page_stride)), uni(num_slots - 1),
-                                 uni(P - 1), uni(static_cast<int>(x_stride)), uni(kv_hi - 1 - P),
+                // (mode 6, the fp8 pool: strides of the codes and of the row exponents, and where the latter lie)
+                const uint64_t exp_addr = reinterpret_cast<uint64_t>(exp_g);
+                const i32x8 c = {uni(page_shift), uni(page_size - 1),
+                                 uni(static_cast<int>(mode == 6 ? page_stride8 : mode == 3 ? page_stride / ROWB : page_stride)), uni(num_slots - 1),
+                                 uni(P - 1), uni(static_cast<int>(mode == 6 ? exp_page : x_stride)),
+                                 uni(mode == 6 ? static_cast<int>(exp_v) : kv_hi - 1 - P),
                                  uni(static_cast<int>(smem_addr) + wave * (UPW * 1024))};
-                const i32x4 c2 = {uni(128), uni(192), uni(P), uni(__float_as_int(scale_log2e))};
+                const i32x4 c2 = {uni(mode == 6 ? static_cast<int>(exp_addr) : 128), uni(mode == 6 ? static_cast<int>(exp_addr >> 32) : 192), uni(P),
+                                  uni(__float_as_int(scale_log2e))};
                 p0 = uni(p0);
                 ring = uni(ring);
                 p_end = uni(p_end);
                 const int row_in_tile = wave * (UPW * RPB) + ld_rowl;
-                const void* base_k = mode == 2 ? static_cast<const void*>(kx_g) : static_cast<const void*>(pool_g);
-                const void* base_v = mode == 2 ? static_cast<const void*>(vx_g) : static_cast<const void*>(pool_g + v_off32);
+                const void* base_k = mode == 2 ? static_cast<const void*>(kx_g) : mode == 6 ? static_cast<const void*>(pool8_g) : static_cast<const void*>(pool_g);
+                const void* base_v = mode == 2 ? static_cast<const void*>(vx_g) : mode == 6 ? static_cast<const void*>(pool8_g + v_off8) : static_cast<const void*>(pool_g + v_off32);
                 const int lim = vis_end[0] - p0 - 4 * hh;
-                if constexpr (NW == 4)
+                if constexpr (KV8)  // (single tiles only; they end with this wave's loads landed and leave the barrier to the caller)
+                    fast_tiles_d128_kv8(uni(mode), oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
+                                        k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
+                                        uni_ptr(base_k), uni_ptr(base_v), lim, c, c2, uni(static_cast<int>(smem_addr) + EX_OFF + wave * EXPB));
+                else if constexpr (NW == 4)
                     fast_tiles_d128(uni(mode), oacc[0][0], oacc[0][1], oacc[0][2], oacc[0][3], q_lo, q_hi, l_run[0], -m_run[0], sl_next,
                                     k_rd[0], v_rd[0][0], ld_koff0, ld_voff0, row_in_tile, p0, ring, st, p_end, uni_ptr(slots),
                                     uni_ptr(base_k), uni_ptr(base_v), lim, c, c2);
@@ -1284,7 +1403,7 @@ __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf
                                        uni_ptr(base_k), uni_ptr(base_v), lim, c, c2);
 #ifdef PA_PROBE_DETAIL
                 if (clk) {
-                    if (mode <= 3) {
+                    if (mode <= 3 || mode == 6) {
                         probe_fast += clock64() - probe_r0;
                         probe_nfast += (p0 - p_start) / kKT;
                     } else {
@@ -1293,11 +1412,24 @@ __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf
                     }
                 }
 #endif
+                if constexpr (KV8) {
+                    if (mode == 6 && st != 0) raw_mask = (1 << UPW) - 1;  // left inside a tile: the next one's rows are still codes
+                    if (st == 0 && mode != 6 && mode >= 4) {
+#ifdef PA_PROBE_DETAIL
+                        const long long probe_l0 = clk ? clock64() : 0;
+#endif
+                        landed8(ring);
+#ifdef PA_PROBE_DETAIL
+                        if (clk) probe_landed += clock64() - probe_l0;
+#endif
+                        wg_barrier();
+                    }
+                }
                 if (((p0 - p_start) / kKT) & 1) move_read_addresses(ring_start);
                 // (a run fetched slot ids from the common list only: where the tile they are for holds a member's own
                 // prefix keys they are fetched again, from that member's list.  That tile is the next one, or, if the
                 // run was left inside a tile - the next one's loads are in flight then - the one after it.)
-                if (mode <= 3 && has_own_prefix()) {
+                if ((mode <= 3 || mode == 6) && has_own_prefix()) {
                     const int pn = p0 + (st == 0 ? kKT : 2 * kKT);
                     if (pn + kKT > P) load_slots(pn);
                 }
@@ -1373,6 +1505,8 @@ __global__ __launch_bounds__(NW * 64, RB == 1 && NW == 4 ? 2 : 1) void extend_bf
         atomicAdd(clk + 9, static_cast<unsigned long long>(probe_gen_math));
         atomicAdd(clk + 10, static_cast<unsigned long long>(probe_single));
         atomicAdd(clk + 11, static_cast<unsigned long long>(probe_nsingle));
+        atomicAdd(clk + 12, static_cast<unsigned long long>(probe_single_issue));
+        atomicAdd(clk + 13, static_cast<unsigned long long>(probe_landed));
     }
 #endif
 }
@@ -1465,7 +1599,7 @@ static void page_divider(int d, int* shift, unsigned* magic, int* mshift) {
     *mshift = k - 32;
 }
 
-template <int D, int NW, int RB>
+template <int D, int NW, int RB, bool KV8>
 static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_ext, const void* v_ext,
                          const void* kv_pool, const int32_t* slot_idx, const int32_t* ext_len, const int32_t* ext_offsets,
                          int Hq, int Hkv, int page_size, int64_t num_slots, int64_t T_total, float scale_log2e, void* out,
@@ -1473,7 +1607,9 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
                          const int4* item_tab, const int32_t* merge_tiles, float* part_o, float* part_ml,
                          unsigned long long* clk, hipStream_t stream) {
     // the K/V ring, and behind it the table of a shared tile's members (4 ints each, one int more) and 2 ints per wave
-    constexpr size_t lds_bytes = static_cast<size_t>(kStages) * 2 * kKT * D * 2 + (4 * 32 * RB * NW + 1 + 2 * NW) * sizeof(int);
+    // (fp8 pool: rounded up to 256 bytes, then one 32-bit word per lane, load block of a wave and tensor for the row exponents)
+    constexpr size_t lds_plain = static_cast<size_t>(kStages) * 2 * kKT * D * 2 + (4 * 32 * RB * NW + 1 + 2 * NW) * sizeof(int);
+    constexpr size_t lds_bytes = KV8 ? ((lds_plain + 255) & ~size_t{255}) + static_cast<size_t>(NW) * 256 * 2 * (kKT / (1024 / (D * 2)) / NW) : lds_plain;
     int page_shift = -1, page_mshift = 0;
     unsigned page_magic = 0;
     page_divider(page_size, &page_shift, &page_magic, &page_mshift);
@@ -1483,7 +1619,7 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
     const char* pad_env = getenv("PA_PROBE_LDS_PAD");
     const size_t lds_pad = pad_env ? static_cast<size_t>(atol(pad_env)) : 0;
     if (lds_pad)
-        PA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&extend_bf16_kernel<D, NW, RB>),
+        PA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&extend_bf16_kernel<D, NW, RB, KV8>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes + lds_pad)));
 #else
     constexpr size_t lds_pad = 0;
@@ -1500,12 +1636,19 @@ static int launch_extend(const ExtendPlan& p, const void* q_ext, const void* k_e
     const bool ok32 = common_ok && pool_bytes < (int64_t{1} << 32) && page_bytes < (1 << 24);
     const bool ok64 = common_ok && rowb == 256 && (reinterpret_cast<uintptr_t>(kv_pool) & 255u) == 0 &&
                       page_bytes / rowb < (1 << 24) && pool_bytes / rowb < (int64_t{1} << 28);
-    const int fast_ok = ok32 ? 1 : ok64 ? 2 : 0;
+    // (fp8 pool: 1 = the extend tensors can be addressed by 32-bit offsets, all that its runs of tiles ask for)
+    // (fp8 pool: bit 0 = the extend tensors can be addressed by 32-bit offsets, as the runs over extend tokens do; bit 1 =
+    // so can the codes, with page numbers and page strides that fit the 24-bit multiplications of the runs over the pool)
+    const bool ext_ok = T_total < (1 << 24) && T_total * Hkv * rowb < (int64_t{1} << 32);
+    const bool pool8_ok = page_shift >= 0 && num_slots / page_size < (1 << 24) && pool_bytes / 2 < (int64_t{1} << 32) && page_bytes / 2 < (1 << 24);
+    const int fast_ok = KV8 ? (ext_ok ? 1 : 0) | (pool8_ok ? 2 : 0) : ok32 ? 1 : ok64 ? 2 : 0;
+    // (fp8 pool: the row exponents lie behind the codes)
+    const signed char* pool_exp = KV8 ? static_cast<const signed char*>(kv_pool) + static_cast<size_t>(num_slots) * 2u * Hkv * D : nullptr;
     {
         ProfScope prof(kProfExtend, stream);
-        hipLaunchKernelGGL((extend_bf16_kernel<D, NW, RB>), grid, dim3(NW * 64), lds_bytes + lds_pad, stream,
+        hipLaunchKernelGGL((extend_bf16_kernel<D, NW, RB, KV8>), grid, dim3(NW * 64), lds_bytes + lds_pad, stream,
                            static_cast<const __hip_bfloat16*>(q_ext), static_cast<const __hip_bfloat16*>(k_ext),
-                           static_cast<const __hip_bfloat16*>(v_ext), static_cast<const __hip_bfloat16*>(kv_pool), slot_idx,
+                           static_cast<const __hip_bfloat16*>(v_ext), static_cast<const __hip_bfloat16*>(kv_pool), pool_exp, slot_idx,
                            Hq, Hkv, page_size, page_shift, page_magic, page_mshift, static_cast<int>(num_slots), fast_ok,
                            scale_log2e,
                            static_cast<__hip_bfloat16*>(out), hdr, item_tab, member_tab, part_o, part_ml, clk);
@@ -1563,7 +1706,7 @@ size_t pa_extend_workspace_bytes_bf16(int B, int64_t T, int64_t max_kv_len, int 
 static int run_extend_bf16(pa::ExtendPlan p, const void* q_ext, const void* k_ext, const void* v_ext, const void* kv_pool,
                            const int32_t* slot_idx, const int32_t* slot_offsets, const int32_t* prefix_len,
                            const int32_t* ext_len, const int32_t* ext_offsets, int B, int64_t T, int Hq, int Hkv, int D,
-                           int page_size, int64_t num_slots, float scale, void* out, void* workspace, hipStream_t stream) {
+                           int page_size, int64_t num_slots, bool kv8, float scale, void* out, void* workspace, hipStream_t stream) {
     using namespace pa;
     if (!g_row_sharing.load()) p.pack = 0;
     unsigned char* ws = static_cast<unsigned char*>(workspace);
@@ -1586,14 +1729,20 @@ static int run_extend_bf16(pa::ExtendPlan p, const void* q_ext, const void* k_ex
                            G, 32 * p.rb * p.nw, p.tiles_cap, p.items_cap, p.parts_cap, p.merge_cap, p.slots * p.rounds, p.pack, p.tile_parts, hdr, order,
                            tile_tab, tile_aux, member_tab, item_tab, merge_tiles);
     }
-    if (D == 64)
-        launch_extend<64, 4, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots, T,
+    if (kv8 && D == 64)
+        launch_extend<64, 4, 1, true>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots, T,
+                             scale_log2e, out, hdr, tile_tab, tile_aux, member_tab, item_tab, merge_tiles, part_o, part_ml, clk, stream);
+    else if (kv8)
+        launch_extend<128, 4, 1, true>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots, T,
+                              scale_log2e, out, hdr, tile_tab, tile_aux, member_tab, item_tab, merge_tiles, part_o, part_ml, clk, stream);
+    else if (D == 64)
+        launch_extend<64, 4, 1, false>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots, T,
                              scale_log2e, out, hdr, tile_tab, tile_aux, member_tab, item_tab, merge_tiles, part_o, part_ml, clk, stream);
     else if (p.nw == 8)
-        launch_extend<128, 8, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots, T,
+        launch_extend<128, 8, 1, false>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots, T,
                               scale_log2e, out, hdr, tile_tab, tile_aux, member_tab, item_tab, merge_tiles, part_o, part_ml, clk, stream);
     else
-        launch_extend<128, 4, 1>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots, T,
+        launch_extend<128, 4, 1, false>(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, ext_len, ext_offsets, Hq, Hkv, page_size, num_slots, T,
                               scale_log2e, out, hdr, tile_tab, tile_aux, member_tab, item_tab, merge_tiles, part_o, part_ml, clk, stream);
     PA_HIP(hipGetLastError());
     return PA_OK;
@@ -1610,16 +1759,16 @@ static int check_bf16_args(float scale, int64_t num_slots, int page_size, int Hk
 int pa_extend_attention_bf16(const void* q_ext, const void* k_ext, const void* v_ext, const void* kv_pool,
                              const int32_t* slot_idx, const int32_t* slot_offsets, const int32_t* prefix_len,
                              const int32_t* ext_len, const int32_t* ext_offsets, int B, int64_t T, int64_t max_kv_len,
-                             int Hq, int Hkv, int D, int page_size, int64_t num_slots, float scale, void* out,
+                             int Hq, int Hkv, int D, int page_size, int64_t num_slots, bool kv8, float scale, void* out,
                              void* workspace, size_t workspace_bytes, hipStream_t stream) {
     using namespace pa;
     if (const int rc = check_bf16_args(scale, num_slots, page_size, Hkv, D)) return rc;
-    const ExtendPlan p = make_plan(B, T, max_kv_len, Hq, Hkv, D, kRounds, waves_for(B, T, Hq, Hkv, D));  // (sized for shared row tiles whether or not they are on)
+    const ExtendPlan p = make_plan(B, T, max_kv_len, Hq, Hkv, D, kRounds, kv8 ? 4 : waves_for(B, T, Hq, Hkv, D));  // (sized for shared row tiles whether or not they are on)
     if (workspace_bytes < p.total || workspace == nullptr)
         return fail(PA_ENOMEM, "pa_extend_attention: workspace of %zu bytes given, %zu needed", workspace_bytes, p.total);
     PA_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255u) == 0, "pa_extend_attention: workspace must be 256-byte aligned");
     return run_extend_bf16(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, B, T, Hq,
-                           Hkv, D, page_size, num_slots, scale, out, workspace, stream);
+                           Hkv, D, page_size, num_slots, kv8, scale, out, workspace, stream);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1656,16 +1805,16 @@ int pa_extend_attention_bf16_static(const void* q_ext, const void* k_ext, const 
                                     const int32_t* slot_idx, const int32_t* slot_offsets, const int32_t* prefix_len,
                                     const int32_t* ext_len, const int32_t* ext_offsets, int B, int64_t T,
                                     int64_t max_kv_len, int Hq, int Hkv, int D, int page_size, int64_t num_slots,
-                                    float scale, void* out, hipStream_t stream) {
+                                    bool kv8, float scale, void* out, hipStream_t stream) {
     using namespace pa;
     if (const int rc = check_bf16_args(scale, num_slots, page_size, Hkv, D)) return rc;
     // (one work item per workgroup slot is aimed at instead of three: a third of the partial results at most)
-    const ExtendPlan p = make_plan(B, T, max_kv_len, Hq, Hkv, D, kRoundsStatic, waves_for(B, T, Hq, Hkv, D));
+    const ExtendPlan p = make_plan(B, T, max_kv_len, Hq, Hkv, D, kRoundsStatic, kv8 ? 4 : waves_for(B, T, Hq, Hkv, D));
     if (p.total > PA_STATIC_SCRATCH_BYTES)
         return fail(PA_ENOMEM, "pa_extend_attention_static: this batch needs %zu bytes of workspace, the library's own buffer holds %zu; "
                                "use pa_extend_attention with a workspace of the caller's", p.total, static_cast<size_t>(PA_STATIC_SCRATCH_BYTES));
     void* ws = nullptr;
     if (const int rc = scratch_of_current_device(&ws)) return rc;
     return run_extend_bf16(p, q_ext, k_ext, v_ext, kv_pool, slot_idx, slot_offsets, prefix_len, ext_len, ext_offsets, B, T, Hq,
-                           Hkv, D, page_size, num_slots, scale, out, ws, stream);
+                           Hkv, D, page_size, num_slots, kv8, scale, out, ws, stream);
 }

@@ -55,6 +55,11 @@ C2 = 60                                 # s[60:63]
 S_T = [68, 69, 70, 71]                  # scratch scalars
 C_SHIFT, C_MASK, C_PSTRIDE, C_NSLOT1, C_P1, C_XSTRIDE, C_EXTMAX, C_LDSW = range(C, C + 8)
 C_128, C_192, C_P, C_SCALE = range(C2, C2 + 4)
+# the fp8 pool's runs (kind pool8) take other values in four of the operands, and one operand more:
+C_EXPPAGE, C_EXPV = C_XSTRIDE, C_EXTMAX   # bytes from one page's row exponents to the next page's; from a K row's exponent to its V row's
+EXP_BASE = C_128                          # s[60:61]: the row exponents of this KV head
+EXST = 51                                 # LDS address of this wave's staging area for row exponents
+DEC_RAW, DEC_EXP, DEC_OUT = 80, 96, 128   # decode at the end of a tile: codes (16 registers), exponents (8), bfloat16 (32)
 LIMIT = "0x53800000"   # 2^40: a lane's probabilities of one key block may sum to this much before the run is left
 ONES = "0x3f803f80"    # bf16 (1, 1)
 
@@ -101,7 +106,7 @@ def tile(st, kind, ring, uid, upw):
     of M0 and the load that uses it, a transcendental and the use of its result, the last MFMA of a score block and
     the first ALU read of it - eleven issue slots) other work stands there instead of s_nop."""
     e = st.emit
-    ext, wide = kind == "ext", kind == "pool64"
+    ext, wide, raw8 = kind == "ext", kind == "pool64", kind == "pool8"
     noload, masked = kind in ("plain", "masked"), kind == "masked"   # (single tiles: the kernel issues the next tile's loads itself)
     here, there = ring * STAGEB, (ring ^ 1) * STAGEB
     last = {}   # fragment number (0..15 K, 16..31 V) -> id of its last LDS read
@@ -187,6 +192,71 @@ def tile(st, kind, ring, uid, upw):
         else:
             e(f"global_load_lds_dwordx4 {v(addr)}, {s(base, 2)}")
 
+    def load_piece8(u, half):
+        """fp8 pool: the next tile's rows as codes.  A row's 128 codes go to the first half of the 256 LDS bytes its
+        bfloat16 form will take (the lanes that would fetch the second half are switched off), its two exponents (K, V)
+        as one byte each to the wave's staging area (one lane per row).  T[6] = 16 (lane % 16)."""
+        if half == 0:
+            e(f"s_add_u32 m0, {s(C_LDSW)}, {there + u * 1024}")
+            e(f"v_med3_i32 {v(T[0])}, {v(SLN[u])}, 0, {s(C_NSLOT1)}")
+            e(f"v_lshrrev_b32 {v(T[1])}, {s(C_SHIFT)}, {v(T[0])}")
+            e(f"v_and_b32 {v(T[0])}, {s(C_MASK)}, {v(T[0])}")
+            e(f"v_mad_u32_u24 {v(T[2])}, {v(T[1])}, {s(C_PSTRIDE)}, {v(T[6])}")
+            e(f"v_lshl_add_u32 {v(T[2])}, {v(T[0])}, 7, {v(T[2])}")
+            e(f"v_mad_u32_u24 {v(T[3])}, {v(T[1])}, {s(C_EXPPAGE)}, {v(T[0])}")
+            e(f"s_mov_b64 exec, {s(MASKS[0], 2)}")
+            e(f"global_load_lds_dwordx4 {v(T[2])}, {s(BASE_K, 2)}")
+            e(f"s_add_u32 m0, {s(C_LDSW)}, {there + TILEB + u * 1024}")
+            e("s_nop 0")
+            e(f"global_load_lds_dwordx4 {v(T[2])}, {s(BASE_V, 2)}")
+            e("s_mov_b64 exec, -1")
+        else:
+            e(f"s_add_u32 m0, {s(EXST)}, {2 * u * 256}")
+            e(f"v_add_u32 {v(T[2])}, {s(C_EXPV)}, {v(T[3])}")
+            e(f"s_mov_b64 exec, {s(MASKS[1], 2)}")
+            e(f"global_load_lds_ubyte {v(T[3])}, {s(EXP_BASE, 2)}")
+            e(f"s_add_u32 m0, {s(EXST)}, {(2 * u + 1) * 256}")
+            e("s_nop 0")
+            e(f"global_load_lds_ubyte {v(T[2])}, {s(EXP_BASE, 2)}")
+            e("s_mov_b64 exec, -1")
+
+    def decode8():
+        """fp8 pool, after this wave's loads have landed: its rows of the next tile from codes to bfloat16, in place.
+        All sixteen lanes of a row read their 8 codes before any of them writes, and nobody else touches the row
+        before the barrier.  The fragment and score registers are free here."""
+        e(f"v_and_b32 {v(T[0])}, 15, {v(ROWI)}")                          # lane / 16
+        e(f"v_lshl_add_u32 {v(T[1])}, {v(T[0])}, 8, {s(C_LDSW)}")          # this lane's row in load block 0, ring slot 0
+        e(f"v_lshl_add_u32 {v(T[5])}, {v(T[0])}, 6, {s(EXST)}")            # the word that holds the row's exponent
+        e(f"v_lshlrev_b32 {v(T[0])}, 4, {v(T[0])}")
+        e(f"v_xor_b32 {v(T[6])}, {v(KOFF0)}, {v(T[0])}")                   # 16 (lane % 16)
+        e(f"v_add_u32 {v(T[6])}, {v(T[1])}, {v(T[6])}")                    # where this lane's 16 bytes of a load block go
+        e(f"v_lshrrev_b32 {v(T[2])}, 1, {v(KOFF0)}")
+        e(f"v_lshrrev_b32 {v(T[3])}, 1, {v(VOFF0)}")
+        for u in range(upw):
+            if 32 * u <= 64:
+                e(f"v_xad_u32 {v(T[4])}, {v(T[2])}, {32 * u}, {v(T[1])}")
+            else:   # (not an inline constant)
+                e(f"v_xor_b32 {v(T[4])}, {32 * u}, {v(T[2])}")
+                e(f"v_add_u32 {v(T[4])}, {v(T[1])}, {v(T[4])}")
+            st.lds_read(f"ds_read_b64 {v(DEC_RAW + 4 * u, 2)}, {v(T[4])} offset:{there + u * 1024}")
+            e(f"v_xad_u32 {v(T[4])}, {v(T[3])}, {8 * u}, {v(T[1])}")
+            st.lds_read(f"ds_read_b64 {v(DEC_RAW + 4 * u + 2, 2)}, {v(T[4])} offset:{there + TILEB + u * 1024}")
+            st.lds_read(f"ds_read_b32 {v(DEC_EXP + 2 * u)}, {v(T[5])} offset:{2 * u * 256}")
+            st.lds_read(f"ds_read_b32 {v(DEC_EXP + 2 * u + 1)}, {v(T[5])} offset:{(2 * u + 1) * 256}")
+        for u in range(upw):
+            for t in range(2):
+                if u == 0 and t == 0:
+                    e("s_waitcnt lgkmcnt(0)")
+                    st.lds.clear()
+                ex, raw, out = DEC_EXP + 2 * u + t, DEC_RAW + 4 * u + 2 * t, DEC_OUT + 4 * (2 * u + t)
+                e(f"v_bfe_i32 {v(ex)}, {v(ex)}, 0, 8")
+                e(f"v_lshl_add_u32 {v(ex)}, {v(ex)}, 23, 0x3f800000")       # 2^k as a float
+                for h in range(2):
+                    e(f"v_cvt_scalef32_pk_bf16_fp8 {v(out + 2 * h)}, {v(raw + h)}, {v(ex)}")
+                    e(f"v_cvt_scalef32_pk_bf16_fp8 {v(out + 2 * h + 1)}, {v(raw + h)}, {v(ex)} op_sel:[1,0,0]")
+                e(f"ds_write_b128 {v(T[6])}, {v(out, 4)} offset:{there + t * TILEB + u * 1024}")
+        e("s_waitcnt lgkmcnt(0)")
+
     pending = []   # probability pair whose row-sum contribution is still to be added: [register]
 
     def flush_sum():
@@ -256,12 +326,18 @@ def tile(st, kind, ring, uid, upw):
         read_frag(f)
     if wide:
         e(f"v_mov_b32 {v(T[1])}, 0")
+    if raw8:
+        e(f"v_and_b32 {v(T[6])}, 15, {v(ROWI)}")
+        e(f"v_lshlrev_b32 {v(T[6])}, 4, {v(T[6])}")
+        e(f"v_xor_b32 {v(T[6])}, {v(KOFF0)}, {v(T[6])}")   # 16 (lane % 16): load block 0 swizzles by the row, lane / 16
     # ---- phase A: S0 = K(block 0) Q^T | the next tile's loads ----
     for sl in range(KS):
         wait_pair(sl)
         mfma(v(SC0, 16), v(FR[sl % NFR], 4), v(Q[sl], 4), v(SC0, 16) if sl else "0")
         read_frag(sl + PD)
-        if sl < 2 * upw and not noload:
+        if sl < 2 * upw and raw8:
+            load_piece8(sl // 2, sl % 2)
+        elif sl < 2 * upw and not noload:
             load_piece(sl // 2, sl % 2)
     # ---- phase B: S1 = K(block 1) Q^T | slot ids of the tile after next, probabilities of block 0 ----
     e(f"v_mov_b32 {v(LSUM)}, 0")
@@ -313,20 +389,25 @@ def tile(st, kind, ring, uid, upw):
     assert not st.lds, st.lds
     # ---- this wave's part of the next tile has landed, and so has everyone else's ----
     e("s_waitcnt vmcnt(0)")
-    e("s_barrier")
+    if raw8:
+        decode8()
+    if kind not in st.no_barrier:
+        e("s_barrier")
     e(f"s_add_u32 {s(P0)}, {s(P0)}, 64")
     e(f"s_mov_b32 {s(RING)}, {ring ^ 1}")
     e(f"s_cmp_lt_i32 {s(P0)}, {s(PEND)}")
 
 
-KINDS = ["pool", "ext", "pool64", "plain", "masked"]   # mode operand = 1 + index
+KINDS = ["pool", "ext", "pool64", "plain", "masked", "pool8"]   # mode operand = 1 + index
 MODE = 50                                                # scalar register of the mode operand
 
 
-def gen(upw):
+def gen(upw, kinds=KINDS, no_barrier=()):
     """All kinds of run in one statement (one set of register constraints for the compiler to meet), chosen by the mode
-    operand.  Labels of a kind carry its name; Lover1 / Lover2 / Ldone are common."""
+    operand.  Labels of a kind carry its name; Lover1 / Lover2 / Ldone are common.  A tile of a kind in no_barrier ends
+    once this wave's loads have landed, and the caller brings the workgroup together (it has work to do on what landed)."""
     st = Stream()
+    st.no_barrier = no_barrier
     e = st.emit
     end = "%="
     # ---- entry: LDS read addresses in ring slot 0 (the operands give those of the slot that holds the tile at P0) ----
@@ -341,12 +422,18 @@ def gen(upw):
         e(f"v_xor_b32 {v(VRD[2 * b + 1])}, 32, {v(VRD[2 * b])}")
         e(f"v_add_u32 {v(VRD[2 * b + 1])}, 0x800, {v(VRD[2 * b + 1])}")
     e(f"s_mov_b32 {s(STATUS)}, 0")
-    for i, kind in enumerate(KINDS[1:], start=2):
-        e(f"s_cmp_eq_u32 {s(MODE)}, {i}")
+    for kind in kinds[1:]:
+        e(f"s_cmp_eq_u32 {s(MODE)}, {KINDS.index(kind) + 1}")
         e(f"s_cbranch_scc1 Lkind_{kind}{end}")
-    for kind in KINDS:
+    for kind in kinds:
         uid = f"_{kind}{end}"
         e(f"Lkind{uid}:")
+        if kind == "pool8":
+            # lanes that fetch the codes of a row (the first eight of every sixteen); the lane that fetches its exponents
+            e(f"s_mov_b32 {s(MASKS[0])}, 0x00ff00ff")
+            e(f"s_mov_b32 {s(MASKS[0] + 1)}, 0x00ff00ff")
+            e(f"s_mov_b32 {s(MASKS[1])}, 0x00010001")
+            e(f"s_mov_b32 {s(MASKS[1] + 1)}, 0x00010001")
         e(f"s_cmp_eq_u32 {s(RING)}, 0")
         e(f"s_cbranch_scc0 Lring1{uid}")
         # the loop body is written out for both ring slots: every LDS offset is an immediate
@@ -370,11 +457,12 @@ def gen(upw):
     return st.lines
 
 
-def emit(name, upw):
-    lines = gen(upw)
+def emit(name, upw, kinds=KINDS[:5], no_barrier=()):
+    lines = gen(upw, kinds, no_barrier)
+    kv8 = "pool8" in kinds
     body = "\n".join(f'        "{ln}\\n\\t"' for ln in lines)
     clob = ([f"v{i}" for i in range(FIRST_V, 53) if i != LIM0] + [f"v{i}" for i in range(64, 160)] + [f"s{i}" for i in S_T] +
-            [f"s{i}" for i in range(MASKS[0], MASKS[1] + 2)] + ["vcc", "scc", "memory"])
+            [f"s{i}" for i in range(MASKS[0], MASKS[1] + 2)] + ["vcc", "scc", "memory"] + (["exec"] if kv8 else []))
     clobbers = ", ".join(f'"{c}"' for c in clob)
     sln = ", ".join(f'"+{{v{SLN[u]}}}"(sl_next[{u}])' for u in range(upw))
     return f'''
@@ -383,7 +471,7 @@ __device__ __forceinline__ void {name}(int mode, f32x16& acc0, f32x16& acc1, f32
                                        const bf16x32& q_hi, float& l_run, float neg_m, int32_t (&sl_next)[{upw}],
                                        unsigned k_rd0, unsigned v_rd0, unsigned ld_koff0, unsigned ld_voff0, int row_in_tile,
                                        int& p0, int& ring, int& status, int p_end, const void* slots, const void* base_k,
-                                       const void* base_v, int lim, const i32x8& c, const i32x4& c2) {{
+                                       const void* base_v, int lim, const i32x8& c, const i32x4& c2{", unsigned exp_stage" if kv8 else ""}) {{
     asm volatile(
 {body}
         : "+{{v[192:207]}}"(acc0), "+{{v[208:223]}}"(acc1), "+{{v[224:239]}}"(acc2), "+{{v[240:255]}}"(acc3), "+{{v59}}"(l_run),
@@ -391,7 +479,7 @@ __device__ __forceinline__ void {name}(int mode, f32x16& acc0, f32x16& acc1, f32
           "+{{s41}}"(ring), "={{s42}}"(status), "+{{v{LIM0}}}"(lim)
         : "{{v[160:175]}}"(q_lo), "{{v[176:191]}}"(q_hi), "{{v58}}"(neg_m), "{{v54}}"(k_rd0), "{{v53}}"(v_rd0), "{{v57}}"(ld_koff0),
           "{{v56}}"(ld_voff0), "{{v55}}"(row_in_tile), "{{s43}}"(p_end), "{{s[44:45]}}"(slots), "{{s[46:47]}}"(base_k),
-          "{{s[48:49]}}"(base_v), "{{s[52:59]}}"(c), "{{s[60:63]}}"(c2), "{{s{MODE}}}"(mode)
+          "{{s[48:49]}}"(base_v), "{{s[52:59]}}"(c), "{{s[60:63]}}"(c2), "{{s{MODE}}}"(mode){f', "{{s{EXST}}}"(exp_stage)' if kv8 else ""}
         : {clobbers});
 }}
 '''
@@ -406,6 +494,13 @@ HEADER = '''// GENERATED by gen_fast_run.py - do not edit.  Tiles of extend_bf16
 //   3  as 1 for pools of 4 GB and more (pool rows addressed in 64 bits; base_k / base_v 256-byte aligned)
 //   4  one tile, arithmetic only (the caller has issued the next tile's loads)
 //   5  as 4 with keys hidden from rows: lim = how many keys of the tile, counted from the lane's first, its row sees
+// (_kv8, for the fp8 pool: modes 2, 4, 5 and
+//   6  a run of tiles, the next tile of each wholly in the prefix: its rows arrive as codes and row exponents and are
+//      turned into bfloat16 in LDS once they have landed; base_k / base_v then point at the codes, c[2] is the page
+//      stride of the codes in bytes, c[5] the page stride of the row exponents, c[6] the distance from a K row's
+//      exponent to its V row's, c2[0..1] the address of the KV head's row exponents, exp_stage the LDS address of the
+//      wave's staging area for them;
+// a single tile (4, 5) ends without the workgroup barrier - the caller decodes the pool rows that have landed first.)
 //
 // Operands: acc0..3 output accumulators (head-dim blocks 0..3); q_lo / q_hi the eight query fragments (k-slices 0..3,
 // 4..7); l_run this lane's share of the row sum; neg_m minus the running maximum; sl_next the pool
@@ -423,7 +518,8 @@ HEADER = '''// GENERATED by gen_fast_run.py - do not edit.  Tiles of extend_bf16
 
 def main():
     here = os.path.dirname(os.path.abspath(__file__))
-    text = HEADER + emit("fast_tiles_d128", 4) + emit("fast_tiles_d128_w8", 2)
+    text = (HEADER + emit("fast_tiles_d128", 4) + emit("fast_tiles_d128_w8", 2) +
+            emit("fast_tiles_d128_kv8", 4, ["pool8", "ext", "plain", "masked"], no_barrier=("plain", "masked")))
     path = os.path.join(here, "fast_run_d128.inc")
     old = open(path).read() if os.path.exists(path) else None
     if old != text:

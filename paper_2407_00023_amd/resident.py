@@ -13,7 +13,7 @@ from . import workloads as W
 def to_torch(a: np.ndarray, dtype: str, device) -> torch.Tensor:
     """Host array of the generators (bf16 as uint16 bit patterns) -> device tensor of the same bits."""
     if a.dtype == np.uint16:
-        assert dtype == "bf16"
+        assert dtype in ("bf16", "bf16_kv8")
         return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
     return torch.from_numpy(a).to(device)
 
@@ -27,9 +27,10 @@ class ResidentWorkload:
             for i in range(wl.n_cached):
                 self.tree.insert(*wl.cached_seq(i))
         self.tree.upload()
-        nbytes = pa.kv_pool_bytes(wl.num_slots, wl.Hkv, wl.D, self.tdtype, wl.page_size)
+        self.kv8 = wl.dtype == "bf16_kv8"   # bf16 tensors, the KV pool in its fp8 form
+        nbytes = pa.kv_pool_bytes(wl.num_slots, wl.Hkv, wl.D, self.tdtype, wl.page_size, self.kv8)
         self.pool = torch.zeros(nbytes, dtype=torch.uint8, device=device)
-        self.kw = dict(page_size=wl.page_size, num_slots=wl.num_slots)
+        self.kw = dict(page_size=wl.page_size, num_slots=wl.num_slots, kv8=self.kv8)
         if len(wl.pool_slots):
             pa.append_kv(self.pool, torch.from_numpy(wl.pool_slots).to(device), to_torch(wl.pool_k, wl.dtype, device),
                          to_torch(wl.pool_v, wl.dtype, device), **self.kw)
