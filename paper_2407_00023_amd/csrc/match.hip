@@ -22,11 +22,11 @@ __device__ __forceinline__ int32_t find_child(const DeviceTree& t, int32_t node,
     for (uint32_t probed = 0; probed <= t.ht_mask; probed += 64) {
         const uint32_t idx = (h + lane) & t.ht_mask;
         const unsigned long long k = t.ht_key[idx];
+        const int32_t val = t.ht_val[idx];  // (fetched with the key, not after it: one round trip to memory, not two)
         const unsigned long long hit = __ballot(k == key);
         if (hit) {
             const int src = __ffsll(static_cast<long long>(hit)) - 1;
-            const int32_t v = t.ht_val[(h + src) & t.ht_mask];
-            return v;
+            return __shfl(val, src);
         }
         if (__ballot(k == kEmptyKey)) return -1;
         h = (h + 64) & t.ht_mask;
@@ -44,17 +44,25 @@ __device__ __forceinline__ int32_t find_child(const DeviceTree& t, int32_t node,
 // position on.  The workgroup forms the prefix hash of the prompt at every position of the window (a scan
 // seeded with the stored hash of the path that ends at the current node) and looks every (hash, position)
 // up: a hit NOMINATES a node whose edge would start there.  The edges of all nominated nodes are compared
-// with the prompt in parallel.  Then the nodes that really lie on the path are marked by pointer doubling
-// over the links "edge fully matched, and the node nominated at its end names this node as its parent",
-// starting from position 0, which holds the child found exactly.  The slots of all marked nodes are copied
-// in parallel.  Whatever ends the chain (a mismatch, no nomination, a very long edge, the window's end), the
-// loop head takes over from the last confirmed position with an exact child lookup, so the result never
-// depends on the hash being free of collisions: a collision can only cost time.
+// with the prompt in parallel.  Then the nodes that really lie on the path are marked: hash collisions apart,
+// the nominated nodes are the path's nodes in order, so each must be linked to the one nominated before it
+// ("that one matched its whole edge, ends where this one starts, and is this one's parent"), starting from
+// position 0, which holds the child found exactly; the path's nodes are those before the first broken link (a
+// prefix maximum and a minimum over the workgroup, no walk along the chain).  The slots of all marked nodes are
+// copied in parallel.  Whatever ends the chain (a mismatch, no nomination, a very long edge, a collision, the
+// window's end), the loop head takes over from the last confirmed position with an exact child lookup, so the
+// result never depends on the hash being free of collisions: a collision can only cost time.
+// What a window costs (measured, 4,096 positions, a tree of 4,096 sequences): 3.6 us for the table probes (one
+// 16-byte entry per position from a table far larger than any cache: the compute unit's memory pipeline takes
+// about one such line per cycle, then a second trip for the hits), 2 us for the edge comparisons, 2 us for the
+// marking, 1 us each for the scan, the child lookup and the slot copy.
 // ---------------------------------------------------------------------------------------------------
 constexpr int kWin = 1024;        // threads per workgroup
-constexpr int kPos = 2;           // prompt positions per thread and window (consecutive ones)
-constexpr int kWinP = kWin * kPos;  // prompt positions per window
-constexpr int kGroupEdge = 64;    // edges with at most this many tokens to compare are compared by 16 lanes, in one round
+// kPos = prompt positions per thread and window (consecutive ones), kWinP = kWin * kPos positions per window: 2 / 2048
+// for large batches (two workgroups fit a compute unit), 4 / 4096 for small ones (a window costs a fixed number of
+// dependent round trips to memory, so a long prompt is done in fewer of them; 110 KB of LDS, one workgroup per unit)
+constexpr int kQuadEdge = 16;     // edges with at most this many tokens to compare are compared by 4 lanes, in one round
+constexpr int kGroupEdge = 64;    // ... with at most this many by 16 lanes, in one round
 constexpr int kWaveEdge = 1024;   // ... by one wave, 256 tokens per round; longer ones by the whole workgroup
 constexpr int kDirectEdge = 256;  // a next edge at least this long is compared directly, without opening a window
 constexpr int kWideUnroll = 4;    // tokens per thread and round of a wave- or workgroup-wide comparison
@@ -67,24 +75,23 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+template <int kPos>
 __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, const int32_t* __restrict__ tokens,
                                                                  const int32_t* __restrict__ offsets,
                                                                  int32_t* __restrict__ prefix_len,
                                                                  int32_t* __restrict__ slot_idx) {
+    constexpr int kWinP = kWin * kPos;
     constexpr int kWaves = kWin / 64;
     __shared__ unsigned long long s_wtot[kWaves];
     // per window position: {candidate node or -1, its parent, its edge length, tokens of the edge that match the
     // prompt (-2 = not compared yet: very long edge)}
     __shared__ int4 s_rec[kWinP];
     __shared__ int32_t s_es[kWinP];      // index of the candidate's first edge token
-    __shared__ int16_t s_list[kWinP];    // window positions of candidates compared by 16 lanes
+    __shared__ int16_t s_list0[kWinP];   // window positions of candidates compared by 4 lanes
+    __shared__ int16_t s_list[kWinP];    // ... by 16 lanes
     __shared__ int16_t s_list2[kWinP];   // ... by one wave
-    __shared__ int s_live[3];             // pointer doubling: does any position still reach another (round mod 3: the
-                                          // flag of a round is cleared two barriers after its last reader)
-    __shared__ int16_t s_jump[kWinP];    // position reached from a window position after 2^round valid hops, -1 = none
-    __shared__ uint8_t s_mark[kWinP];    // 1 = the position starts a node on the prompt's path
-    __shared__ int32_t s_wmax[kWaves];
-    __shared__ int32_t s_count, s_count2;
+    __shared__ int32_t s_wmax[kWaves], s_brk[kWaves], s_last[kWaves];
+    __shared__ int32_t s_count0, s_count, s_count2;
     __shared__ int32_t s_red[2][kWaves];
     const int r = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -111,6 +118,7 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
     while (!done && pos < n) {
         // The next node, found exactly (child table keyed by parent and first token).  A long edge is compared
         // right away by the whole workgroup; a short one opens a window.
+        const unsigned long long h = t.node_endhash[cur];  // hash of prompt[0 .. pos) (asked for ahead of its use below)
         const int32_t child = find_child(t, cur, prompt[pos]);
         if (child < 0) break;
         const int32_t c_es = t.node_start[child];
@@ -152,7 +160,6 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
             cur = child;
             continue;
         }
-        const unsigned long long h = t.node_endhash[cur];  // hash of prompt[0 .. pos)
         const int32_t w0 = pos;
         const int32_t rel0 = tid * kPos;  // this thread's first position in the window; its positions are rel0 + i
         // ---- A. prefix hashes of the window: inclusive scan of x -> x * B + (token + 1).  A thread folds its own
@@ -175,7 +182,7 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
             if (lane >= (1 << k)) c = left * bp2[k] + c;
         }
         if (lane == 63) s_wtot[wave] = c;
-        if (tid == 0) { s_count = 0; s_count2 = 0; }
+        if (tid == 0) { s_count0 = 0; s_count = 0; s_count2 = 0; }
         unsigned long long excl = __shfl_up(c, 1);  // hash of the wave's positions before this thread's
         if (lane == 0) excl = 0ull;
         lds_barrier();
@@ -184,17 +191,30 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
         const unsigned long long upto = before * bpow_lane + excl;  // hash of prompt[0 .. w0 + rel0)
         // ---- B. candidates: nodes whose edge starts at p after exactly this prefix (by hash) ----
         {
+            // (the first probe of every position of the thread goes out before any is looked at, both halves of the
+            // entry: one round trip to memory for all of them; only a collision in the table costs another)
+            unsigned long long hps[kPos];
+            uint32_t ats[kPos];
+            uint4 lo0[kPos];
             unsigned long long bi = 1ull;
 #pragma unroll
             for (int i = 0; i < kPos; ++i) {
                 bi *= kPathHashBase;
+                const int32_t p = w0 + rel0 + i;
+                hps[i] = upto * bi + loc[i];  // hash of prompt[0 .. p]
+                ats[i] = path_slot(hps[i], p) & t.ph_mask;
+                lo0[i] = make_uint4(0, 0, 0, 0xFFFFFFFFu);
+                if (p < n) lo0[i] = reinterpret_cast<const uint4*>(t.ph_entry + ats[i])[0];  // hash, depth, node
+            }
+#pragma unroll
+            for (int i = 0; i < kPos; ++i) {
                 const int32_t rel = rel0 + i, p = w0 + rel;
-                const unsigned long long hp = upto * bi + loc[i];  // hash of prompt[0 .. p]
+                const unsigned long long hp = hps[i];
                 int4 rec = make_int4(-1, -1, 0, 0);
                 if (p < n) {
-                    uint32_t at = path_slot(hp, p) & t.ph_mask;
+                    uint32_t at = ats[i];
+                    uint4 lo = lo0[i];
                     for (uint32_t probes = 0; probes <= t.ph_mask; ++probes) {
-                        const uint4 lo = reinterpret_cast<const uint4*>(t.ph_entry + at)[0];  // hash, depth, node
                         const int32_t nd = static_cast<int32_t>(lo.w);
                         if (nd < 0) break;
                         const unsigned long long eh = (static_cast<unsigned long long>(lo.y) << 32) | lo.x;
@@ -205,6 +225,7 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
                             break;
                         }
                         at = (at + 1) & t.ph_mask;
+                        lo = reinterpret_cast<const uint4*>(t.ph_entry + at)[0];
                     }
                 }
                 if (rel == 0) {  // position 0 holds the node found exactly above, whatever the probe said
@@ -214,7 +235,8 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
                 s_rec[rel] = rec;
                 if (rec.x >= 0) {
                     const int32_t lim = min(rec.z, n - p);
-                    if (lim <= kGroupEdge) s_list[atomicAdd(&s_count, 1)] = static_cast<int16_t>(rel);
+                    if (lim <= kQuadEdge) s_list0[atomicAdd(&s_count0, 1)] = static_cast<int16_t>(rel);
+                    else if (lim <= kGroupEdge) s_list[atomicAdd(&s_count, 1)] = static_cast<int16_t>(rel);
                     else if (lim <= kWaveEdge) s_list2[atomicAdd(&s_count2, 1)] = static_cast<int16_t>(rel);
                 }
             }
@@ -222,7 +244,26 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
         lds_barrier();
         // ---- C. compare the candidates' edges with the prompt, all candidates at once ----
         {
-            const int n1 = s_count, n2 = s_count2;
+            const int n0 = s_count0, n1 = s_count, n2 = s_count2;
+            for (int j = tid >> 2; j < n0; j += kWin / 4) {  // 4 lanes per candidate, one round of <= 16 tokens
+                const int rel = s_list0[j], sub4 = tid & 3;
+                const int32_t es = s_es[rel];
+                const int32_t lim = min(s_rec[rel].z, n - (w0 + rel));
+                bool bad[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int32_t k = sub4 + 4 * u, kk = min(k, lim - 1);
+                    const int32_t a = t.edge_tok[es + kk], b = prompt[w0 + rel + kk];
+                    bad[u] = (k < lim) & (a != b);
+                }
+                int32_t m = lim;
+#pragma unroll
+                for (int u = 3; u >= 0; --u) {
+                    const unsigned mine = static_cast<unsigned>(__ballot(bad[u]) >> (lane & 60)) & 0xFu;
+                    if (mine) m = 4 * u + __ffs(mine) - 1;
+                }
+                if (sub4 == 0) s_rec[rel].w = m;
+            }
             const int sub = tid & 15;
             for (int j = tid >> 4; j < n1; j += kWin / 16) {  // 16 lanes per candidate, one round of <= 64 tokens
                 const int rel = s_list[j];
@@ -268,74 +309,67 @@ __global__ __launch_bounds__(kWin) void match_prefixes_pos_kernel(DeviceTree t, 
             }
         }
         lds_barrier();
-        // ---- D. which candidates lie on the prompt's path: follow "edge fully matched, and the candidate at its
-        // end is a child of this node" links from position 0, by pointer doubling ----
-        {
-#pragma unroll
-            for (int i = 0; i < kPos; ++i) {
-                const int rel = rel0 + i;
-                const int4 rec = s_rec[rel];
-                int32_t link = -1;
-                if (rec.x >= 0 && rec.w == rec.z && rel + rec.z < kWinP) {
-                    const int4 nx = s_rec[rel + rec.z];
-                    if (nx.x >= 0 && nx.y == rec.x) link = rel + rec.z;
-                }
-                s_jump[rel] = static_cast<int16_t>(link);
-                s_mark[rel] = rel == 0 ? 1 : 0;
-            }
-            if (threadIdx.x == 0) s_live[0] = 0;
-            lds_barrier();
-#pragma unroll 1
-            for (int round = 0; round < 11; ++round) {  // 2^11 = kWinP hops at most
-                int32_t jj[kPos];
-                bool live = false;  // some position of this thread still reaches another one
-#pragma unroll
-                for (int i = 0; i < kPos; ++i) {
-                    const int rel = rel0 + i;
-                    const int32_t j = s_jump[rel];
-                    if (j >= 0 && s_mark[rel]) s_mark[j] = 1;
-                    jj[i] = j >= 0 ? s_jump[j] : -1;
-                    live |= jj[i] >= 0;
-                }
-                if (threadIdx.x == 0) s_live[(round + 1) % 3] = 0;
-                lds_barrier();
-#pragma unroll
-                for (int i = 0; i < kPos; ++i) s_jump[rel0 + i] = static_cast<int16_t>(jj[i]);
-                if (live) s_live[round % 3] = 1;
-                lds_barrier();
-                if (!s_live[round % 3]) break;  // every chain has run off its end: nothing is left to mark
-            }
-        }
-        // ---- E. slots of the matched positions: position i belongs to the last path node starting at or before it ----
-        int32_t covs[kPos];
+        // ---- D. which candidates lie on the prompt's path.  A candidate's whole path hashes like the prompt up to its
+        // position, so (hash collisions apart) the candidates ARE the path's nodes, in order, and each is the child
+        // of the one before it.  Exactly that is checked: a candidate is linked if the candidate before it matched its
+        // whole edge, ends where this one starts and is its parent.  The path's nodes in this window are the
+        // candidates before the first one that is not linked; whatever broke the chain (the end of the match, a very
+        // long edge left uncompared, a collision) is the loop head's business. ----
+        int32_t candm[kPos];  // the last candidate at or before each of the thread's positions, among its own
+        int4 recs[kPos];
         {
             int32_t run = -1;
 #pragma unroll
             for (int i = 0; i < kPos; ++i) {
-                run = max(run, s_mark[rel0 + i] ? rel0 + i : -1);
-                covs[i] = run;
+                recs[i] = s_rec[rel0 + i];
+                run = max(run, recs[i].x >= 0 ? rel0 + i : -1);
+                candm[i] = run;
             }
         }
-        int32_t cov = covs[kPos - 1];
+        int32_t cm = candm[kPos - 1];
 #pragma unroll
         for (int k = 0; k < 6; ++k) {
-            const int32_t left = __shfl_up(cov, 1u << k);
-            if (lane >= (1 << k)) cov = max(cov, left);
+            const int32_t left = __shfl_up(cm, 1u << k);
+            if (lane >= (1 << k)) cm = max(cm, left);
         }
-        if (lane == 63) s_wmax[wave] = cov;
-        int32_t cov_before = __shfl_up(cov, 1);  // last path node before this thread's positions, in this wave
-        if (lane == 0) cov_before = -1;
+        if (lane == 63) s_wmax[wave] = cm;
+        int32_t cand_before = __shfl_up(cm, 1);  // last candidate before this thread's positions
+        if (lane == 0) cand_before = -1;
+        lds_barrier();
+        for (int v = 0; v < wave; ++v) cand_before = max(cand_before, s_wmax[v]);
+        int32_t brk = INT32_MAX;  // first candidate of this thread that is not linked
+#pragma unroll
+        for (int i = kPos - 1; i >= 0; --i) {
+            const int rel = rel0 + i;
+            if (recs[i].x >= 0 && rel != 0) {
+                const int32_t pc = i > 0 ? max(cand_before, candm[i - 1]) : cand_before;  // (position 0 is a candidate: pc >= 0)
+                const int4 pr = s_rec[pc];
+                if (!(pr.w == pr.z && pc + pr.z == rel && recs[i].y == pr.x)) brk = rel;
+            }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) brk = min(brk, __shfl_xor(brk, off));
+        if (lane == 0) s_brk[wave] = brk;
+        lds_barrier();
+        int32_t first_break = INT32_MAX;
+#pragma unroll
+        for (int v = 0; v < kWaves; ++v) first_break = min(first_break, s_brk[v]);
+        int32_t lastm = -1;  // last path node among the thread's positions
+#pragma unroll
+        for (int i = 0; i < kPos; ++i)
+            if (recs[i].x >= 0 && rel0 + i < first_break) lastm = rel0 + i;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) lastm = max(lastm, __shfl_xor(lastm, off));
+        if (lane == 0) s_last[wave] = lastm;
         lds_barrier();
         int32_t z = -1;  // last path node of the window
-        for (int v = 0; v < kWaves; ++v) {
-            const int32_t x = s_wmax[v];
-            if (v < wave) cov_before = max(cov_before, x);
-            z = max(z, x);
-        }
+#pragma unroll
+        for (int v = 0; v < kWaves; ++v) z = max(z, s_last[v]);
+        // ---- E. slots of the matched positions: position i belongs to the last path node starting at or before it ----
 #pragma unroll
         for (int i = 0; i < kPos; ++i) {
             const int rel = rel0 + i;
-            const int32_t cv = max(cov_before, covs[i]);
+            const int32_t cv = rel < first_break ? max(cand_before, candm[i]) : z;
             if (cv >= 0) {
                 const int4 cr = s_rec[cv];
                 if (cr.w >= 0 && rel < cv + cr.w) out_slots[w0 + rel] = t.edge_slot[s_es[cv] + (rel - cv)];
@@ -378,8 +412,13 @@ extern "C" int pa_match_prefixes(const pa_tree* tree, const int32_t* tokens, con
     // tokens / slot_idx may be NULL only if every prompt is empty (offsets[B] == 0), which the host cannot see
     {
         pa::ProfScope prof(pa::kProfMatch, static_cast<hipStream_t>(stream));
-        hipLaunchKernelGGL(pa::match_prefixes_pos_kernel, dim3(B), dim3(pa::kWin), 0, static_cast<hipStream_t>(stream),
-                           *view, tokens, offsets, prefix_len, slot_idx);
+        // (windows of 4,096 positions while every workgroup has a compute unit of its own anyway)
+        if (B <= 256)
+            hipLaunchKernelGGL(pa::match_prefixes_pos_kernel<4>, dim3(B), dim3(pa::kWin), 0, static_cast<hipStream_t>(stream),
+                               *view, tokens, offsets, prefix_len, slot_idx);
+        else
+            hipLaunchKernelGGL(pa::match_prefixes_pos_kernel<2>, dim3(B), dim3(pa::kWin), 0, static_cast<hipStream_t>(stream),
+                               *view, tokens, offsets, prefix_len, slot_idx);
     }
     PA_HIP(hipGetLastError());
     return PA_OK;

@@ -90,11 +90,13 @@ def test_match_random_small_vocab(pa, gpu_device, vocab, seed):
         np.testing.assert_array_equal(si[off[r]:off[r] + pl_ref[r]], si_ref[off[r]:off[r] + pl_ref[r]])
 
 
+@pytest.mark.parametrize("copies", [1, 5])
 @pytest.mark.parametrize("seed", [0, 1, 2])
-def test_match_long_paths_of_mixed_edge_lengths(pa, gpu_device, seed):
+def test_match_long_paths_of_mixed_edge_lengths(pa, gpu_device, seed, copies):
     """A trunk with branch points at spacings from 1 to thousands of tokens: the prompt's path runs through
     hundreds of nodes whose edges are short, medium and very long in turn, stops at node boundaries, inside
-    edges of every class, at the trunk's end and inside side branches; bit-exact vs the oracle trie."""
+    edges of every class, at the trunk's end and inside side branches; bit-exact vs the oracle trie.
+    copies = 5: the batch repeated to 320 prompts (the matcher takes shorter windows for batches above 256)."""
     import oracle
     rng = np.random.default_rng(100 + seed)
     vocab = 50000
@@ -127,6 +129,7 @@ def test_match_long_paths_of_mixed_edge_lengths(pa, gpu_device, seed):
         cut = min(cut, len(base))
         tail = rng.integers(0, vocab, int(rng.integers(0, 30))).astype(np.int32)
         prompts.append(np.concatenate([base[:cut], tail]))
+    prompts = prompts * copies
     toks = np.concatenate(prompts).astype(np.int32)
     off = np.zeros(len(prompts) + 1, np.int32)
     off[1:] = np.cumsum([len(p) for p in prompts])
