@@ -35,8 +35,9 @@ FP8_POOL_CONFIGS = ["long_doc_qa"]   # measured once more with the KV pool held 
 # run cannot share a process with the timed one): FETCH_SIZE x the factor that the same counter shows for append_kv, a
 # plain copy of known size, + WRITE_SIZE x its factor (KiB).  The runs are summarised in
 # profiles/extend_attention_<workload>.md, which is the source named beside each figure.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"tool_use": 198_302_353, "agent_tree": 2_422_883_467, "long_doc_qa": 846_093_494,
-                          "video_qa": 314_095_251, "programming": 259_820_888, "decode": 348_881_083}
+MEASURED_TRAFFIC_BYTES = {"tool_use": 199_480_913, "agent_tree": 2_460_428_241, "long_doc_qa": 905_065_992,
+                          "video_qa": 347_008_741, "programming": 267_142_670, "decode": 353_390_959,
+                          "long_doc_qa_fp8_pool": 483_164_245}
 
 
 def algorithmic_work(wl, prefix_len):
@@ -322,7 +323,8 @@ def measure(name, steps, warmup, args, with_extras, kv_pool="bf16"):
                         "frac": tfs / peak_f}
         traffic = MEASURED_TRAFFIC_BYTES.get(name + ("_fp8_pool" if wl.dtype == "bf16_kv8" else ""))
         roofline.update({"traffic": traffic,
-                         "traffic_source": f"profiles/extend_attention_{name}.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, runs of their own)" if traffic else None,
+                         "traffic_source": (f"profiles/extend_attention_{name}{'_fp8_pool' if wl.dtype == 'bf16_kv8' else ''}.md "
+                                            "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, runs of their own)") if traffic else None,
                          "kernel": main_k, "avg_kernel_us": kern[main_k]["avg_us"], "algorithmic_bytes": nbytes,
                          "algorithmic_flops": flops, "hbm_frac": gbs / HBM_PEAK_GBS, "compute_frac": tfs / peak_f})
         if hdr is not None:
