@@ -260,7 +260,7 @@ size_t pa_kv_pool_bytes(int64_t num_slots, int Hkv, int D, int dtype, int page_s
  * requests, T extend tokens in total and prefix_len[r] + ext_len[r] <= max_kv_len.
  * It holds the work list of the launch and the partial results of row tiles whose key range is
  * split over several workgroups; with bf16 at serving sizes the bound on the latter dominates
- * (about 200 MB for 8 KV heads of 128: 2 x 3 parts per workgroup slot, each 128 rows of fp32).
+ * (about 135 MB for 8 KV heads of 128: 2 x 2 parts per workgroup slot, each 128 rows of fp32).
  * Returns 0 for invalid arguments. */
 size_t pa_extend_workspace_bytes(int B, int64_t T, int64_t max_kv_len, int Hq, int Hkv, int D, int dtype);
 

@@ -60,7 +60,9 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr int kKT = 64;                  // key tokens per tile
 constexpr int kStages = 2;               // LDS ring: one tile being read, one being filled
 constexpr int kWgSlots = 512;            // workgroups resident at once: two on each of the 256 compute units
-constexpr int kRounds = 3;               // the plan aims at about this many work items per workgroup slot
+constexpr int kRounds = 2;               // the plan aims at about this many work items per workgroup slot (measured: with 3
+                                         // long_doc_qa's kernel took 6 % longer - every item pays its start-up, its partial
+                                         // results and their merge - with 1.5 its last round ran thin; the rest did not care)
 constexpr int kRoundsStatic = 1;         // ... with the library's own scratch buffer as workspace (fewer partial results)
 constexpr int kMinChunkTiles = 8;        // never split below this many key tiles (512 keys) per part
 constexpr int kItemOverhead = 4;         // fixed cost of a work item, in key tiles (its prologue and epilogue)
