@@ -64,7 +64,8 @@ constexpr int kRounds = 2;               // the plan aims at about this many wor
                                          // long_doc_qa's kernel took 6 % longer - every item pays its start-up, its partial
                                          // results and their merge - with 1.5 its last round ran thin; the rest did not care)
 constexpr int kRoundsStatic = 1;         // ... with the library's own scratch buffer as workspace (fewer partial results)
-constexpr int kMinChunkTiles = 8;        // never split below this many key tiles (512 keys) per part
+constexpr int kMinChunkTiles = 16;       // never split below this many key tiles (1,024 keys) per part (with 512 decode's
+                                         // step took 3 % longer; nothing else splits that fine)
 constexpr int kItemOverhead = 4;         // fixed cost of a work item, in key tiles (its prologue and epilogue)
 constexpr int kMaxParts = 64;            // parts of one row tile at most
 constexpr int kSortMax = 1024;           // up to this many requests are ordered (and their lengths staged in LDS)

@@ -1,25 +1,32 @@
 #!/usr/bin/env python3
-"""Writes fast_run_d128.inc: the runs of steady-state tiles of the bf16 extend-attention kernel as gfx950 assembly.
+"""Writes fast_run_d128.inc: the tiles of the bf16 extend-attention kernel as gfx950 assembly.
 
-One inline-assembly statement holds the whole loop over a run of tiles that need no mask, for head dimension 128,
-32 packed query rows per wave, with every register chosen here.  (Left to the compiler's register allocator the 64
-output accumulators are split around the phases of a tile and copied every tile, and spill reloads inside the loop
-serialise the global -> LDS loads behind them.)  Two variants: the NEXT tile lies wholly in the prefix (its rows come
-from the pool through slot ids) or wholly in the extend tokens.
+One inline-assembly statement per kernel instance holds every kind of tile, for head dimension 128 and 32 packed query
+rows per wave, with every register chosen here.  (Left to the compiler's register allocator the 64 output accumulators
+are split around the phases of a tile and copied every tile, and spill reloads inside the loop serialise the
+global -> LDS loads behind them; and several statements, each with its fixed registers, made the compiler spill
+everything it held around them.)  A mode operand picks the kind: runs of consecutive unmasked tiles that issue the
+next tile's loads themselves (its rows in the pool through slot ids, 32-bit or 64-bit addresses, as codes of the fp8
+pool, or in the extend tokens), and single tiles, plain or with keys hidden from rows, whose loads the caller issues.
 
 A tile is 32 slots of one MFMA each; what follows an MFMA in the stream runs in its shadow:
-    phase A  S0 = K(block 0) Q^T     | addresses + issue of the next tile's global -> LDS loads (8 pieces)
+    phase A  S0 = K(block 0) Q^T     | addresses + issue of the next tile's global -> LDS loads
     phase B  S1 = K(block 1) Q^T     | probabilities 2^(c S0 - m), their sum; slot ids of the tile after next
     (leave with status 1 if a lane's sum exceeds the limit: block 0 outgrew the running maximum m)
     phase C  O += V(block 0) P0      | probabilities 2^(c S1 - m), their sum
     (leave with status 2)
     phase D  O += V(block 1) P1      | -
-    wait for this wave's loads, workgroup barrier, next tile
+    wait for this wave's loads (fp8 pool: turn the rows that landed into bfloat16), workgroup barrier, next tile
 
-Wait states the hardware does not interlock are written out: an s_nop block between the last MFMA that writes a score
-block and the first ALU read of it, one instruction between a transcendental and a use of its result, one s_nop after
-a write of M0.  LDS reads are awaited by counting them (they return in order).  The loop is written out for both ring slots,
-so that every LDS offset is an immediate and no address register changes between tiles.
+Every instruction costs its wave an issue slot of about four cycles whatever unit executes it, so the schedule is
+written for few instructions: row sums deferred by one piece, one address for the four slot-id loads where the tile
+after next lies wholly in the prefix, M0 written ahead of the address arithmetic that then serves as its wait state,
+LDS reads awaited two fragments at a time by counting them (they return in order).  Wait states the hardware does not
+interlock are written out, other work standing in them where there is any: the last MFMA of a score block and the
+first ALU read of it (eleven slots), a dot-product instruction and any other kind of ALU instruction that reads its
+result (three), a transcendental and a use of its result (one), a write of M0 and the load that uses it (one).  The
+loop is written out for both ring slots, so that every LDS offset is an immediate and no address register changes
+between tiles.
 
 Run:  python gen_fast_run.py  (the build does)."""
 import os

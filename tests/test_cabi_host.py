@@ -78,7 +78,7 @@ def test_size_queries_and_errors(pa):
     split = pa.extend_workspace_bytes(16, 800, 16464, 32, 8, 128, torch.bfloat16)
     tiny = pa.extend_workspace_bytes(4, 100, 128, 8, 2, 64, torch.bfloat16)
     # partial results of split row tiles dominate: bounded by the work-list rule at serving sizes, by the number of
-    # 512-key pieces at small ones
+    # 1,024-key pieces at small ones
     assert 0 < tiny < 4 << 20 and tiny < small <= 512 << 20 and 0 < split <= 512 << 20
     with pytest.raises(ValueError):
         pa.extend_workspace_bytes(1, 1, 1, 32, 5, 128, torch.bfloat16)  # Hq not a multiple of Hkv
@@ -110,3 +110,18 @@ def test_status_and_switch_calls_check_their_arguments(pa):
     assert lib.pa_extend_set_row_sharing(0) == 0 and lib.pa_extend_set_row_sharing(1) == 0
     assert pa.kv_pool_bytes(36864, 4, 128, torch.bfloat16, 12) == 36864 * 2 * 4 * 128 * 2
     assert pa.kv_pool_bytes(36864, 4, 128, torch.bfloat16, 48) == 36864 * 2 * 4 * 128 * 2
+    # the fp8 pool: one byte per element and one exponent byte per row; it goes with bf16 tensors only
+    assert pa.kv_pool_bytes(4096, 8, 128, torch.bfloat16, 16, kv8=True) == 4096 * 2 * 8 * 129
+    assert pa.kv_pool_bytes(4096, 2, 64, torch.bfloat16, 16, kv8=True) == 4096 * 2 * 2 * 65
+    with pytest.raises(TypeError):
+        pa.kv_pool_bytes(4096, 8, 128, torch.float32, 16, kv8=True)
+    lib.pa_kv_pool_bytes.restype = C.c_size_t
+    lib.pa_kv_pool_bytes.argtypes = [C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int]
+    assert lib.pa_kv_pool_bytes(4096, 8, 128, 3, 16) == 0       # no such dtype
+    assert pa.extend_workspace_bytes(16, 800, 16464, 32, 8, 128, torch.bfloat16) == lib_ws(lib, 16, 800, 16464, 32, 8, 128, 2)
+
+
+def lib_ws(lib, B, T, kv, Hq, Hkv, D, dtype):
+    lib.pa_extend_workspace_bytes.restype = C.c_size_t
+    lib.pa_extend_workspace_bytes.argtypes = [C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int]
+    return lib.pa_extend_workspace_bytes(B, T, kv, Hq, Hkv, D, dtype)
