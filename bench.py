@@ -35,9 +35,9 @@ FP8_POOL_CONFIGS = ["long_doc_qa"]   # measured once more with the KV pool held 
 # run cannot share a process with the timed one): FETCH_SIZE x the factor that the same counter shows for append_kv, a
 # plain copy of known size, + WRITE_SIZE x its factor (KiB).  The runs are summarised in
 # profiles/extend_attention_<workload>.md, which is the source named beside each figure.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"tool_use": 199_480_913, "agent_tree": 2_460_428_241, "long_doc_qa": 905_065_992,
-                          "video_qa": 347_008_741, "programming": 267_142_670, "decode": 353_390_959,
-                          "long_doc_qa_fp8_pool": 483_164_245}
+MEASURED_TRAFFIC_BYTES = {"tool_use": 199_538_842, "agent_tree": 2_459_918_968, "long_doc_qa": 449_398_084,
+                          "video_qa": 347_416_528, "programming": 230_917_030, "decode": 300_751_065,
+                          "long_doc_qa_fp8_pool": 292_844_657}
 
 
 def algorithmic_work(wl, prefix_len):
