@@ -196,3 +196,29 @@ def test_fp8_pool_full_config_extend_every_element(pa, gpu_device, name):
     err = np.abs(out_to_f64(out) - o.extend(pl_ref, si_ref)).max()
     say(f"  all {wl.T * wl.Hq} rows: max abs err {err:.3e}")
     assert err <= TOL
+
+
+def test_fp8_pool_beyond_4_gib(pa, gpu_device):
+    """Codes of 4.8 GB: rows on both sides of the 4 GiB line.  The runs of assembly tiles address the codes by 32-bit
+    offsets and stand back here; the other tiles, append and gather compute in 64 bits.  Every element, and the stored
+    rows bit-exact."""
+    say("[case] fp8 pool beyond 4 GiB")
+    wl = dataclasses.replace(W.tool_use(22, B=8, sys_len=1300, n_tools=3, tool_lo=100, tool_hi=500, ext_lo=20, ext_hi=160,
+                                        num_slots=2_359_296), dtype="bf16_kv8")
+    page_off = (wl.pool_slots.astype(np.int64) // wl.page_size) * wl.page_size * 2 * wl.Hkv * wl.D
+    assert (page_off < 2 ** 32).sum() > 100 and (page_off >= 2 ** 32).sum() > 100
+    g, o = GpuSide(wl, gpu_device), OracleSide(wl)
+    pl, si, out = g.step()
+    torch.cuda.synchronize()
+    pl_ref, si_ref = o.match()
+    assert_match_equal(wl, pl, si, pl_ref, si_ref)
+    err = np.abs(out_to_f64(out) - o.extend(pl_ref, si_ref)).max()
+    say(f"  max abs err {err:.3e}")
+    assert err <= TOL
+    o.append()
+    allslots = np.concatenate([wl.pool_slots, wl.new_slots])
+    gk, gv = pa.gather_kv(g.pool, torch.from_numpy(allslots).to(gpu_device), Hkv=wl.Hkv, D=wl.D, dtype=g.tdtype, **g.kw)
+    np.testing.assert_array_equal(gk.view(torch.int16).cpu().numpy(), o.pool_k[allslots].view(np.int16))
+    np.testing.assert_array_equal(gv.view(torch.int16).cpu().numpy(), o.pool_v[allslots].view(np.int16))
+    del g
+    torch.cuda.empty_cache()
