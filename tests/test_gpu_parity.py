@@ -90,18 +90,19 @@ def test_match_random_small_vocab(pa, gpu_device, vocab, seed):
         np.testing.assert_array_equal(si[off[r]:off[r] + pl_ref[r]], si_ref[off[r]:off[r] + pl_ref[r]])
 
 
-@pytest.mark.parametrize("copies", [1, 5])
+@pytest.mark.parametrize("copies,trunk_len", [(1, 9000), (2, 9000), (5, 9000), (1, 40000)])
 @pytest.mark.parametrize("seed", [0, 1, 2])
-def test_match_long_paths_of_mixed_edge_lengths(pa, gpu_device, seed, copies):
+def test_match_long_paths_of_mixed_edge_lengths(pa, gpu_device, seed, copies, trunk_len):
     """A trunk with branch points at spacings from 1 to thousands of tokens: the prompt's path runs through
     hundreds of nodes whose edges are short, medium and very long in turn, stops at node boundaries, inside
     edges of every class, at the trunk's end and inside side branches; bit-exact vs the oracle trie.
-    copies = 5: the batch repeated to 320 prompts (the matcher takes shorter windows for batches above 256)."""
+    copies = 1: 64 prompts, several workgroups per prompt (a trunk of 40,000 tokens reaches past the windows that get a
+    workgroup of their own); 2: 128 prompts, one workgroup each; 5: 320 prompts, shorter windows."""
     import oracle
     rng = np.random.default_rng(100 + seed)
     vocab = 50000
     spacing = []
-    while sum(spacing) < 9000:
+    while sum(spacing) < trunk_len:
         kind = rng.integers(0, 4)
         lo, hi = [(1, 9), (20, 200), (260, 1000), (1100, 3000)][kind]
         run = int(rng.integers(20, 150)) if kind == 0 else 1
