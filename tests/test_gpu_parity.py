@@ -675,6 +675,37 @@ def test_the_path_on_a_stream_of_the_callers(pa, gpu_device):
     assert torch.equal(ga.pool, gb.pool)
 
 
+def test_match_calls_in_flight_on_several_streams(pa, gpu_device):
+    """Matches of long prompts (several workgroups per prompt, which meet in buffers of the library's own) enqueued on
+    eight streams at once, many times over, each with outputs of its own: every one of them bit for bit what the same
+    call gives alone."""
+    wl = W.small_variant("video_qa", 3)
+    wl2 = W.video_qa(5, B=6, vis_len=9000, n_templates=2, tmpl_len=60, ext_lo=4, ext_hi=9, n_cached=300, len_lo=200,
+                     len_hi=9500, Hq=16, Hkv=2, num_slots=32768)
+    sides = [GpuSide(w, gpu_device) for w in (wl, wl2)]
+    want = [g.match() for g in sides]
+    torch.cuda.synchronize()
+    assert int(want[1][0].max()) > 8192          # (prompts that reach into a third window)
+    streams = [torch.cuda.Stream() for _ in range(8)]
+    got = []
+    for rep in range(12):
+        for k, st in enumerate(streams):
+            g = sides[(rep + k) % 2]
+            pl = torch.full_like(want[(rep + k) % 2][0], -7)
+            si = torch.full_like(want[(rep + k) % 2][1], -7)
+            pa.match_prefixes(g.tree, g.tokens, g.offsets, pl, si, stream=st)
+            got.append(((rep + k) % 2, pl, si))
+    for st in streams:
+        st.synchronize()
+    torch.cuda.synchronize()
+    for which, pl, si in got:
+        w, (pl_w, si_w) = sides[which].wl, want[which]
+        assert torch.equal(pl, pl_w)
+        for r in range(w.B):
+            lo, P = int(w.offsets[r]), int(pl_w[r])
+            assert torch.equal(si[lo:lo + P], si_w[lo:lo + P])
+
+
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_extend_packs_leftover_rows_of_requests_with_a_common_prefix(pa, gpu_device, seed):
     """Requests that share a prefix of 512 keys or more have the rows past their last full 128-row tile laid end to
