@@ -35,9 +35,9 @@ FP8_POOL_CONFIGS = ["long_doc_qa"]   # measured once more with the KV pool held 
 # run cannot share a process with the timed one): FETCH_SIZE x the factor that the same counter shows for append_kv, a
 # plain copy of known size, + WRITE_SIZE x its factor (KiB).  The runs are summarised in
 # profiles/extend_attention_<workload>.md, which is the source named beside each figure.  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"tool_use": 199_497_651, "agent_tree": 2_460_216_010, "long_doc_qa": 451_201_316,
+MEASURED_TRAFFIC_BYTES = {"tool_use": 199_497_651, "agent_tree": 2_460_216_010, "long_doc_qa": 451_358_556,
                           "video_qa": 346_810_464, "programming": 231_169_958, "decode": 300_863_715,
-                          "long_doc_qa_fp8_pool": 294_335_523}
+                          "long_doc_qa_fp8_pool": 294_184_352}
 
 
 def algorithmic_work(wl, prefix_len):

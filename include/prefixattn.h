@@ -281,9 +281,10 @@ size_t pa_extend_workspace_bytes(int B, int64_t T, int64_t max_kv_len, int Hq, i
  *                                unspecified (never read by pa_extend_attention).
  * The tree must have been uploaded after its last insert (else PA_ESTATE).  B = 0 is a
  * no-op.  Read-only on the tree: concurrent matches on different streams are safe.  (For
- * batches of up to 64 requests a prompt longer than 4,096 tokens is matched by several
- * workgroups, which meet in one of 64 small buffers of the library's own, taken in turn:
- * more than 64 such calls in flight at once on one device are not supported.) */
+ * batches of up to 64 requests, on a tree whose edges hold at most 4,096 tokens on average,
+ * a prompt longer than 4,096 tokens is matched by several workgroups, which meet in one of
+ * 64 small buffers of the library's own, taken in turn: more than 64 such calls in flight
+ * at once on one device are not supported.) */
 int pa_match_prefixes(const pa_tree* tree, const int32_t* tokens, const int32_t* offsets, int B,
                       int32_t* prefix_len, int32_t* slot_idx, void* stream);
 

@@ -58,6 +58,7 @@ struct DeviceTree {
     const int32_t* ht_val;
     uint32_t ht_mask;
     int32_t n_nodes;
+    int32_t n_tokens;  // edge tokens of all nodes together (as of the upload)
     // Second index, by position: a node is also reachable through the hash of the whole token path from
     // the root up to and including the FIRST token of its edge, together with the depth of that token.
     // A prompt can therefore look up every node boundary on its path at once from its own prefix hashes.

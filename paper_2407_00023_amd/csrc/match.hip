@@ -659,8 +659,12 @@ extern "C" int pa_match_prefixes(const pa_tree* tree, const int32_t* tokens, con
     if (B == 0) return PA_OK;
     PA_REQUIRE(offsets && prefix_len, "pa_match_prefixes: offsets or prefix_len is NULL");
     // tokens / slot_idx may be NULL only if every prompt is empty (offsets[B] == 0), which the host cannot see
+    // Several workgroups per request pay where a prompt's path has nodes in most of its windows.  Where the tree's edges
+    // are longer than a window on average (a few long documents), a walk crosses whole windows inside one edge, compared
+    // in one go by the workgroup that got there, and the others' work would only be waited for: one workgroup then.
+    const bool multi = B <= pa::kMultiMaxB && static_cast<int64_t>(view->n_tokens) <= 4096ll * (view->n_nodes > 1 ? view->n_nodes - 1 : 1);
     pa::MatchScratch* scratch = nullptr;
-    if (B <= pa::kMultiMaxB) {
+    if (multi) {
         if ((rc = match_scratch_of_current_device(&scratch)) != PA_OK) return rc;
         scratch += g_ms_next.fetch_add(1) % pa::kScratchSets;
     }
@@ -668,7 +672,7 @@ extern "C" int pa_match_prefixes(const pa_tree* tree, const int32_t* tokens, con
         pa::ProfScope prof(pa::kProfMatch, static_cast<hipStream_t>(stream));
         // Small batches: several workgroups per request.  Up to 256 requests: windows of 4,096 positions (every workgroup
         // has a compute unit of its own anyway).  Above: windows of 2,048, two workgroups per unit.
-        if (B <= pa::kMultiMaxB)
+        if (multi)
             hipLaunchKernelGGL((pa::match_prefixes_pos_kernel<4, true>), dim3(B * pa::kMaxW), dim3(pa::kWin), 0,
                                static_cast<hipStream_t>(stream), *view, tokens, offsets, prefix_len, slot_idx, scratch);
         else if (B <= 256)

@@ -790,6 +790,7 @@ extern "C" int pa_tree_upload(pa_tree* tree, void* stream_) {
             tree->xfer_pending[x] = true;
         }
         tree->view.n_nodes = static_cast<int32_t>(nn);
+        tree->view.n_tokens = static_cast<int32_t>(tree->n_tokens);
         tree->uploaded = true;
         ++tree->n_incremental_uploads;
         tree->last_upload_bytes = static_cast<int64_t>(bytes);
@@ -918,6 +919,7 @@ extern "C" int pa_tree_upload(pa_tree* tree, void* stream_) {
     tree->view.node_endhash = reinterpret_cast<const unsigned long long*>(b + f.o_end);
     tree->view.ph_mask = static_cast<uint32_t>(cap - 1);
     tree->view.n_nodes = static_cast<int32_t>(nn);
+    tree->view.n_tokens = static_cast<int32_t>(ntok);
     tree->uploaded = true;
     tree->mirror_ok = tree->incremental;
     tree->arena_end = cursor;

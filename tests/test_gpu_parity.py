@@ -147,6 +147,67 @@ def test_match_long_paths_of_mixed_edge_lengths(pa, gpu_device, seed, copies, tr
         np.testing.assert_array_equal(si[off[r]:off[r] + pl_ref[r]], si_ref[off[r]:off[r] + pl_ref[r]])
 
 
+@pytest.mark.parametrize("seed", [0, 1])
+def test_match_long_edges_in_a_tree_of_short_ones(pa, gpu_device, seed):
+    """Edges of 10,000 to 18,000 tokens, three or four matcher windows long, in a tree whose edges are short on
+    average - so that small batches get several workgroups per prompt (a tree of long edges only gets one) and the
+    walks cross whole windows inside one edge: prompts that end at and next to window boundaries, inside the long
+    edges, at their ends and in the branches that leave them; bit-exact vs the oracle trie."""
+    import oracle
+    rng = np.random.default_rng(300 + seed)
+    vocab = 60000
+    cached, nslot = [], 0
+
+    def add(seq):
+        nonlocal nslot
+        cached.append((np.asarray(seq, np.int32), np.arange(nslot, nslot + len(seq), dtype=np.int32)))
+        nslot += len(seq)
+
+    docs = [rng.integers(0, vocab, int(n)).astype(np.int32) for n in (18000, 12500, 10000)]
+    for d in docs:
+        add(d)
+    for _ in range(4):  # branches that leave a document inside its edge
+        d = docs[int(rng.integers(0, 3))]
+        cut = int(rng.integers(1, len(d)))
+        tail = rng.integers(0, vocab, int(rng.integers(5, 400))).astype(np.int32)
+        tail[0] = (d[cut] + 1) % vocab
+        add(np.concatenate([d[:cut], tail]))
+    firsts = set(int(d[0]) for d in docs)
+    for _ in range(300):  # many short sequences
+        seq = rng.integers(0, vocab, int(rng.integers(3, 20))).astype(np.int32)
+        while int(seq[0]) in firsts:
+            seq[0] = rng.integers(0, vocab)
+        add(seq)
+    prompts = []
+    for d in docs:
+        for cut in (len(d), 4096, 4095, 4097, 8192, 8191, 8193, 12288, 1, int(rng.integers(1, len(d)))):
+            cut = min(cut, len(d))
+            prompts.append(np.concatenate([d[:cut], rng.integers(0, vocab, int(rng.integers(0, 40))).astype(np.int32)]))
+    for c in cached[3:7]:
+        prompts.append(np.concatenate([c[0], rng.integers(0, vocab, 9).astype(np.int32)]))
+        prompts.append(c[0][: len(c[0]) - 2].copy())
+    for _ in range(64 - len(prompts)):
+        c = cached[int(rng.integers(0, len(cached)))][0]
+        prompts.append(np.concatenate([c[: int(rng.integers(0, len(c) + 1))], rng.integers(0, vocab, 3).astype(np.int32)]))
+    assert len(prompts) == 64
+    toks = np.concatenate(prompts).astype(np.int32)
+    off = np.zeros(len(prompts) + 1, np.int32)
+    off[1:] = np.cumsum([len(p) for p in prompts])
+    pl_ref, si_ref = oracle.match_prefixes(cached, toks, off)
+    assert pl_ref.max() == 18000
+    tree = pa.Tree()
+    for c in cached:
+        tree.insert(*c)
+    n_nodes, n_tokens = tree.stats()
+    assert n_tokens <= 4096 * (n_nodes - 1)  # (short edges on average: the several-workgroup form)
+    tree.upload()
+    pl, si = pa.match_prefixes(tree, torch.from_numpy(toks).to(gpu_device), torch.from_numpy(off).to(gpu_device))
+    pl, si = pl.cpu().numpy(), si.cpu().numpy()
+    np.testing.assert_array_equal(pl, pl_ref)
+    for r in range(len(prompts)):
+        np.testing.assert_array_equal(si[off[r]:off[r] + pl_ref[r]], si_ref[off[r]:off[r] + pl_ref[r]])
+
+
 def test_match_empty_tree_and_empty_batch(pa, gpu_device):
     tree = pa.Tree()
     tree.upload()
@@ -689,12 +750,12 @@ def test_match_calls_in_flight_on_several_streams(pa, gpu_device):
     streams = [torch.cuda.Stream() for _ in range(8)]
     got = []
     for rep in range(12):
-        for k, st in enumerate(streams):
-            g = sides[(rep + k) % 2]
-            pl = torch.full_like(want[(rep + k) % 2][0], -7)
-            si = torch.full_like(want[(rep + k) % 2][1], -7)
-            pa.match_prefixes(g.tree, g.tokens, g.offsets, pl, si, stream=st)
-            got.append(((rep + k) % 2, pl, si))
+        for k in range(len(streams)):
+            got.append(((rep + k) % 2, torch.full_like(want[(rep + k) % 2][0], -7), torch.full_like(want[(rep + k) % 2][1], -7)))
+    torch.cuda.synchronize()  # (the outputs are filled on the current stream: done before any match on another one starts)
+    for i, (which, pl, si) in enumerate(got):
+        g = sides[which]
+        pa.match_prefixes(g.tree, g.tokens, g.offsets, pl, si, stream=streams[i % len(streams)])
     for st in streams:
         st.synchronize()
     torch.cuda.synchronize()
